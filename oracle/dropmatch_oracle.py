@@ -1,0 +1,305 @@
+"""CPU oracle for the DropMatch Monte-Carlo-dropout LM-head verification step.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain definition that the HIP
+path is checked against.  Only the test-suite, the smoke check and the benchmark's
+`cpu_baseline` leg may import it; the product path never does, and this module
+imports nothing from the product package.  Everything here is numpy in float64 and
+Python integers; nothing is blocked, fused or reordered beyond what the method
+states, so each function can be read against the paper by eye.
+
+What the paper fixes (Methodology, "Multi-Sample LM Head via MC Dropout" and
+"Acceptance Criteria"):
+
+  Eq. (1)  m_j^(i) ~ Bernoulli(1 - p_drop), i.i.d. over j = 1..d, one mask per path i
+  Eq. (2)  h_t^(i) = h_t * m^(i) / (1 - p_drop)          (inverted-dropout scaling)
+  Eq. (3)  l_t^(i) = W h_t^(i)                           (shared LM-head weight W[V,d])
+  y_t^(i) = argmax_v l_t^(i)[v]                          (token of path i; softmax is monotone)
+  Eq. (4)  naive token matching: accept iff draft token is in {y_t^(i)}
+  Eq. (7)  majority rule: accept iff majority({y_t^(i)}) equals the draft token
+  a rejected position rejects every later one; the count of accepted draft
+  tokens is the acceptance length (Metrics paragraph, "Mean Acceptance Length").
+
+What the paper leaves open and this oracle decides (each decision is a reading,
+listed with its reason in the design notes of the repository):
+
+  * the random source: Philox4x32-10 (Salmon et al., SC'11), counter
+    (j >> 2, t, i, step), key = the sequence's 64-bit seed (low word, high word);
+    dimension j takes output word j & 3; keep iff word >= floor(p * 2^32),
+    p being the float32 the caller passes, widened exactly to float64;
+  * a fresh mask per (path, position) unless `share_mask_across_pos` (then t := 0);
+  * argmax ties -> smallest vocabulary index;  majority = plurality (mode) of the K
+    tokens (the paper's agreement table lists majority sizes 1..5 for K = 5),
+    ties between modes -> smallest token id;
+  * draft id < 0 means "no draft token at this row" and never matches;
+  * tree verification: parent[n] < n, node 0 is the root (always accepted); node n
+    is accepted iff its parent is accepted and the rule holds for draft[n] against
+    the K path tokens of row parent[n]; result = depth of the deepest accepted node.
+
+Pins (tests/test_oracle_*.py, all CPU): Philox known-answer vectors and an
+independent big-integer implementation; exact integer thresholds by rational
+arithmetic; keep-rate and E[h^(i)] = h statistics; p = 0 reducing to plain greedy
+verification through a separate library matmul; hand-checkable integer cases by
+brute force in exact rational arithmetic; identical masks -> identical paths;
+rule set-relations; chain/tree equivalence; batch independence.
+Parity unpinned: nothing in this file.  (Task quality on real text - accuracy,
+acceptance length on benchmarks - is not computed here at all.)
+"""
+from __future__ import annotations
+
+import numpy as np
+
+RULE_ANY = 0       # Eq. (4): draft token is one of the K path tokens
+RULE_MAJORITY = 1  # Eq. (7): draft token is the most frequent path token
+
+_PHILOX_M0 = np.uint64(0xD2511F53)
+_PHILOX_M1 = np.uint64(0xCD9E8D57)
+_PHILOX_W0 = 0x9E3779B9
+_PHILOX_W1 = 0xBB67AE85
+_LO32 = np.uint64(0xFFFFFFFF)
+_SH32 = np.uint64(32)
+
+
+# --------------------------------------------------------------------------- #
+# Random source (reading of Eq. (1): the paper only says "i.i.d. Bernoulli")
+# --------------------------------------------------------------------------- #
+def philox4x32_10(c0, c1, c2, c3, k0, k1):
+    """Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random
+    numbers: as easy as 1, 2, 3", SC'11).  All arguments broadcast; each holds
+    32-bit words.  Returns four uint32 arrays.
+
+    One round maps (c0,c1,c2,c3) to (hi(M1*c2)^c1^k0, lo(M1*c2), hi(M0*c0)^c3^k1,
+    lo(M0*c0)); the key is bumped by the Weyl constants between rounds.
+    """
+    c0, c1, c2, c3, k0, k1 = np.broadcast_arrays(
+        *(np.asarray(x, dtype=np.uint64) & _LO32 for x in (c0, c1, c2, c3, k0, k1)))
+    for r in range(10):
+        p0 = _PHILOX_M0 * c0          # < 2^64, exact in uint64
+        p1 = _PHILOX_M1 * c2
+        kk0 = (k0 + np.uint64((_PHILOX_W0 * r) & 0xFFFFFFFF)) & _LO32
+        kk1 = (k1 + np.uint64((_PHILOX_W1 * r) & 0xFFFFFFFF)) & _LO32
+        n0 = (p1 >> _SH32) ^ c1 ^ kk0
+        n1 = p1 & _LO32
+        n2 = (p0 >> _SH32) ^ c3 ^ kk1
+        n3 = p0 & _LO32
+        c0, c1, c2, c3 = n0, n1, n2, n3
+    return tuple(x.astype(np.uint32) for x in (c0, c1, c2, c3))
+
+
+def drop_threshold(p) -> int:
+    """Integer t such that a uniform 32-bit word u is DROPPED iff u < t.
+
+    t = floor(p * 2^32) with p the float32 value widened to float64 (exact: a
+    float32 times 2^32 is representable).  P(keep) = 1 - t / 2^32.
+    """
+    p64 = float(np.float32(p))
+    if not (0.0 <= p64 < 1.0):
+        raise ValueError("p_drop must satisfy 0 <= p < 1")
+    return int(np.floor(p64 * 4294967296.0))
+
+
+def keep_mask(seed: int, step: int, t: int, i: int, d: int, p) -> np.ndarray:
+    """Eq. (1): keep-mask m^(i) in {0,1}^d of path i at row t, as bool[d]."""
+    seed = int(seed) & 0xFFFFFFFFFFFFFFFF
+    nctr = (d + 3) // 4                      # counter c serves dimensions 4c .. 4c+3
+    words = philox4x32_10(np.arange(nctr, dtype=np.uint64), t, i, step,
+                          seed & 0xFFFFFFFF, seed >> 32)
+    u = np.stack(words, axis=1).reshape(-1)[:d]          # u[j] = word (j & 3) of counter j >> 2
+    return u.astype(np.uint64) >= np.uint64(drop_threshold(p))
+
+
+def keep_masks(seed: int, step: int, T: int, K: int, d: int, p,
+               share_mask_across_pos: bool = False) -> np.ndarray:
+    """All masks of one sequence, bool[T, K, d].  With `share_mask_across_pos`
+    path i uses one mask at every row (position word of the counter forced to 0)."""
+    out = np.empty((T, K, d), dtype=bool)
+    for t in range(T):
+        for i in range(K):
+            out[t, i] = keep_mask(seed, step, 0 if share_mask_across_pos else t, i, d, p)
+    return out
+
+
+def pack_mask_bits(keep: np.ndarray) -> np.ndarray:
+    """Bit-pack bool[..., d] to uint32[..., ceil(d/32)]: word w holds dimensions
+    32w .. 32w+31, bit (j & 31) is keep(j); bits past d are zero."""
+    d = keep.shape[-1]
+    nw = (d + 31) // 32
+    padded = np.zeros(keep.shape[:-1] + (nw * 32,), dtype=np.uint64)
+    padded[..., :d] = keep
+    weights = np.uint64(1) << np.arange(32, dtype=np.uint64)
+    return (padded.reshape(keep.shape[:-1] + (nw, 32)) * weights).sum(axis=-1).astype(np.uint32)
+
+
+# --------------------------------------------------------------------------- #
+# Eq. (2), Eq. (3), path token
+# --------------------------------------------------------------------------- #
+def masked_state(h_t: np.ndarray, keep: np.ndarray, p) -> np.ndarray:
+    """Eq. (2): h_t^(i) = h_t * m^(i) / (1 - p_drop), float64."""
+    p64 = float(np.float32(p))
+    return np.asarray(h_t, dtype=np.float64) * keep.astype(np.float64) / (1.0 - p64)
+
+
+def path_logits(W: np.ndarray, h_t: np.ndarray, keep: np.ndarray, p) -> np.ndarray:
+    """Eq. (3): l_t^(i) = W h_t^(i), float64[V]."""
+    return np.asarray(W, dtype=np.float64) @ masked_state(h_t, keep, p)
+
+
+def path_token(logits: np.ndarray):
+    """y = argmax_v l[v], ties -> smallest v.  Also returns top1 - top2 (inf if V == 1)."""
+    y = int(np.argmax(logits))            # numpy returns the first maximal index
+    if logits.shape[0] < 2:
+        return y, float("inf")
+    top2 = np.partition(logits, -2)[-2:]
+    return y, float(top2[1] - top2[0])
+
+
+# --------------------------------------------------------------------------- #
+# Eq. (4), Eq. (7), prefix / tree acceptance
+# --------------------------------------------------------------------------- #
+def vote(ids):
+    """Mode of the K path tokens (Eq. (7), "majority"): returns (token, count);
+    among equally frequent tokens the smallest id wins."""
+    counts = {}
+    for y in ids:
+        counts[int(y)] = counts.get(int(y), 0) + 1
+    best = max(counts.values())
+    return min(tok for tok, c in counts.items() if c == best), best
+
+
+def rule_hit(draft: int, ids, rule: int) -> bool:
+    """Acceptance test of one draft token against the K path tokens of one row."""
+    draft = int(draft)
+    if draft < 0:
+        return False
+    if rule == RULE_ANY:                       # Eq. (4)
+        return any(int(y) == draft for y in ids)
+    if rule == RULE_MAJORITY:                  # Eq. (7)
+        return vote(ids)[0] == draft
+    raise ValueError("unknown rule")
+
+
+def accept_chain(hit):
+    """Prefix rule: the first rejected row rejects all later ones.
+    Returns (accept_len, best_node, accept_mask)."""
+    T = len(hit)
+    mask = np.zeros(T, dtype=np.uint8)
+    n = 0
+    while n < T and hit[n]:
+        mask[n] = 1
+        n += 1
+    return n, n - 1, mask
+
+
+def accept_tree(edge_hit, parent):
+    """Tree of draft candidates in topological order (parent[n] < n, parent[0] = -1).
+    Node 0 is accepted; node n > 0 is accepted iff its parent is and edge_hit[n].
+    Returns (max accepted depth, that node - smallest index on ties, accept_mask)."""
+    T = len(parent)
+    acc = np.zeros(T, dtype=np.uint8)
+    depth = np.zeros(T, dtype=np.int64)
+    acc[0] = 1
+    best_depth, best = 0, 0
+    for n in range(1, T):
+        q = int(parent[n])
+        if not (0 <= q < n):
+            raise ValueError("parent[] is not a topological order rooted at node 0")
+        depth[n] = depth[q] + 1
+        acc[n] = 1 if (acc[q] and edge_hit[n]) else 0
+        if acc[n] and depth[n] > best_depth:
+            best_depth, best = int(depth[n]), n
+    return best_depth, best, acc
+
+
+# --------------------------------------------------------------------------- #
+# The whole step
+# --------------------------------------------------------------------------- #
+def verify(h, W, draft_ids, seeds, K: int, p, step: int = 0, rule: int = RULE_ANY,
+           share_mask_across_pos: bool = False, parent=None, want_logits=None):
+    """One DropMatch verification step for B sequences.
+
+    h          [B, T, d]  final hidden states (any float dtype; used as float64)
+    W          [V, d]     LM-head weight
+    draft_ids  [B, T]     chain: token verified by row t;  tree: token of node t
+    seeds      [B]        64-bit mask seed per sequence
+    parent     None (chain) or [B, T] (tree)
+    want_logits optional (v0, v1): also return logits[B*T*K, v1-v0] for parity of values
+
+    Returns a dict of numpy arrays: path_ids[B,T,K], gap[B,T,K] (top-1 minus top-2
+    logit of each path), vote_ids[B,T], vote_cnt[B,T], hit[B,T], accept_mask[B,T],
+    accept_len[B], best_node[B] (and logits if asked).
+    """
+    h = np.asarray(h, dtype=np.float64)
+    W64 = np.asarray(W, dtype=np.float64)
+    draft_ids = np.asarray(draft_ids)
+    B, T, d = h.shape
+    V = W64.shape[0]
+    if W64.shape[1] != d or draft_ids.shape != (B, T) or len(seeds) != B or K < 1:
+        raise ValueError("shape mismatch")
+
+    path_ids = np.zeros((B, T, K), dtype=np.int32)
+    gap = np.zeros((B, T, K), dtype=np.float64)
+    logits_out = None
+    if want_logits is not None:
+        v0, v1 = want_logits
+        logits_out = np.zeros((B * T * K, v1 - v0), dtype=np.float64)
+
+    for b in range(B):
+        for t in range(T):
+            tt = 0 if share_mask_across_pos else t
+            # K masked states of this row, Eq. (1)-(2)
+            Hm = np.stack([masked_state(h[b, t], keep_mask(seeds[b], step, tt, i, d, p), p)
+                           for i in range(K)], axis=0)          # [K, d]
+            L = W64 @ Hm.T                                       # Eq. (3), [V, K]
+            for i in range(K):
+                path_ids[b, t, i], gap[b, t, i] = path_token(L[:, i])
+                if logits_out is not None:
+                    logits_out[(b * T + t) * K + i] = L[v0:v1, i]
+
+    out = acceptance_from_path_ids(path_ids, draft_ids, rule, parent)
+    out["path_ids"] = path_ids
+    out["gap"] = gap
+    if logits_out is not None:
+        out["logits"] = logits_out
+    return out
+
+
+def acceptance_from_path_ids(path_ids, draft_ids, rule: int = RULE_ANY, parent=None):
+    """Eq. (4)/(7) and the prefix (or tree) rule applied to given path tokens.
+    Split out so that acceptance can also be re-derived from another set of path
+    tokens (used when a near-tie legitimately flips a path token)."""
+    path_ids = np.asarray(path_ids)
+    draft_ids = np.asarray(draft_ids)
+    B, T, K = path_ids.shape
+    vote_ids = np.zeros((B, T), dtype=np.int32)
+    vote_cnt = np.zeros((B, T), dtype=np.int32)
+    hit = np.zeros((B, T), dtype=np.uint8)
+    accept_mask = np.zeros((B, T), dtype=np.uint8)
+    accept_len = np.zeros(B, dtype=np.int32)
+    best_node = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        for t in range(T):
+            vote_ids[b, t], vote_cnt[b, t] = vote(path_ids[b, t])
+        if parent is None:
+            for t in range(T):
+                hit[b, t] = rule_hit(draft_ids[b, t], path_ids[b, t], rule)
+            accept_len[b], best_node[b], accept_mask[b] = accept_chain(hit[b])
+        else:
+            par = np.asarray(parent)[b]
+            hit[b, 0] = 1
+            for n in range(1, T):
+                hit[b, n] = rule_hit(draft_ids[b, n], path_ids[b, int(par[n])], rule)
+            accept_len[b], best_node[b], accept_mask[b] = accept_tree(hit[b], par)
+    return dict(vote_ids=vote_ids, vote_cnt=vote_cnt, hit=hit, accept_mask=accept_mask,
+                accept_len=accept_len, best_node=best_node)
+
+
+def greedy_ids(h, W):
+    """Plain LM head without dropout: argmax_v (W h_t)[v] per row, int32[B, T].
+    (The p = 0 special case of the step; also used to plant draft tokens.)"""
+    h = np.asarray(h, dtype=np.float64)
+    W64 = np.asarray(W, dtype=np.float64)
+    B, T, d = h.shape
+    out = np.zeros((B, T), dtype=np.int32)
+    for b in range(B):
+        for t in range(T):
+            out[b, t] = path_token(W64 @ h[b, t])[0]
+    return out

@@ -1,0 +1,420 @@
+"""Pins for the CPU oracle: every check compares it with something that is NOT the
+oracle - published known-answer vectors, exact rational arithmetic written out here
+with Python integers, closed forms, special cases that reduce to a library routine,
+or invariants the method's definitions (Eq. (1)-(4), (7), prefix rule) impose."""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import dropmatch_oracle as orc
+from paper_2603_03333_amd import workloads as wk
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---- an independent Philox4x32-10 in plain Python integers ------------------ #
+def philox_int(ctr, key):
+    c0, c1, c2, c3 = ctr
+    k0, k1 = key
+    for _ in range(10):
+        p0 = 0xD2511F53 * c0
+        p1 = 0xCD9E8D57 * c2
+        c0, c1, c2, c3 = ((p1 >> 32) ^ c1 ^ k0) & 0xFFFFFFFF, p1 & 0xFFFFFFFF, \
+                         ((p0 >> 32) ^ c3 ^ k1) & 0xFFFFFFFF, p0 & 0xFFFFFFFF
+        k0 = (k0 + 0x9E3779B9) & 0xFFFFFFFF
+        k1 = (k1 + 0xBB67AE85) & 0xFFFFFFFF
+    return c0, c1, c2, c3
+
+
+def keep_int(seed, step, t, i, j, p):
+    """Eq. (1) with this build's counter layout, in exact integer arithmetic."""
+    thr = int(Fraction(float(np.float32(p))) * 2 ** 32)
+    word = philox_int((j >> 2, t, i, step), (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF))[j & 3]
+    return word >= thr
+
+
+def _read_rows(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+# ---- random source ----------------------------------------------------------- #
+def test_philox_known_answers():
+    rows = _read_rows("philox4x32_10_kat.txt")
+    assert len(rows) == 3
+    for r in rows:
+        v = [int(x, 16) for x in r]
+        got = orc.philox4x32_10(*v[:6])
+        assert [int(g) for g in got] == v[6:]
+        assert list(philox_int(v[:4], v[4:6])) == v[6:]      # the test's own generator too
+
+
+def test_philox_matches_integer_implementation():
+    rng = np.random.default_rng(1)
+    args = rng.integers(0, 2 ** 32, size=(6, 500), dtype=np.uint64)
+    got = np.stack(orc.philox4x32_10(*args), axis=1)
+    for n in range(args.shape[1]):
+        a = [int(x) for x in args[:, n]]
+        assert tuple(int(x) for x in got[n]) == philox_int(a[:4], a[4:])
+
+
+def test_drop_thresholds_exact():
+    for p, t in _read_rows("drop_thresholds.txt"):
+        assert orc.drop_threshold(float(p)) == int(t)
+        assert int(Fraction(float(np.float32(float(p)))) * 2 ** 32) == int(t)
+    for bad in (-0.1, 1.0, 1.5):
+        with pytest.raises(ValueError):
+            orc.drop_threshold(bad)
+
+
+@pytest.mark.parametrize("seed,step,t,i,d,p", [
+    (0, 0, 0, 0, 64, 0.1), (12345678901234567, 3, 4, 7, 37, 0.3), (2 ** 64 - 1, 2 ** 32 - 1, 63, 31, 130, 0.5),
+])
+def test_mask_counter_layout(seed, step, t, i, d, p):
+    got = orc.keep_mask(seed, step, t, i, d, p)
+    want = [keep_int(seed, step, t, i, j, p) for j in range(d)]
+    assert got.tolist() == want
+
+
+def test_masks_differ_by_every_key_component():
+    base = orc.keep_mask(5, 0, 1, 2, 4096, 0.3)
+    for other in (orc.keep_mask(6, 0, 1, 2, 4096, 0.3), orc.keep_mask(5 + 2 ** 32, 0, 1, 2, 4096, 0.3),
+                  orc.keep_mask(5, 1, 1, 2, 4096, 0.3), orc.keep_mask(5, 0, 2, 2, 4096, 0.3),
+                  orc.keep_mask(5, 0, 1, 3, 4096, 0.3)):
+        frac_equal = np.mean(base == other)
+        # independent Bernoulli(0.7) masks agree with probability 0.7^2 + 0.3^2 = 0.58
+        assert abs(frac_equal - 0.58) < 0.04
+
+
+def test_p_zero_keeps_everything():
+    assert orc.keep_masks(9, 0, 3, 4, 100, 0.0).all()
+
+
+@pytest.mark.parametrize("p", [0.05, 0.1, 0.3, 0.5])
+def test_keep_rate_is_one_minus_p(p):
+    m = orc.keep_masks(seed=42, step=0, T=4, K=16, d=4096, p=p)
+    n = m.size
+    assert abs(m.mean() - (1 - p)) < 4 * np.sqrt(p * (1 - p) / n)
+    # flat marginals: per path and per 256-wide slab of dimensions
+    per_path = m.mean(axis=(0, 2))
+    assert np.all(np.abs(per_path - (1 - p)) < 5 * np.sqrt(p * (1 - p) / (4 * 4096)))
+    per_slab = m.reshape(4, 16, 16, 256).mean(axis=(0, 1, 3))
+    assert np.all(np.abs(per_slab - (1 - p)) < 5 * np.sqrt(p * (1 - p) / (64 * 256)))
+
+
+def test_share_mask_across_positions():
+    m = orc.keep_masks(3, 0, 4, 3, 96, 0.3, share_mask_across_pos=True)
+    assert (m == m[0:1]).all()
+    assert (m[0] == orc.keep_masks(3, 0, 1, 3, 96, 0.3)[0]).all()
+    assert not (orc.keep_masks(3, 0, 4, 3, 96, 0.3)[1] == m[0]).all()
+
+
+def test_pack_mask_bits_layout():
+    d = 70
+    keep = np.array([(j % 3 == 0) or j == 69 for j in range(d)])
+    words = orc.pack_mask_bits(keep)
+    want = [sum(1 << (j - 32 * w) for j in range(32 * w, min(d, 32 * w + 32)) if keep[j]) for w in range(3)]
+    assert words.dtype == np.uint32 and words.tolist() == want
+    assert orc.pack_mask_bits(np.ones((2, 3, 33), dtype=bool)).tolist() == [[[0xFFFFFFFF, 1]] * 3] * 2
+
+
+# ---- Eq. (2), Eq. (3), path token --------------------------------------------- #
+def test_inverted_dropout_scale_hand_values():
+    # Eq. (2) with p = 0.25: kept entries are multiplied by 4/3, dropped ones are 0
+    out = orc.masked_state(np.array([3.0, -6.0, 9.0]), np.array([True, False, True]), 0.25)
+    assert out.tolist() == [4.0, 0.0, 12.0]
+    assert orc.masked_state(np.array([3.0, -6.0]), np.array([True, True]), 0.5).tolist() == [6.0, -12.0]
+    assert orc.masked_state(np.array([3.0, -6.0]), np.array([True, False]), 0.0).tolist() == [3.0, 0.0]
+
+
+def test_masked_state_preserves_expectation():
+    # the property the paper states below Eq. (2): E[h^(i)] = h
+    rng = np.random.default_rng(0)
+    d, n, p = 64, 4096, 0.1
+    h = rng.standard_normal(d)
+    acc = np.zeros(d)
+    for i in range(n):
+        acc += orc.masked_state(h, orc.keep_mask(77, 0, 0, i, d, p), p)
+    err = np.abs(acc / n - h)
+    assert np.all(err <= 5 * np.abs(h) * np.sqrt(p / ((1 - p) * n)) + 1e-12)
+
+
+def test_logits_hand_values():
+    # Eq. (3), W is [V, d] = 3 x 2 (not square, so a transposed operand cannot pass)
+    W = np.array([[1.0, 2.0], [3.0, 4.0], [-1.0, 0.0]])
+    h = np.array([3.0, -6.0])
+    l = orc.path_logits(W, h, np.array([True, True]), 0.25)       # h' = [4, -8]
+    assert l.tolist() == [-12.0, -20.0, -4.0]
+    assert orc.path_token(l) == (2, 8.0)
+    l = orc.path_logits(W, h, np.array([True, False]), 0.25)      # h' = [4, 0]
+    assert l.tolist() == [4.0, 12.0, -4.0]
+    assert orc.path_token(l) == (1, 8.0)
+
+
+def test_path_token_ties_and_gap():
+    assert orc.path_token(np.array([1.0, 5.0, 5.0, 2.0])) == (1, 0.0)
+    assert orc.path_token(np.array([1.0, 5.0, 3.0])) == (1, 2.0)
+    assert orc.path_token(np.array([-3.0])) == (0, float("inf"))
+
+
+# ---- Eq. (4), Eq. (7), prefix rule, trees -------------------------------------- #
+def test_vote_hand_cases():
+    assert orc.vote([7, 3, 7, 3, 1]) == (3, 2)        # two modes: smallest id
+    assert orc.vote([5]) == (5, 1)
+    assert orc.vote([2, 2, 2]) == (2, 3)
+    assert orc.vote([9, 4, 4, 9, 9]) == (9, 3)
+    assert orc.vote([8, 6, 4, 2, 0]) == (0, 1)        # majority size 1 is still a majority (plurality)
+
+
+def test_rule_hand_cases():
+    ids = [7, 3, 7, 3, 1]
+    assert orc.rule_hit(1, ids, orc.RULE_ANY) and not orc.rule_hit(1, ids, orc.RULE_MAJORITY)
+    assert orc.rule_hit(3, ids, orc.RULE_ANY) and orc.rule_hit(3, ids, orc.RULE_MAJORITY)
+    assert orc.rule_hit(7, ids, orc.RULE_ANY) and not orc.rule_hit(7, ids, orc.RULE_MAJORITY)
+    assert not orc.rule_hit(2, ids, orc.RULE_ANY) and not orc.rule_hit(2, ids, orc.RULE_MAJORITY)
+    assert not orc.rule_hit(-1, ids, orc.RULE_ANY) and not orc.rule_hit(-1, [-1], orc.RULE_ANY)
+
+
+def test_accept_chain_hand_cases():
+    n, best, mask = orc.accept_chain([1, 1, 0, 1])
+    assert (n, best, mask.tolist()) == (2, 1, [1, 1, 0, 0])
+    assert orc.accept_chain([0, 1, 1])[0] == 0 and orc.accept_chain([0, 1, 1])[1] == -1
+    assert orc.accept_chain([1, 1, 1])[0] == 3
+
+
+def test_accept_tree_hand_cases():
+    #        0
+    #      / | \
+    #     1  2  3
+    #    /|  |
+    #   4 5  6
+    #   |
+    #   7
+    parent = [-1, 0, 0, 0, 1, 1, 2, 4]
+    n, best, mask = orc.accept_tree([1, 1, 1, 1, 1, 1, 1, 1], parent)
+    assert (n, best, mask.tolist()) == (3, 7, [1] * 8)
+    n, best, mask = orc.accept_tree([1, 0, 1, 1, 1, 1, 1, 1], parent)     # edge to 1 fails: its subtree dies
+    assert (n, best, mask.tolist()) == (2, 6, [1, 0, 1, 1, 0, 0, 1, 0])
+    n, best, mask = orc.accept_tree([1, 1, 1, 0, 1, 1, 0, 0], parent)     # depth-2 tie between 4 and 5
+    assert (n, best, mask.tolist()) == (2, 4, [1, 1, 1, 0, 1, 1, 0, 0])
+    n, best, mask = orc.accept_tree([1, 0, 0, 0, 1, 1, 1, 1], parent)
+    assert (n, best, mask.tolist()) == (0, 0, [1, 0, 0, 0, 0, 0, 0, 0])
+    with pytest.raises(ValueError):
+        orc.accept_tree([1, 1, 1], [-1, 2, 0])
+
+
+# ---- the whole step against brute force in exact arithmetic -------------------- #
+def _brute_force(h, W, draft, seeds, K, p, step, rule, parent=None):
+    """Every quantity from the definitions, with Fractions and Python loops."""
+    B, T, d = h.shape
+    V = W.shape[0]
+    s = 1 / (1 - Fraction(float(np.float32(p))))
+    path = np.zeros((B, T, K), dtype=np.int64)
+    for b in range(B):
+        for t in range(T):
+            for i in range(K):
+                best, best_v = None, -1
+                for v in range(V):
+                    l = sum(Fraction(int(W[v, j])) * Fraction(int(h[b, t, j])) * s
+                            for j in range(d) if keep_int(int(seeds[b]), step, t, i, j, p))
+                    if best is None or l > best:
+                        best, best_v = l, v
+                path[b, t, i] = best_v
+    hit = np.zeros((B, T), dtype=np.int64)
+    acc_len = np.zeros(B, dtype=np.int64)
+    for b in range(B):
+        def rule_ok(g, ids):
+            ids = [int(x) for x in ids]
+            if g < 0:
+                return False
+            if rule == orc.RULE_ANY:
+                return g in ids
+            top = max(ids.count(x) for x in ids)
+            return g == min(x for x in ids if ids.count(x) == top)
+        if parent is None:
+            for t in range(T):
+                hit[b, t] = rule_ok(int(draft[b, t]), path[b, t])
+            n = 0
+            while n < T and hit[b, n]:
+                n += 1
+            acc_len[b] = n
+        else:
+            ok = [True] + [False] * (T - 1)
+            depth = [0] * T
+            for n in range(1, T):
+                q = int(parent[b, n])
+                depth[n] = depth[q] + 1
+                ok[n] = ok[q] and rule_ok(int(draft[b, n]), path[b, q])
+            acc_len[b] = max(depth[n] for n in range(T) if ok[n])
+    return path, hit, acc_len
+
+
+@pytest.mark.parametrize("rule", [orc.RULE_ANY, orc.RULE_MAJORITY])
+def test_verify_against_exact_brute_force(rule):
+    rng = np.random.default_rng(11)
+    B, T, d, V, K, p, step = 2, 4, 8, 11, 5, 0.25, 2
+    h = rng.integers(-4, 5, size=(B, T, d)).astype(np.float64)
+    W = rng.integers(-3, 4, size=(V, d)).astype(np.float64)
+    seeds = np.array([3, 2 ** 40 + 17], dtype=np.uint64)
+    ref_path, _, _ = _brute_force(h, W, np.zeros((B, T), int), seeds, K, p, step, rule)
+    draft = np.where(rng.random((B, T)) < 0.7, ref_path[:, :, 0], rng.integers(0, V, size=(B, T)))
+    ref_path, ref_hit, ref_len = _brute_force(h, W, draft, seeds, K, p, step, rule)
+    got = orc.verify(h, W, draft, seeds, K, p, step=step, rule=rule)
+    # integer inputs with p = 1/4: every logit is an exact multiple of 4/3 well inside 2^53,
+    # so float64 ordering equals rational ordering except through the rounding of 4/3,
+    # which scales all logits of a row alike and cannot reorder them.
+    assert got["path_ids"].tolist() == ref_path.tolist()
+    assert got["hit"].tolist() == ref_hit.tolist()
+    assert got["accept_len"].tolist() == ref_len.tolist()
+
+
+def test_verify_tree_against_exact_brute_force():
+    rng = np.random.default_rng(12)
+    B, T, d, V, K, p = 1, 7, 8, 9, 3, 0.5
+    h = rng.integers(-4, 5, size=(B, T, d)).astype(np.float64)
+    W = rng.integers(-3, 4, size=(V, d)).astype(np.float64)
+    seeds = np.array([99], dtype=np.uint64)
+    parent = np.array([[-1, 0, 0, 1, 1, 2, 3]])
+    path, _, _ = _brute_force(h, W, np.zeros((B, T), int), seeds, K, p, 0, orc.RULE_ANY)
+    draft = np.full((B, T), -1)
+    for n in range(1, T):
+        draft[0, n] = path[0, parent[0, n], n % K] if n != 2 else (path[0, 0, 0] + 1) % V
+    _, _, ref_len = _brute_force(h, W, draft, seeds, K, p, 0, orc.RULE_ANY, parent=parent)
+    got = orc.verify(h, W, draft, seeds, K, p, parent=parent)
+    assert got["accept_len"].tolist() == ref_len.tolist()
+    assert got["hit"][0, 0] == 1 and got["accept_mask"][0, 0] == 1
+
+
+# ---- fixed points the method implies -------------------------------------------- #
+def _small_problem(seed=0, B=2, T=6, d=96, V=257, dtype="f32"):
+    wl = wk.Workload("unit", d=d, V=V, dtype=dtype, B=B, T=T, K=6, p=0.3, data_seed=seed)
+    return wl, wk.make_weight(wl), wk.make_hidden(wl), wk.make_seeds(wl, 5)
+
+
+def test_p_zero_is_plain_greedy_verification():
+    wl, W, h, seeds = _small_problem(1)
+    greedy = np.argmax(np.einsum("btd,vd->btv", h.astype(np.float64), W.astype(np.float64)), axis=-1)
+    assert orc.greedy_ids(h, W).tolist() == greedy.tolist()
+    draft = greedy.copy()
+    draft[0, 3] = (draft[0, 3] + 1) % wl.V          # first mismatch of sequence 0 at row 3
+    draft[1, 0] = (draft[1, 0] + 1) % wl.V          # sequence 1 fails at once
+    for rule in (orc.RULE_ANY, orc.RULE_MAJORITY):
+        out = orc.verify(h, W, draft, seeds, wl.K, 0.0, rule=rule)
+        assert (out["path_ids"] == greedy[:, :, None]).all()
+        assert (out["vote_cnt"] == wl.K).all() and (out["vote_ids"] == greedy).all()
+        assert out["accept_len"].tolist() == [3, 0]
+        assert out["best_node"].tolist() == [2, -1]
+
+
+def test_identical_masks_give_identical_paths():
+    wl, W, h, seeds = _small_problem(2)
+    h[:, :] = h[:, :1]                                # the same hidden state at every row
+    out = orc.verify(h, W, np.zeros((wl.B, wl.T), int), seeds, wl.K, wl.p, share_mask_across_pos=True)
+    assert (out["path_ids"] == out["path_ids"][:, :1]).all()
+    # two sequences with equal seed and equal h give equal results; different seeds do not
+    h[1] = h[0]
+    same = orc.verify(h, W, np.zeros((wl.B, wl.T), int), np.array([5, 5], dtype=np.uint64), wl.K, wl.p)
+    assert (same["path_ids"][0] == same["path_ids"][1]).all()
+    diff = orc.verify(h, W, np.zeros((wl.B, wl.T), int), np.array([5, 6], dtype=np.uint64), wl.K, wl.p)
+    assert not (diff["path_ids"][0] == diff["path_ids"][1]).all()
+
+
+def test_counter_based_paths_nest():
+    wl, W, h, seeds = _small_problem(3)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    small = orc.verify(h, W, draft, seeds, 4, wl.p)
+    large = orc.verify(h, W, draft, seeds, 9, wl.p)
+    assert (large["path_ids"][:, :, :4] == small["path_ids"]).all()
+    assert (large["accept_len"] >= small["accept_len"]).all()       # Eq. (4) can only gain members
+
+
+def test_rule_relations():
+    wl, W, h, seeds = _small_problem(4)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    a = orc.verify(h, W, draft, seeds, wl.K, wl.p, rule=orc.RULE_ANY)
+    m = orc.verify(h, W, draft, seeds, wl.K, wl.p, rule=orc.RULE_MAJORITY)
+    assert (a["path_ids"] == m["path_ids"]).all()
+    assert (a["hit"] >= m["hit"]).all() and (a["accept_len"] >= m["accept_len"]).all()
+    one_a = orc.verify(h, W, draft, seeds, 1, wl.p, rule=orc.RULE_ANY)
+    one_m = orc.verify(h, W, draft, seeds, 1, wl.p, rule=orc.RULE_MAJORITY)
+    assert (one_a["hit"] == one_m["hit"]).all()
+    # permuting the K paths changes nothing but the order of path_ids
+    perm = np.array([3, 0, 5, 1, 4, 2])
+    for rule, ref in ((orc.RULE_ANY, a), (orc.RULE_MAJORITY, m)):
+        p2 = orc.acceptance_from_path_ids(ref["path_ids"][:, :, perm], draft, rule)
+        for k in ("vote_ids", "vote_cnt", "hit", "accept_len", "accept_mask", "best_node"):
+            assert (p2[k] == ref[k]).all()
+    # a row without a draft token never hits
+    draft2 = draft.copy()
+    draft2[:, 2] = -1
+    cut = orc.verify(h, W, draft2, seeds, wl.K, wl.p)
+    assert (cut["hit"][:, 2] == 0).all() and (cut["accept_len"] <= 2).all()
+
+
+def test_chain_equals_degenerate_tree():
+    wl, W, h, seeds = _small_problem(5, B=3, T=7)
+    wl = wl.with_(bonus=True)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    assert (draft[:, -1] == -1).all()
+    chain = orc.verify(h, W, draft, seeds, wl.K, 0.05)
+    parent, tdraft = wk.chain_as_tree(draft)
+    tree = orc.verify(h, W, tdraft, seeds, wl.K, 0.05, parent=parent)
+    assert (chain["path_ids"] == tree["path_ids"]).all()
+    assert chain["accept_len"].tolist() == tree["accept_len"].tolist()
+    assert (tree["best_node"] == chain["accept_len"]).all()        # node index = depth on a path
+    assert chain["accept_len"].max() > 0
+
+
+def test_tree_planted_full_depth_and_all_wrong():
+    wl = wk.Workload("unit-tree", d=64, V=101, dtype="f32", B=2, T=20, K=4, p=0.1, tree=True, data_seed=6)
+    W, h, seeds = wk.make_weight(wl), wk.make_hidden(wl), wk.make_seeds(wl)
+    parent = wk.make_tree_parents(wl, max_depth=5, max_branch=3)
+    assert (parent[:, 0] == -1).all() and all((parent[b, 1:] < np.arange(1, wl.T)).all() for b in range(wl.B))
+    paths = orc.verify(h, W, np.zeros((wl.B, wl.T), int), seeds, wl.K, wl.p)["path_ids"]
+    # plant: every node carries path 0's token of its parent row -> everything is accepted
+    draft = np.full((wl.B, wl.T), -1)
+    for b in range(wl.B):
+        for n in range(1, wl.T):
+            draft[b, n] = paths[b, parent[b, n], 0]
+    out = orc.verify(h, W, draft, seeds, wl.K, wl.p, parent=parent)
+    assert out["accept_len"].tolist() == [5, 5] and (out["accept_mask"] == 1).all()
+    # all children wrong -> only the root
+    wrong = np.full((wl.B, wl.T), wl.V)             # an id no path can produce
+    out = orc.verify(h, W, wrong, seeds, wl.K, wl.p, parent=parent)
+    assert out["accept_len"].tolist() == [0, 0] and out["best_node"].tolist() == [0, 0]
+
+
+def test_batch_independence():
+    wl, W, h, seeds = _small_problem(7, B=3)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    full = orc.verify(h, W, draft, seeds, wl.K, wl.p)
+    for b in range(wl.B):
+        alone = orc.verify(h[b:b + 1], W, draft[b:b + 1], seeds[b:b + 1], wl.K, wl.p)
+        for k in ("path_ids", "hit", "accept_len", "vote_ids", "vote_cnt"):
+            assert (alone[k][0] == full[k][b]).all()
+
+
+def test_lower_dropout_gives_more_agreement():
+    # qualitative statement of the paper (paths agree more at lower p_drop), on a planted input
+    wl = wk.Workload("unit-planted", d=256, V=512, dtype="f32", B=1, T=24, K=5, p=0.1, data_seed=8)
+    W = wk.make_weight(wl)
+    h, planted = wk.make_planted_hidden(wl, W, alpha=6.0)
+    seeds = wk.make_seeds(wl)
+    cnt = [orc.verify(h, W, planted, seeds, wl.K, p)["vote_cnt"].mean() for p in (0.0, 0.3, 0.6)]
+    assert cnt[0] == wl.K and cnt[0] >= cnt[1] >= cnt[2] and cnt[2] < wl.K
+
+
+def test_tiny_config_end_to_end():
+    wl = wk.CONFIGS["tiny"]
+    W, h, seeds = wk.make_weight(wl), wk.make_hidden(wl), wk.make_seeds(wl)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    out = orc.verify(h, W, draft, seeds, wl.K, wl.p, want_logits=(10, 20))
+    assert out["path_ids"].shape == (1, 5, 8) and out["logits"].shape == (40, 10)
+    assert ((out["vote_cnt"] >= 1) & (out["vote_cnt"] <= wl.K)).all()
+    assert (out["gap"] >= 0).all()
+    # logits slice agrees with the single-path function
+    keep = orc.keep_mask(int(seeds[0]), 0, 2, 3, wl.d, wl.p)
+    np.testing.assert_allclose(out["logits"][2 * 8 + 3], orc.path_logits(W, h[0, 2], keep, wl.p)[10:20],
+                               rtol=0, atol=1e-12)
