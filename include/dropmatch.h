@@ -1,0 +1,162 @@
+/*
+ * dropmatch.h - C ABI of the DropMatch Monte-Carlo-dropout LM-head verification step
+ * for AMD Instinct MI355X (gfx950).
+ *
+ * The step (paper: Methodology, "Multi-Sample LM Head via MC Dropout" and "Acceptance
+ * Criteria"): for every row t of the final hidden states h, draw K keep-masks
+ * m^(i) ~ Bernoulli(1 - p_drop)^d (Eq. 1), form h_t^(i) = h_t * m^(i) / (1 - p_drop)
+ * (Eq. 2), project through the shared LM head, l_t^(i) = W h_t^(i) (Eq. 3), reduce each
+ * path to its token y_t^(i) = argmax_v l_t^(i)[v], and accept the draft token of the row
+ * if it is one of the K path tokens (Eq. 4, naive token matching) or if it is their
+ * most frequent token (Eq. 7, majority).  The first rejected row rejects all later ones;
+ * the number of accepted draft tokens is the accepted length.  With draft trees (the
+ * EAGLE-3 experiments use tree decoding with naive matching) the rule is applied along
+ * parent links and the result is the depth of the deepest accepted node.
+ *
+ * Everything here is plain C: opaque context, plain pointers, sizes.  Pointers are
+ * marked HOST or DEVICE.  The caller owns every buffer it passes; the library owns only
+ * the workspace inside the context, allocates nothing per call, never synchronises the
+ * stream and never frees caller memory.  All device work is enqueued on the stream the
+ * caller passes (a hipStream_t cast to void*; NULL is the default stream).
+ *
+ * Errors: every function returns a dm_status; DM_OK is 0, errors are negative.  A
+ * failed call enqueues nothing.  dm_last_error() returns a human-readable message for
+ * the last failure on that context (or, with NULL, of the last failed call that had no
+ * context).  Faults inside kernels (e.g. a wrong DEVICE pointer) surface at the caller's
+ * next synchronisation, as with any HIP launch.
+ *
+ * Random source (the paper only says "i.i.d. Bernoulli"): Philox4x32-10, counter
+ * (j >> 2, row t, path i, step), key (low, high word of the sequence's 64-bit seed);
+ * dimension j uses output word j & 3 and is kept iff word >= floor(p * 2^32).  Masks are
+ * therefore a pure function of (seed, step, i, t, j): reproducible on any machine.
+ */
+#ifndef DROPMATCH_H
+#define DROPMATCH_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dm_ctx dm_ctx; /* opaque; owns only its workspace */
+
+typedef enum {
+  DM_OK = 0,
+  DM_EINVAL = -1,       /* bad argument (null pointer, size, p, enum, limit of the context) */
+  DM_ENOMEM = -2,       /* workspace allocation failed in dm_create */
+  DM_EHIP = -3,         /* a HIP runtime call failed; message holds hipGetErrorString */
+  DM_EUNSUPPORTED = -4  /* valid request outside what this build implements */
+} dm_status;
+
+typedef enum { DM_F32 = 0, DM_BF16 = 1 } dm_dtype; /* storage type of BOTH h and W */
+
+typedef enum {
+  DM_RULE_ANY = 0,      /* Eq. 4: draft token is among the K path tokens */
+  DM_RULE_MAJORITY = 1  /* Eq. 7: draft token equals the mode of the K path tokens */
+} dm_rule;
+
+/* One mask per path shared by all rows of a sequence ("K persistent heads"): the row word
+ * of the Philox counter is forced to 0.  Default (flag clear): a fresh mask per (path, row). */
+#define DM_FLAG_SHARE_MASK_ACROSS_POS 1u
+/* Testing aid: run the contraction on the generic fp32-FMA kernel even where the MFMA
+ * kernel applies (lets the two kernels be compared on the same inputs). */
+#define DM_FLAG_FORCE_GENERIC 2u
+
+/* Limits of this build. */
+#define DM_MAX_K 1024            /* paths per row */
+#define DM_MAX_ROWS_PER_SEQ 4096 /* T */
+#define DM_MAX_TK 16384          /* T*K per sequence (path tokens of a sequence live in LDS) */
+
+typedef struct {
+  int32_t B;       /* sequences, >= 1 */
+  int32_t T;       /* rows of h per sequence: chain positions (incl. a bonus row) or tree nodes */
+  int32_t K;       /* dropout paths per row, 1..DM_MAX_K */
+  int32_t d;       /* hidden size */
+  int32_t V;       /* vocabulary size */
+  int32_t dtype;   /* dm_dtype */
+  float p;         /* p_drop, 0 <= p < 1 (Eq. 1) */
+  uint32_t step;   /* Philox counter word 3: vary per decode step to get fresh masks from fixed seeds */
+  int32_t rule;    /* dm_rule */
+  uint32_t flags;  /* DM_FLAG_* */
+  const uint64_t* seeds; /* HOST [B]: mask seed per sequence; read before the call returns */
+  const int32_t* parent; /* DEVICE [B,T] or NULL.  NULL: chain.  Else tree: parent[b,0] = -1,
+                            0 <= parent[b,n] < n.  A node whose parent index breaks this is
+                            treated as rejected (never read out of bounds). */
+} dm_params;
+
+/* Create a context on HIP device `device` able to serve calls with B*T*K <= max_rows,
+ * d <= max_d, V <= max_V.  Allocates the workspace (masked rows: max_rows rounded up to
+ * 128 times max_d rounded up to 64 elements of 4 bytes, plus 8 bytes per row).  The context
+ * may be used from one host thread at a time; calls on one context must be enqueued on
+ * one stream (or be ordered by the caller), since they share the workspace. */
+dm_status dm_create(dm_ctx** out, int device, int64_t max_rows, int32_t max_d, int32_t max_V);
+
+/* Synchronises the device, frees the workspace and the context.  NULL is accepted. */
+dm_status dm_destroy(dm_ctx* ctx);
+
+/* Message of the last failure (string owned by the context / the library; never free it). */
+const char* dm_last_error(const dm_ctx* ctx);
+
+/* Pure host check of a parameter block (no device is touched; usable without a GPU):
+ * sizes, p, enums, flags, limits, seeds != NULL.  `msg`/`msg_len` may be NULL/0; otherwise
+ * receives a NUL-terminated reason on failure. */
+dm_status dm_validate(const dm_params* prm, char* msg, int32_t msg_len);
+
+/*
+ * The verification step (Eq. 1-4 and 7, prefix / tree rule).  Rows are ordered (b, t, i):
+ * row index = (b*T + t)*K + i.
+ *
+ * Chain mode (prm->parent == NULL): the K paths of row t test draft_ids[b,t].
+ *   hit[b,t]        = rule(draft_ids[b,t], path_ids[b,t,:])
+ *   accept_len[b]   = first t with hit == 0 (T if none)
+ *   accept_mask[b,t]= 1 for t < accept_len[b], else 0
+ *   best_node[b]    = accept_len[b] - 1
+ *   A row with draft id < 0 (e.g. the bonus row after gamma draft tokens) never hits.
+ * Tree mode: row n holds the hidden state of node n and predicts n's children.
+ *   hit[b,0] = 1; hit[b,n] = rule(draft_ids[b,n], path_ids[b,parent[n],:]) for n > 0
+ *   accept_mask[b,n] = hit[b,n] and accept_mask[b,parent[n]]
+ *   accept_len[b]   = largest depth of an accepted node; best_node[b] = that node
+ *                     (smallest index among equally deep ones)
+ * In both modes vote_ids/vote_cnt give the mode of the K path tokens of every row and its
+ * multiplicity (ties between modes: smallest token id); argmax ties: smallest vocabulary id.
+ *
+ * The LM-head product runs in the storage type with fp32 accumulation (bf16 x bf16 products
+ * are exact in fp32); the K*T x V logits are never written to memory.  The factor
+ * 1 / (1 - p) of Eq. 2 is positive and common to a row, so it cannot change an argmax and is
+ * not applied on this path (dm_debug_logits applies it).
+ *
+ * h, W must be 16-byte aligned.  Inputs must be finite.
+ */
+dm_status dropmatch_verify(dm_ctx* ctx, const dm_params* prm,
+                           const void* h,            /* DEVICE [B,T,d] contiguous */
+                           const void* W,            /* DEVICE [V,d] row-major contiguous */
+                           const int32_t* draft_ids, /* DEVICE [B,T] */
+                           int32_t* accept_len,      /* DEVICE [B], required */
+                           int32_t* best_node,       /* DEVICE [B] or NULL */
+                           uint8_t* accept_mask,     /* DEVICE [B,T] or NULL */
+                           uint8_t* hit,             /* DEVICE [B,T] or NULL */
+                           int32_t* path_ids,        /* DEVICE [B,T,K] or NULL */
+                           int32_t* vote_ids,        /* DEVICE [B,T] or NULL */
+                           int32_t* vote_cnt,        /* DEVICE [B,T] or NULL */
+                           void* stream);
+
+/* Debug: the keep-masks of Eq. 1 exactly as dropmatch_verify draws them, bit-packed.
+ * bits: DEVICE uint32 [B,T,K,ceil(d/32)]; word w of a row holds dimensions 32w..32w+31,
+ * bit (j & 31) = keep(j); bits past d are 0. */
+dm_status dm_debug_masks(dm_ctx* ctx, const dm_params* prm, uint32_t* bits, void* stream);
+
+/* Debug: logits of Eq. 3 including the Eq. 2 scale, for vocabulary rows v0 <= v < v1, taken
+ * from the accumulators of the same contraction kernel the verify path would use:
+ * logits: DEVICE float [B*T*K, v1 - v0], value = (float)(1/(1-p)) * fp32 accumulator. */
+dm_status dm_debug_logits(dm_ctx* ctx, const dm_params* prm, const void* h, const void* W,
+                          int32_t v0, int32_t v1, float* logits, void* stream);
+
+/* Which contraction kernel a parameter block selects: 0 = generic fp32-FMA tiles (any
+ * shape, f32 or bf16), 1 = bf16 MFMA kernel (bf16, d % 64 == 0).  Negative = dm_status. */
+int32_t dm_kernel_choice(const dm_params* prm);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DROPMATCH_H */

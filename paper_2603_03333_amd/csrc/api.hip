@@ -1,0 +1,245 @@
+// C ABI of the DropMatch verify step (see include/dropmatch.h for the contract).
+#include "../../include/dropmatch.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "kernels.hpp"
+
+struct dm_ctx {
+  int device = 0;
+  int num_cu = 0;
+  int64_t max_rows = 0;
+  int32_t max_d = 0, max_V = 0;
+  int64_t rows_pad = 0;  // max_rows rounded up to 128
+  int32_t d_pad = 0;     // max_d rounded up to 64
+  void* a_ws = nullptr;               // masked rows
+  unsigned long long* keys = nullptr; // packed (logit, index) argmax per row
+  char err[512] = {0};
+};
+
+namespace {
+
+char g_err[512] = {0};  // failures that have no context (dm_create, NULL ctx)
+
+dm_status fail(dm_ctx* ctx, dm_status st, const char* fmt, ...) {
+  char* buf = ctx ? ctx->err : g_err;
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, 512, fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+dm_status fail_hip(dm_ctx* ctx, const char* what, hipError_t e) {
+  return fail(ctx, DM_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Reason a parameter block is unusable, or nullptr.
+const char* check_params(const dm_params* p, char* scratch, size_t n) {
+  if (!p) return "params is NULL";
+  if (p->B < 1) return "B must be >= 1";
+  if (p->T < 1 || p->T > DM_MAX_ROWS_PER_SEQ) {
+    snprintf(scratch, n, "T must be in 1..%d", DM_MAX_ROWS_PER_SEQ);
+    return scratch;
+  }
+  if (p->K < 1 || p->K > DM_MAX_K) {
+    snprintf(scratch, n, "K must be in 1..%d", DM_MAX_K);
+    return scratch;
+  }
+  if ((int64_t)p->T * p->K > DM_MAX_TK) {
+    snprintf(scratch, n, "T*K must be <= %d", DM_MAX_TK);
+    return scratch;
+  }
+  if (p->d < 1) return "d must be >= 1";
+  if (p->V < 1) return "V must be >= 1";
+  if ((int64_t)p->B * p->T * p->K > (int64_t)1 << 40) return "B*T*K too large";
+  if (p->dtype != DM_F32 && p->dtype != DM_BF16) return "dtype must be DM_F32 or DM_BF16";
+  if (!(p->p >= 0.0f && p->p < 1.0f)) return "p must satisfy 0 <= p < 1";
+  if (p->rule != DM_RULE_ANY && p->rule != DM_RULE_MAJORITY) return "rule must be DM_RULE_ANY or DM_RULE_MAJORITY";
+  if (p->flags & ~(DM_FLAG_SHARE_MASK_ACROSS_POS | DM_FLAG_FORCE_GENERIC)) return "unknown bits in flags";
+  if (!p->seeds) return "seeds is NULL";
+  return nullptr;
+}
+
+bool use_mfma(const dm_params* p) {
+  return p->dtype == DM_BF16 && (p->d % 64) == 0 && !(p->flags & DM_FLAG_FORCE_GENERIC);
+}
+
+int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// Geometry of a call inside the limits of the context, or an error.
+dm_status make_geom(dm_ctx* ctx, const dm_params* p, bool mfma, dm::RowGeom* g) {
+  char scratch[128];
+  if (const char* why = check_params(p, scratch, sizeof scratch)) return fail(ctx, DM_EINVAL, "%s", why);
+  const int64_t M = (int64_t)p->B * p->T * p->K;
+  if (M > ctx->max_rows) return fail(ctx, DM_EINVAL, "B*T*K = %lld exceeds the context's max_rows %lld", (long long)M, (long long)ctx->max_rows);
+  if (p->d > ctx->max_d) return fail(ctx, DM_EINVAL, "d = %d exceeds the context's max_d %d", p->d, ctx->max_d);
+  if (p->V > ctx->max_V) return fail(ctx, DM_EINVAL, "V = %d exceeds the context's max_V %d", p->V, ctx->max_V);
+  g->B = p->B;
+  g->T = p->T;
+  g->K = p->K;
+  g->d = p->d;
+  g->M = M;
+  // MFMA kernel: 32-row tiles, up to four per workgroup; beyond 128 rows whole groups of four
+  g->M_pad = mfma ? (M <= 128 ? round_up(M, 32) : round_up(M, 128)) : round_up(M, 128);
+  g->d_pad = (int)round_up(p->d, 64);
+  g->thr = (uint32_t)std::floor((double)p->p * 4294967296.0);
+  g->step = p->step;
+  g->share_pos = (p->flags & DM_FLAG_SHARE_MASK_ACROSS_POS) ? 1 : 0;
+  return DM_OK;
+}
+
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = true;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) != hipSuccess) { ok = false; return; }
+    if (prev != dev && hipSetDevice(dev) != hipSuccess) ok = false;
+  }
+  ~DeviceGuard() {
+    int cur = -1;
+    if (prev >= 0 && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
+  }
+};
+
+// Eq. (1)-(3) + argmax keys; shared by dropmatch_verify and dm_debug_logits.
+dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g, bool mfma, const void* h,
+                          const void* W, float* logits, int v0, int v1, hipStream_t s) {
+  const bool bf16 = p->dtype == DM_BF16;
+  hipError_t e = dm::launch_mask_rows(h, ctx->a_ws, ctx->keys, p->seeds, g, bf16, mfma, s);
+  if (e != hipSuccess) return fail_hip(ctx, "mask_rows launch", e);
+  const float scale = (float)(1.0 / (1.0 - (double)p->p));
+  if (mfma)
+    e = dm::launch_lmhead_mfma(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, s);
+  else
+    e = dm::launch_lmhead_generic(W, ctx->a_ws, ctx->keys, g, p->V, bf16, logits, v0, v1, scale, s);
+  if (e != hipSuccess) return fail_hip(ctx, "lmhead launch", e);
+  return DM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+dm_status dm_validate(const dm_params* prm, char* msg, int32_t msg_len) {
+  char scratch[128];
+  const char* why = check_params(prm, scratch, sizeof scratch);
+  if (msg && msg_len > 0) snprintf(msg, (size_t)msg_len, "%s", why ? why : "");
+  return why ? DM_EINVAL : DM_OK;
+}
+
+int32_t dm_kernel_choice(const dm_params* prm) {
+  char scratch[128];
+  if (check_params(prm, scratch, sizeof scratch)) return DM_EINVAL;
+  return use_mfma(prm) ? 1 : 0;
+}
+
+const char* dm_last_error(const dm_ctx* ctx) { return ctx ? ctx->err : g_err; }
+
+dm_status dm_create(dm_ctx** out, int device, int64_t max_rows, int32_t max_d, int32_t max_V) {
+  if (!out) return fail(nullptr, DM_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (max_rows < 1 || max_d < 1 || max_V < 1) return fail(nullptr, DM_EINVAL, "max_rows, max_d, max_V must be >= 1");
+  int ndev = 0;
+  hipError_t e = hipGetDeviceCount(&ndev);
+  if (e != hipSuccess) return fail_hip(nullptr, "hipGetDeviceCount", e);
+  if (device < 0 || device >= ndev) return fail(nullptr, DM_EINVAL, "device %d not in 0..%d", device, ndev - 1);
+  DeviceGuard guard(device);
+  if (!guard.ok) return fail(nullptr, DM_EHIP, "cannot select device %d", device);
+
+  hipDeviceProp_t prop;
+  if ((e = hipGetDeviceProperties(&prop, device)) != hipSuccess) return fail_hip(nullptr, "hipGetDeviceProperties", e);
+  if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+    return fail(nullptr, DM_EUNSUPPORTED, "device %d is %s; this library is built for gfx950 only", device, prop.gcnArchName);
+
+  dm_ctx* ctx = new (std::nothrow) dm_ctx();
+  if (!ctx) return fail(nullptr, DM_ENOMEM, "host allocation failed");
+  ctx->device = device;
+  ctx->num_cu = prop.multiProcessorCount;
+  ctx->max_rows = max_rows;
+  ctx->max_d = max_d;
+  ctx->max_V = max_V;
+  ctx->rows_pad = round_up(max_rows, 128);
+  ctx->d_pad = (int32_t)round_up(max_d, 64);
+  const size_t a_bytes = (size_t)ctx->rows_pad * (size_t)ctx->d_pad * 4;
+  if ((e = hipMalloc(&ctx->a_ws, a_bytes)) != hipSuccess ||
+      (e = hipMalloc((void**)&ctx->keys, (size_t)ctx->rows_pad * 8)) != hipSuccess) {
+    (void)hipGetLastError();
+    if (ctx->a_ws) (void)hipFree(ctx->a_ws);
+    delete ctx;
+    return fail(nullptr, DM_ENOMEM, "workspace allocation of %zu bytes failed: %s", a_bytes, hipGetErrorString(e));
+  }
+  if ((e = dm::prepare_lmhead_mfma()) != hipSuccess || (e = dm::prepare_vote_accept()) != hipSuccess) {
+    (void)hipFree(ctx->a_ws);
+    (void)hipFree(ctx->keys);
+    delete ctx;
+    return fail_hip(nullptr, "raising the dynamic LDS limit", e);
+  }
+  *out = ctx;
+  return DM_OK;
+}
+
+dm_status dm_destroy(dm_ctx* ctx) {
+  if (!ctx) return DM_OK;
+  DeviceGuard guard(ctx->device);
+  dm_status st = DM_OK;
+  if (!guard.ok || hipDeviceSynchronize() != hipSuccess) st = fail(nullptr, DM_EHIP, "device synchronisation failed in dm_destroy");
+  if (ctx->a_ws) (void)hipFree(ctx->a_ws);
+  if (ctx->keys) (void)hipFree(ctx->keys);
+  delete ctx;
+  return st;
+}
+
+dm_status dropmatch_verify(dm_ctx* ctx, const dm_params* prm, const void* h, const void* W,
+                           const int32_t* draft_ids, int32_t* accept_len, int32_t* best_node,
+                           uint8_t* accept_mask, uint8_t* hit, int32_t* path_ids, int32_t* vote_ids,
+                           int32_t* vote_cnt, void* stream) {
+  if (!ctx) return fail(nullptr, DM_EINVAL, "ctx is NULL");
+  if (!prm) return fail(ctx, DM_EINVAL, "params is NULL");
+  if (!h || !W || !draft_ids || !accept_len) return fail(ctx, DM_EINVAL, "h, W, draft_ids and accept_len are required");
+  if (((uintptr_t)h | (uintptr_t)W) & 15) return fail(ctx, DM_EINVAL, "h and W must be 16-byte aligned");
+  const bool mfma = use_mfma(prm);
+  dm::RowGeom g;
+  if (dm_status st = make_geom(ctx, prm, mfma, &g)) return st;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return fail(ctx, DM_EHIP, "cannot select device %d", ctx->device);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  if (dm_status st = run_contraction(ctx, prm, g, mfma, h, W, nullptr, 0, 0, s)) return st;
+  dm::VoteOut out{accept_len, best_node, accept_mask, hit, path_ids, vote_ids, vote_cnt};
+  hipError_t e = dm::launch_vote_accept(ctx->keys, draft_ids, prm->parent, prm->B, prm->T, prm->K, prm->rule, out, s);
+  if (e != hipSuccess) return fail_hip(ctx, "vote_accept launch", e);
+  return DM_OK;
+}
+
+dm_status dm_debug_masks(dm_ctx* ctx, const dm_params* prm, uint32_t* bits, void* stream) {
+  if (!ctx) return fail(nullptr, DM_EINVAL, "ctx is NULL");
+  if (!prm || !bits) return fail(ctx, DM_EINVAL, "params and bits are required");
+  dm::RowGeom g;
+  if (dm_status st = make_geom(ctx, prm, false, &g)) return st;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return fail(ctx, DM_EHIP, "cannot select device %d", ctx->device);
+  hipError_t e = dm::launch_mask_bits(bits, prm->seeds, g, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail_hip(ctx, "mask_bits launch", e);
+  return DM_OK;
+}
+
+dm_status dm_debug_logits(dm_ctx* ctx, const dm_params* prm, const void* h, const void* W, int32_t v0,
+                          int32_t v1, float* logits, void* stream) {
+  if (!ctx) return fail(nullptr, DM_EINVAL, "ctx is NULL");
+  if (!prm || !h || !W || !logits) return fail(ctx, DM_EINVAL, "params, h, W and logits are required");
+  if (((uintptr_t)h | (uintptr_t)W) & 15) return fail(ctx, DM_EINVAL, "h and W must be 16-byte aligned");
+  const bool mfma = use_mfma(prm);
+  dm::RowGeom g;
+  if (dm_status st = make_geom(ctx, prm, mfma, &g)) return st;
+  if (v0 < 0 || v1 <= v0 || v1 > prm->V) return fail(ctx, DM_EINVAL, "need 0 <= v0 < v1 <= V");
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return fail(ctx, DM_EHIP, "cannot select device %d", ctx->device);
+  return run_contraction(ctx, prm, g, mfma, h, W, logits, v0, v1, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

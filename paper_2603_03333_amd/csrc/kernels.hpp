@@ -1,0 +1,69 @@
+// Launchers of the device kernels behind the C ABI.  All of them only enqueue work on
+// `stream`; shapes have been validated by the caller (api.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dm {
+
+constexpr int kSeedsPerLaunch = 128;  // seeds travel as kernel arguments, this many per launch
+
+struct SeedPack {
+  uint64_t s[kSeedsPerLaunch];
+};
+
+struct RowGeom {
+  int B, T, K, d;
+  int64_t M;       // B*T*K real rows
+  int64_t M_pad;   // rows of the masked-row workspace (zero rows past M)
+  int d_pad;       // columns of the plain workspace layout (zero columns past d)
+  uint32_t thr;    // drop threshold floor(p * 2^32)
+  uint32_t step;
+  int share_pos;   // row word of the counter forced to 0
+};
+
+// Eq. (1)+(2) without the scale: masked rows a = keep ? h : 0 into the workspace, and the
+// per-row argmax keys reset to 0.  swizzled = layout of the MFMA kernel's B-fragments;
+// otherwise plain [M_pad, d_pad].  is_bf16 selects the element type of h and the workspace.
+hipError_t launch_mask_rows(const void* h, void* a_ws, unsigned long long* keys, const uint64_t* seeds_host,
+                            const RowGeom& g, bool is_bf16, bool swizzled, hipStream_t stream);
+
+// Eq. (1) only, bit-packed [M, ceil(d/32)].
+hipError_t launch_mask_bits(uint32_t* bits, const uint64_t* seeds_host, const RowGeom& g, hipStream_t stream);
+
+// Eq. (3) + per-row argmax, generic fp32-FMA tiles.  a_ws plain layout.  If logits != null the
+// kernel instead stores scale * accumulator for v in [v0, v1) and touches no keys.
+hipError_t launch_lmhead_generic(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g,
+                                 int V, bool is_bf16, float* logits, int v0, int v1, float scale,
+                                 hipStream_t stream);
+
+// Eq. (3) + per-row argmax on bf16 MFMA; a_ws swizzled layout; d % 64 == 0.
+hipError_t launch_lmhead_mfma(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g,
+                              int V, int num_cu, float* logits, int v0, int v1, float scale,
+                              hipStream_t stream);
+hipError_t prepare_lmhead_mfma();  // raises the dynamic-LDS limit of the kernels once per process
+
+// Eq. (4)/(7), prefix / tree rule.  One workgroup per sequence.
+struct VoteOut {
+  int32_t* accept_len;
+  int32_t* best_node;
+  uint8_t* accept_mask;
+  uint8_t* hit;
+  int32_t* path_ids;
+  int32_t* vote_ids;
+  int32_t* vote_cnt;
+};
+hipError_t launch_vote_accept(const unsigned long long* keys, const int32_t* draft_ids, const int32_t* parent,
+                              int B, int T, int K, int rule, const VoteOut& out, hipStream_t stream);
+hipError_t prepare_vote_accept();
+
+// Packed argmax key: larger logit wins, then smaller vocabulary index.  Key 0 = "nothing yet".
+__host__ __device__ inline unsigned long long pack_key(float val, uint32_t v) {
+  union { float f; uint32_t u; } c;
+  c.f = val;
+  uint32_t u = c.u;
+  u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  return ((unsigned long long)u << 32) | (unsigned long long)(0xFFFFFFFFu - v);
+}
+
+}  // namespace dm

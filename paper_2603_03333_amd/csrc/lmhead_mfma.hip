@@ -1,0 +1,268 @@
+// Eq. (3) l = W h^(i) with a fused per-row argmax on the gfx950 matrix cores.
+//
+// The contraction is C[v, m] = sum_k W[v, k] * a[m, k] with W rows as the MFMA "A" operand
+// (index i = vocabulary row) and the masked hidden rows as the "B" operand (index j = masked
+// row).  In the 32x32 accumulator layout a lane then owns ONE masked row (j = lane % 32) and
+// 16 vocabulary rows per tile, so the running argmax over the vocabulary is a per-lane
+// compare with no cross-lane traffic; lanes meet only once per 256-row vocabulary tile.
+//
+// Workgroup: 256 threads = 4 wavefronts; tile = 256 vocabulary rows x (32*MT <= 128) masked
+// rows; wavefront w owns vocabulary rows [64w, 64w+64) (two 32-row MFMA tiles) against all
+// masked rows: 2*MT accumulator tiles of 16 VGPRs.  k advances in slabs of 64 (one 128-byte
+// line of each W row).
+//
+// Data movement: both operands go global -> LDS with the LDS-DMA form of global loads (no
+// VGPR staging), three slabs deep, so two slabs (64 KB of W per CU) are always in flight.
+//   * W: one DMA instruction moves 8 rows x 128 B; eight consecutive lanes read one full
+//     line of a row (coalesced), and the 16-byte piece q of row r is placed at slot
+//     q ^ ((r >> 1) & 7) of the row so that the later ds_read_b128 of MFMA fragments (32
+//     different rows, same piece) spreads over all LDS banks.
+//   * masked rows: the mask kernel has already laid them out in fragment order, so the copy
+//     and the fragment reads are both linear.
+// Each wavefront waits for its own DMA with s_waitcnt vmcnt(n), then one s_barrier per slab
+// makes every wavefront's DMA visible and frees the slab consumed before.  The compiler does
+// not model LDS-DMA, so waits and barriers are explicit, and "memory" clobbers keep its LDS
+// reads between them.
+//
+// Workgroups are persistent: grid.x = min(#tiles, #CUs); a workgroup walks tiles
+// blockIdx.x, blockIdx.x + grid.x, ... with the slab pipeline running across tile borders.
+#include "kernels.hpp"
+
+namespace dm {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BN = 256;                 // vocabulary rows per tile
+constexpr int BK = 64;                  // k per slab
+constexpr int NS = 3;                   // slabs resident in LDS
+constexpr int W_SLAB_BYTES = BN * BK * 2;  // 32 KB
+
+__host__ __device__ constexpr int slab_bytes(int MT) { return W_SLAB_BYTES + MT * 4 * 1024; }
+__host__ __device__ constexpr int lds_bytes(int MT) { return NS * slab_bytes(MT) + 4 * MT * 32 * 8; }
+
+#define DM_GLOBAL_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
+#define DM_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
+
+// s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14])
+#define DM_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+
+template <int MT, bool DUMP>
+__global__ __launch_bounds__(256, 1) void lmhead_mfma_kernel(const __bf16* __restrict__ W,
+                                                             const __bf16* __restrict__ A_sw,
+                                                             unsigned long long* __restrict__ keys, int V, int d,
+                                                             int64_t M, int mt_total, int tile_begin,
+                                                             int tile_end, float* __restrict__ logits, int dv0,
+                                                             int dv1, float scale) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+  constexpr int SLAB = slab_bytes(MT);
+  constexpr int LOADS_PER_SLAB = 8 + MT;  // DMA instructions one lane issues per slab
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int i32 = lane & 31;  // row inside a 32-row MFMA tile
+  const int hb = lane >> 5;   // which 8 of the 16 k of an MFMA step
+  const int mblk = blockIdx.y;
+  const int nchunks = d / BK;
+
+  const int G = gridDim.x;
+  const int first_tile = tile_begin + blockIdx.x;
+  const int my_tiles = (first_tile < tile_end) ? (tile_end - first_tile + G - 1) / G : 0;
+  const int total = my_tiles * nchunks;
+
+  // DMA source coordinates of this lane inside a W slab: row (8*rb + lane/8), 16-byte piece
+  const int ld_row = lane >> 3;
+  const int ld_slot = lane & 7;
+
+  auto issue = [&](int q) {
+    const int n = q / nchunks;
+    const int c = q - n * nchunks;
+    const int v0 = (first_tile + n * G) * BN;
+    unsigned char* stage = lds + (q % NS) * SLAB;
+#pragma unroll
+    for (int rb = 0; rb < 8; ++rb) {
+      const int row = 8 * rb + ld_row;  // row inside this wavefront's 64
+      int vrow = v0 + 64 * wave + row;
+      vrow = vrow < V ? vrow : V - 1;   // tail tile: re-read the last row, masked out later
+      const int piece = ld_slot ^ ((row >> 1) & 7);
+      const __bf16* src = W + (int64_t)vrow * d + c * BK + piece * 8;
+      __builtin_amdgcn_global_load_lds(DM_GLOBAL_PTR(src), DM_LDS_PTR(stage + wave * 8192 + rb * 1024), 16, 0, 0);
+    }
+#pragma unroll
+    for (int x = 0; x < MT; ++x) {
+      const int f = wave + 4 * x;       // fragment index inside the slab: f = s * MT + mt
+      const int s = f / MT;
+      const int mt = f - s * MT;
+      const __bf16* src = A_sw + ((((int64_t)(c * 4 + s) * mt_total + mblk * MT + mt) * 64) + lane) * 8;
+      __builtin_amdgcn_global_load_lds(DM_GLOBAL_PTR(src), DM_LDS_PTR(stage + W_SLAB_BYTES + f * 1024), 16, 0, 0);
+    }
+  };
+
+  f32x16 acc[MT][2];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mt][vt][r] = 0.f;
+
+  if (total > 0) issue(0);
+  if (total > 1) issue(1);
+
+  for (int q = 0; q < total; ++q) {
+    // own DMA of slab q has landed (the slab issued after it may still be in flight)
+    if (q + 1 < total) {
+      DM_WAIT_VMCNT(LOADS_PER_SLAB);
+    } else {
+      DM_WAIT_VMCNT(0);
+    }
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();  // everyone's DMA of slab q landed; everyone finished slab q-1
+    asm volatile("" ::: "memory");
+    if (q + 2 < total) issue(q + 2);  // overwrites the buffer of slab q-1
+
+    const unsigned char* stage = lds + (q % NS) * SLAB;
+    const unsigned char* wbase = stage + wave * 8192 + i32 * 128;
+    const unsigned char* abase = stage + W_SLAB_BYTES + lane * 16;
+    const int swz = (i32 >> 1) & 7;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      bf16x8 wf[2], af[MT];
+#pragma unroll
+      for (int vt = 0; vt < 2; ++vt)
+        wf[vt] = *reinterpret_cast<const bf16x8*>(wbase + vt * 4096 + 16 * ((2 * s + hb) ^ swz));
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) af[mt] = *reinterpret_cast<const bf16x8*>(abase + (s * MT + mt) * 1024);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int vt = 0; vt < 2; ++vt)
+          acc[mt][vt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[vt], af[mt], acc[mt][vt], 0, 0, 0);
+    }
+    asm volatile("" ::: "memory");
+
+    const int n = q / nchunks;
+    if (q - n * nchunks != nchunks - 1) continue;
+
+    // ---- tile finished: accumulator (vt, r) of lane holds row v, column m ----
+    //   v = v0 + 64*wave + 32*vt + 8*(r/4) + 4*hb + (r%4),  m = 128*mblk + 32*mt + lane%32
+    const int v0 = (first_tile + n * G) * BN;
+    if (DUMP) {
+      const int nv = dv1 - dv0;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int64_t m = (int64_t)(mblk * MT + mt) * 32 + i32;
+#pragma unroll
+        for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int v = v0 + 64 * wave + 32 * vt + 8 * (r >> 2) + 4 * hb + (r & 3);
+            if (m < M && v >= dv0 && v < dv1 && v < V) logits[m * nv + (v - dv0)] = scale * acc[mt][vt][r];
+            acc[mt][vt][r] = 0.f;
+          }
+      }
+      continue;
+    }
+
+    unsigned long long* red = reinterpret_cast<unsigned long long*>(lds + NS * SLAB);  // [4][MT*32]
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      float best = -INFINITY;
+      uint32_t bv = 0xFFFFFFFFu;
+#pragma unroll
+      for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {  // ascending v for this lane: strict > keeps the smallest index
+          const int v = v0 + 64 * wave + 32 * vt + 8 * (r >> 2) + 4 * hb + (r & 3);
+          const float val = acc[mt][vt][r] + 0.0f;
+          if (v < V && (bv == 0xFFFFFFFFu || val > best)) {
+            best = val;
+            bv = (uint32_t)v;
+          }
+          acc[mt][vt][r] = 0.f;
+        }
+      unsigned long long key = (bv == 0xFFFFFFFFu) ? 0ull : pack_key(best, bv);
+      const unsigned long long other = __shfl_xor(key, 32, 64);
+      key = other > key ? other : key;
+      if (hb == 0) red[wave * (MT * 32) + mt * 32 + i32] = key;
+    }
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): LDS writes above are done
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (tid < MT * 32) {
+      unsigned long long key = red[tid];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) {
+        const unsigned long long other = red[w * (MT * 32) + tid];
+        key = other > key ? other : key;
+      }
+      const int64_t m = (int64_t)mblk * (MT * 32) + tid;
+      if (m < M && key != 0ull) atomicMax(&keys[m], key);
+    }
+  }
+}
+
+template <int MT>
+hipError_t run(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V, int num_cu,
+               float* logits, int v0, int v1, float scale, hipStream_t stream) {
+  const bool dump = logits != nullptr;
+  const int tile_begin = dump ? v0 / BN : 0;
+  const int tile_end = dump ? (v1 + BN - 1) / BN : (V + BN - 1) / BN;
+  if (tile_end <= tile_begin) return hipSuccess;
+  const int mt_total = (int)(g.M_pad >> 5);
+  const int mblocks = mt_total / MT;
+  int gx = tile_end - tile_begin;
+  const int cap = num_cu / (mblocks < num_cu ? mblocks : num_cu);
+  if (gx > (cap > 0 ? cap : 1)) gx = cap > 0 ? cap : 1;
+  const dim3 grid((unsigned)gx, (unsigned)mblocks), block(256);
+  if (dump)
+    lmhead_mfma_kernel<MT, true><<<grid, block, lds_bytes(MT), stream>>>(
+        static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, V, g.d, g.M, mt_total, tile_begin,
+        tile_end, logits, v0, v1, scale);
+  else
+    lmhead_mfma_kernel<MT, false><<<grid, block, lds_bytes(MT), stream>>>(
+        static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, V, g.d, g.M, mt_total, tile_begin,
+        tile_end, logits, v0, v1, scale);
+  return hipGetLastError();
+}
+
+template <int MT, bool DUMP>
+hipError_t raise_lds() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_mfma_kernel<MT, DUMP>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(MT));
+}
+
+}  // namespace
+
+hipError_t prepare_lmhead_mfma() {
+  hipError_t e;
+  if ((e = raise_lds<1, false>()) != hipSuccess) return e;
+  if ((e = raise_lds<2, false>()) != hipSuccess) return e;
+  if ((e = raise_lds<3, false>()) != hipSuccess) return e;
+  if ((e = raise_lds<4, false>()) != hipSuccess) return e;
+  if ((e = raise_lds<1, true>()) != hipSuccess) return e;
+  if ((e = raise_lds<2, true>()) != hipSuccess) return e;
+  if ((e = raise_lds<3, true>()) != hipSuccess) return e;
+  if ((e = raise_lds<4, true>()) != hipSuccess) return e;
+  return hipSuccess;
+}
+
+hipError_t launch_lmhead_mfma(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V,
+                              int num_cu, float* logits, int v0, int v1, float scale, hipStream_t stream) {
+  const int mt_total = (int)(g.M_pad >> 5);
+  if (mt_total >= 4) {
+    if (mt_total % 4 != 0) return hipErrorInvalidValue;
+    return run<4>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, stream);
+  }
+  switch (mt_total) {
+    case 1: return run<1>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, stream);
+    case 2: return run<2>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, stream);
+    case 3: return run<3>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace dm

@@ -1,0 +1,52 @@
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11) as the random source of the keep-masks
+// of Eq. (1).  Counter (j >> 2, row, path, step), key = 64-bit sequence seed; dimension j
+// takes output word (j & 3); keep iff word >= floor(p * 2^32).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dm {
+
+struct Philox4 {
+  uint32_t w[4];
+};
+
+__device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                 uint32_t k0, uint32_t k1) {
+  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+    const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0;
+    const uint32_t n2 = hi0 ^ c3 ^ k1;
+    c0 = n0;
+    c1 = lo1;
+    c2 = n2;
+    c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  Philox4 o;
+  o.w[0] = c0;
+  o.w[1] = c1;
+  o.w[2] = c2;
+  o.w[3] = c3;
+  return o;
+}
+
+// 8 keep bits for dimensions 8*o .. 8*o+7 of (row word t, path i): bit e = keep(8*o + e).
+__device__ __forceinline__ uint32_t keep_bits8(uint32_t o, uint32_t t, uint32_t i, uint32_t step,
+                                               uint32_t k0, uint32_t k1, uint32_t thr) {
+  const Philox4 a = philox4x32_10(2u * o, t, i, step, k0, k1);
+  const Philox4 b = philox4x32_10(2u * o + 1u, t, i, step, k0, k1);
+  uint32_t bits = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    bits |= (a.w[e] >= thr ? 1u : 0u) << e;
+    bits |= (b.w[e] >= thr ? 1u : 0u) << (4 + e);
+  }
+  return bits;
+}
+
+}  // namespace dm

@@ -1,0 +1,148 @@
+// Acceptance of draft tokens against the K path tokens of every row: naive token matching
+// (Eq. 4), majority (Eq. 7), then the prefix rule of speculative decoding (chain) or its
+// extension along parent links (tree).  One workgroup per sequence; all integer work.
+#include "kernels.hpp"
+
+namespace dm {
+namespace {
+
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long x) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const unsigned long long o = __shfl_xor(x, off, 64);
+    x = o > x ? o : x;
+  }
+  return x;
+}
+
+__global__ __launch_bounds__(256) void vote_accept_kernel(const unsigned long long* __restrict__ keys,
+                                                          const int32_t* __restrict__ draft_ids,
+                                                          const int32_t* __restrict__ parent, int T, int K,
+                                                          int rule, VoteOut out) {
+  extern __shared__ int32_t sm[];
+  int32_t* ids = sm;            // [T*K] path tokens of this sequence
+  int32_t* vid = ids + T * K;   // [T] mode of each row
+  int32_t* hitv = vid + T;      // [T] per-row rule result
+  int32_t* aux = hitv + T;      // [T] tree: depth of accepted nodes, -1 if rejected
+
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int TK = T * K;
+
+  // path token = vocabulary index held in the low word of the packed argmax key
+  for (int x = tid; x < TK; x += 256) {
+    const unsigned long long key = keys[(int64_t)b * TK + x];
+    const int32_t id = (int32_t)(0xFFFFFFFFu - (uint32_t)key);
+    ids[x] = id;
+    if (out.path_ids) out.path_ids[(int64_t)b * TK + x] = id;
+  }
+  __syncthreads();
+
+  // mode of the K tokens of each row (ties: smallest id), one wavefront per row
+  for (int t = wave; t < T; t += 4) {
+    const int32_t* row = ids + t * K;
+    unsigned long long best = 0;
+    for (int i0 = 0; i0 < K; i0 += 64) {
+      const int i = i0 + lane;
+      if (i < K) {
+        const int32_t mine = row[i];
+        uint32_t cnt = 0;
+        for (int j = 0; j < K; ++j) cnt += (row[j] == mine) ? 1u : 0u;
+        const unsigned long long k = ((unsigned long long)cnt << 32) | (0x7FFFFFFFu - (uint32_t)mine);
+        best = k > best ? k : best;
+      }
+    }
+    best = wave_max_u64(best);
+    if (lane == 0) {
+      const int32_t id = (int32_t)(0x7FFFFFFFu - (uint32_t)best);
+      vid[t] = id;
+      if (out.vote_ids) out.vote_ids[(int64_t)b * T + t] = id;
+      if (out.vote_cnt) out.vote_cnt[(int64_t)b * T + t] = (int32_t)(best >> 32);
+    }
+  }
+  __syncthreads();
+
+  // rule result per row (chain: against its own paths; tree: against the parent's paths)
+  for (int t = wave; t < T; t += 4) {
+    int32_t src = t;
+    int forced = -1;  // -1: evaluate the rule
+    if (parent != nullptr) {
+      if (t == 0) {
+        forced = 1;
+      } else {
+        src = parent[(int64_t)b * T + t];
+        if (src < 0 || src >= t) forced = 0;
+      }
+    }
+    int h;
+    if (forced >= 0) {
+      h = forced;
+    } else {
+      const int32_t g = draft_ids[(int64_t)b * T + t];
+      if (g < 0) {
+        h = 0;
+      } else if (rule == 1) {
+        h = (vid[src] == g) ? 1 : 0;
+      } else {
+        int any = 0;
+        for (int i = lane; i < K; i += 64) any |= (ids[src * K + i] == g) ? 1 : 0;
+        h = __any(any) ? 1 : 0;
+      }
+    }
+    if (lane == 0) {
+      hitv[t] = h;
+      if (out.hit) out.hit[(int64_t)b * T + t] = (uint8_t)h;
+    }
+  }
+  __syncthreads();
+
+  if (tid == 0) {
+    int len, best_node;
+    if (parent == nullptr) {
+      int n = 0;
+      while (n < T && hitv[n]) ++n;
+      len = n;
+      best_node = n - 1;
+      for (int t = 0; t < T; ++t) aux[t] = (t < n) ? 0 : -1;
+    } else {
+      aux[0] = 0;
+      len = 0;
+      best_node = 0;
+      for (int n = 1; n < T; ++n) {
+        const int q = parent[(int64_t)b * T + n];
+        int dep = -1;
+        if (q >= 0 && q < n && hitv[n] && aux[q] >= 0) dep = aux[q] + 1;
+        aux[n] = dep;
+        if (dep > len) {
+          len = dep;
+          best_node = n;
+        }
+      }
+    }
+    out.accept_len[b] = len;
+    if (out.best_node) out.best_node[b] = best_node;
+  }
+  __syncthreads();
+  if (out.accept_mask)
+    for (int t = tid; t < T; t += 256) out.accept_mask[(int64_t)b * T + t] = aux[t] >= 0 ? 1 : 0;
+}
+
+}  // namespace
+
+static size_t vote_lds_bytes(int T, int K) { return ((size_t)T * K + 3 * (size_t)T) * sizeof(int32_t); }
+
+hipError_t prepare_vote_accept() {
+  // T*K <= 16384 and T <= 4096: at most 112 KB of LDS
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&vote_accept_kernel),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)vote_lds_bytes(4096, 4));
+}
+
+hipError_t launch_vote_accept(const unsigned long long* keys, const int32_t* draft_ids, const int32_t* parent,
+                              int B, int T, int K, int rule, const VoteOut& out, hipStream_t stream) {
+  vote_accept_kernel<<<dim3((unsigned)B), dim3(256), vote_lds_bytes(T, K), stream>>>(keys, draft_ids, parent, T, K,
+                                                                                      rule, out);
+  return hipGetLastError();
+}
+
+}  // namespace dm

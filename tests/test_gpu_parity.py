@@ -1,0 +1,252 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the C ABI.
+
+Bars: masks, hit, accept_mask, accept_len, best_node, vote bit-exact; path tokens exact
+except at rows whose oracle top-2 logit gap is < 1e-3 (counted, printed); logits within
+2e-2 absolute for bf16 inputs with fp32 accumulation (1e-3 for fp32 inputs)."""
+import numpy as np
+import pytest
+
+from oracle import dropmatch_oracle as orc
+from paper_2603_03333_amd import workloads as wk
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("no GPU", allow_module_level=True)
+
+from paper_2603_03333_amd import binding as dmb  # noqa: E402
+from gpu_harness import Runner, compare_path_ids, to_device  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def runner():
+    r = Runner(max_rows=4096, max_d=4096, max_V=8192)
+    yield r
+    r.close()
+
+
+def _problem(name, d, V, dtype, B, T, K, p, seed, bonus=False):
+    wl = wk.Workload(name, d=d, V=V, dtype=dtype, B=B, T=T, K=K, p=p, bonus=bonus, data_seed=seed)
+    W, h = wk.make_weight(wl), wk.make_hidden(wl)
+    seeds = wk.make_seeds(wl, base_seed=17)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    return wl, W, h, seeds, draft
+
+
+def _check_against_oracle(res, ref, draft, rule, parent=None, label=""):
+    ndiff, nnear = compare_path_ids(res["path_ids"], ref["path_ids"], ref["gap"])
+    print(f"[{label}] rows={ref['gap'].size} near-tie rows(gap<1e-3)={nnear} path-token flips={ndiff}", flush=True)
+    expect = ref if ndiff == 0 else orc.acceptance_from_path_ids(res["path_ids"], draft, rule, parent)
+    for k in ("vote_ids", "vote_cnt", "hit", "accept_mask", "accept_len", "best_node"):
+        assert np.array_equal(res[k], expect[k]), f"{label}: {k} differs"
+    return ndiff
+
+
+# ------------------------------------------------------------------ masks (Eq. 1)
+@pytest.mark.parametrize("d,T,K,B,p,step,share", [
+    (256, 5, 8, 1, 0.1, 0, False),
+    (4096, 8, 16, 1, 0.1, 0, False),
+    (37, 3, 5, 2, 0.3, 7, False),       # d not a multiple of 4, 8 or 32
+    (96, 4, 3, 2, 0.5, 2 ** 32 - 1, True),
+    (64, 1, 1, 1, 0.0, 0, False),
+])
+def test_masks_bit_exact(runner, d, T, K, B, p, step, share):
+    wl = wk.Workload("m", d=d, V=16, dtype="bf16", B=B, T=T, K=K, p=p)
+    seeds = np.array([3 + (2 ** 40) * b + b for b in range(B)], dtype=np.uint64)
+    flags = dmb.DM_FLAG_SHARE_MASK_ACROSS_POS if share else 0
+    got = runner.masks(wl, seeds, step=step, flags=flags)
+    want = np.stack([orc.pack_mask_bits(orc.keep_masks(int(s), step, T, K, d, p, share)) for s in seeds])
+    assert got.shape == want.shape and np.array_equal(got, want)
+
+
+def test_masks_many_sequences_cross_seed_chunks(runner):
+    # more sequences than seeds fit in one launch (seeds travel as kernel arguments)
+    wl = wk.Workload("m", d=64, V=16, dtype="f32", B=300, T=2, K=3, p=0.2)
+    seeds = (np.arange(300, dtype=np.uint64) * np.uint64(2654435761)) + np.uint64(1 << 33)
+    got = runner.masks(wl, seeds)
+    want = np.stack([orc.pack_mask_bits(orc.keep_masks(int(s), 0, 2, 3, 64, 0.2)) for s in seeds])
+    assert np.array_equal(got, want)
+
+
+# ------------------------------------------------------------------ whole step, small shapes
+def test_tiny_config_fp32(runner):
+    wl = wk.CONFIGS["tiny"]
+    W, h, seeds = wk.make_weight(wl), wk.make_hidden(wl), wk.make_seeds(wl)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    ref = orc.verify(h, W, draft, seeds, wl.K, wl.p, want_logits=(0, wl.V))
+    hd, Wd = to_device(h, "f32"), to_device(W, "f32")
+    res = runner.verify(wl, hd, Wd, draft, seeds)
+    _check_against_oracle(res, ref, draft, orc.RULE_ANY, label="tiny/f32")
+    lg = runner.logits(wl, hd, Wd, seeds, 0, wl.V)
+    assert np.abs(lg - ref["logits"]).max() < 1e-3
+
+
+@pytest.mark.parametrize("d,V,B,T,K,p", [
+    (256, 1000, 1, 5, 5, 0.3),     # paper's K=5, p=0.3; M=25 (one partial row tile), ragged last vocabulary tile
+    (128, 777, 1, 3, 16, 0.1),     # M=48 -> two row tiles
+    (512, 2049, 2, 6, 8, 0.2),     # M=96 -> three row tiles; V = 8 tiles + 1 row
+    (256, 4096, 1, 8, 16, 0.1),    # M=128 exactly
+    (192, 1500, 3, 6, 8, 0.05),    # M=144 -> two row blocks of 128
+    (64, 300, 5, 7, 9, 0.5),       # M=315, one k slab only
+])
+@pytest.mark.parametrize("rule", [orc.RULE_ANY, orc.RULE_MAJORITY])
+def test_bf16_mfma_matches_oracle(runner, d, V, B, T, K, p, rule):
+    wl, W, h, seeds, draft = _problem("s", d, V, "bf16", B, T, K, p, seed=d + V, bonus=True)
+    prm, _ = runner.params(wl, seeds)
+    assert dmb.dm_kernel_choice(prm) == 1
+    ref = orc.verify(h, W, draft, seeds, K, p, rule=rule)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    res = runner.verify(wl, hd, Wd, draft, seeds, rule=rule)
+    _check_against_oracle(res, ref, draft, rule, label=f"mfma d={d} V={V} M={B*T*K}")
+    # the generic kernel on the same bf16 inputs
+    gen = runner.verify(wl, hd, Wd, draft, seeds, rule=rule, flags=dmb.DM_FLAG_FORCE_GENERIC)
+    _check_against_oracle(gen, ref, draft, rule, label=f"generic d={d} V={V}")
+
+
+@pytest.mark.parametrize("d,V", [(100, 130), (37, 65), (8, 3)])
+def test_generic_odd_shapes(runner, d, V):
+    for dtype in ("f32", "bf16"):
+        wl, W, h, seeds, draft = _problem("o", d, V, dtype, 2, 4, 6, 0.25, seed=d * V)
+        prm, _ = runner.params(wl, seeds)
+        assert dmb.dm_kernel_choice(prm) == 0
+        ref = orc.verify(h, W, draft, seeds, wl.K, wl.p)
+        res = runner.verify(wl, to_device(h, dtype), to_device(W, dtype), draft, seeds)
+        _check_against_oracle(res, ref, draft, orc.RULE_ANY, label=f"generic {dtype} d={d} V={V}")
+
+
+def test_logits_values_mfma_and_generic(runner):
+    wl, W, h, seeds, draft = _problem("l", 512, 1200, "bf16", 2, 4, 8, 0.1, seed=5)
+    v0, v1 = 250, 1200      # crosses tile borders, ends at the ragged tail
+    ref = orc.verify(h, W, draft, seeds, wl.K, wl.p, want_logits=(v0, v1))["logits"]
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    for flags in (0, dmb.DM_FLAG_FORCE_GENERIC):
+        got = runner.logits(wl, hd, Wd, seeds, v0, v1, flags=flags)
+        assert got.shape == ref.shape and np.isfinite(got).all()
+        err = np.abs(got - ref).max()
+        print(f"logits max abs err (flags={flags}): {err:.3e}", flush=True)
+        assert err < 2e-2
+
+
+def test_logits_exact_on_integer_inputs(runner):
+    # small integers: every product and partial sum is exact in bf16/fp32, so with p = 0.5
+    # (scale exactly 2) the accumulator must equal the fp64 oracle bit for bit
+    rng = np.random.default_rng(3)
+    wl = wk.Workload("int", d=128, V=520, dtype="bf16", B=1, T=4, K=8, p=0.5)
+    h = rng.integers(-4, 5, size=(1, 4, 128)).astype(np.float32)
+    W = rng.integers(-3, 4, size=(520, 128)).astype(np.float32)
+    seeds = np.array([11], dtype=np.uint64)
+    ref = orc.verify(h, W, np.zeros((1, 4), int), seeds, wl.K, wl.p, want_logits=(0, 520))
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    for flags in (0, dmb.DM_FLAG_FORCE_GENERIC):
+        got = runner.logits(wl, hd, Wd, seeds, 0, 520, flags=flags)
+        assert np.array_equal(got.astype(np.float64), ref["logits"])
+    res = runner.verify(wl, hd, Wd, np.zeros((1, 4), np.int32), seeds)
+    assert np.array_equal(res["path_ids"], ref["path_ids"])      # exact ties resolve to the smallest index
+
+
+# ------------------------------------------------------------------ fixed points on the GPU path
+def test_p_zero_is_greedy_verification(runner):
+    wl, W, h, seeds, _ = _problem("g", 256, 3000, "bf16", 2, 6, 8, 0.0, seed=9)
+    greedy = orc.greedy_ids(h, W)
+    draft = greedy.copy()
+    draft[0, 4] = (draft[0, 4] + 1) % wl.V
+    res = runner.verify(wl, to_device(h, "bf16"), to_device(W, "bf16"), draft, seeds)
+    assert (res["path_ids"] == greedy[:, :, None]).all()
+    assert (res["vote_cnt"] == wl.K).all() and res["accept_len"].tolist() == [4, 6]
+
+
+def test_share_mask_flag_and_step(runner):
+    wl, W, h, seeds, draft = _problem("f", 256, 1500, "bf16", 2, 5, 6, 0.3, seed=21)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    for step, share in ((0, True), (5, False), (5, True)):
+        ref = orc.verify(h, W, draft, seeds, wl.K, wl.p, step=step, share_mask_across_pos=share)
+        res = runner.verify(wl, hd, Wd, draft, seeds, step=step,
+                            flags=dmb.DM_FLAG_SHARE_MASK_ACROSS_POS if share else 0)
+        _check_against_oracle(res, ref, draft, orc.RULE_ANY, label=f"step={step} share={share}")
+
+
+def test_tree_mode_matches_oracle(runner):
+    wl = wk.Workload("t", d=256, V=2000, dtype="bf16", B=3, T=24, K=5, p=0.1, tree=True, data_seed=31)
+    W, h, seeds = wk.make_weight(wl), wk.make_hidden(wl), wk.make_seeds(wl, 2)
+    parent = wk.make_tree_parents(wl, max_depth=5, max_branch=3)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    # plant tokens that some path of the parent row produces, so that deep nodes get accepted
+    paths = orc.verify(h, W, np.zeros((wl.B, wl.T), int), seeds, wl.K, wl.p)["path_ids"]
+    rng = np.random.default_rng(4)
+    draft = wk.make_tree_draft_ids(wl, parent, orc.greedy_ids(h, W))
+    for b in range(wl.B):
+        for n in range(1, wl.T):
+            if rng.random() < 0.6:
+                draft[b, n] = paths[b, parent[b, n], rng.integers(0, wl.K)]
+    for rule in (orc.RULE_ANY, orc.RULE_MAJORITY):
+        ref = orc.verify(h, W, draft, seeds, wl.K, wl.p, rule=rule, parent=parent)
+        res = runner.verify(wl, hd, Wd, draft, seeds, rule=rule, parent=parent)
+        _check_against_oracle(res, ref, draft, rule, parent=parent, label=f"tree rule={rule}")
+        assert ref["accept_len"].max() >= 2
+    # a broken parent index rejects the node instead of reading out of bounds
+    bad = parent.copy()
+    bad[0, 5] = 7
+    res = runner.verify(wl, hd, Wd, draft, seeds, parent=bad)
+    assert res["hit"][0, 5] == 0 and res["accept_mask"][0, 5] == 0
+
+
+def test_chain_equals_degenerate_tree_on_gpu(runner):
+    wl, W, h, seeds, draft = _problem("c", 256, 1200, "bf16", 2, 7, 6, 0.05, seed=41, bonus=True)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    chain = runner.verify(wl, hd, Wd, draft, seeds)
+    parent, tdraft = wk.chain_as_tree(draft)
+    tree = runner.verify(wl, hd, Wd, tdraft, seeds, parent=parent)
+    assert np.array_equal(chain["path_ids"], tree["path_ids"])
+    assert np.array_equal(chain["accept_len"], tree["accept_len"])
+
+
+def test_determinism_and_optional_outputs(runner):
+    wl, W, h, seeds, draft = _problem("r", 512, 5000, "bf16", 1, 8, 16, 0.1, seed=51, bonus=True)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    first = runner.verify(wl, hd, Wd, draft, seeds)
+    for _ in range(5):
+        again = runner.verify(wl, hd, Wd, draft, seeds)
+        for k in first:
+            assert np.array_equal(first[k], again[k])
+    # only the required output
+    prm, keep = runner.params(wl, seeds)
+    al = torch.full((wl.B,), -7, dtype=torch.int32, device="cuda")
+    dmb.dropmatch_verify(runner.ctx, prm, hd, Wd, torch.from_numpy(draft).cuda(), al)
+    torch.cuda.synchronize()
+    assert np.array_equal(al.cpu().numpy(), first["accept_len"])
+
+
+def test_works_on_a_side_stream(runner):
+    wl, W, h, seeds, draft = _problem("st", 256, 1000, "bf16", 1, 4, 8, 0.1, seed=61)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    want = runner.verify(wl, hd, Wd, draft, seeds)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        got = runner.verify(wl, hd, Wd, draft, seeds)
+    for k in want:
+        assert np.array_equal(want[k], got[k])
+
+
+def test_argument_errors_enqueue_nothing(runner):
+    wl, W, h, seeds, draft = _problem("e", 64, 100, "bf16", 1, 2, 2, 0.1, seed=71)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    al = torch.zeros(1, dtype=torch.int32, device="cuda")
+    dr = torch.from_numpy(draft).cuda()
+    cases = [dict(p=1.0), dict(p=-0.1), dict(K=0), dict(rule=5), dict(flags=64)]
+    for kw in cases:
+        prm, keep = runner.params(wl, seeds, **{k: v for k, v in kw.items() if k != "K"}, K=kw.get("K"))
+        if "K" in kw:
+            prm.K = kw["K"]
+        with pytest.raises(dmb.DropMatchError) as ei:
+            dmb.dropmatch_verify(runner.ctx, prm, hd, Wd, dr, al)
+        assert ei.value.status == dmb.DM_EINVAL and ei.value.message
+    big = wk.Workload("big", d=64, V=100, dtype="bf16", B=1, T=64, K=128, p=0.1)   # 8192 rows > max_rows
+    prm, keep = runner.params(big, [0])
+    with pytest.raises(dmb.DropMatchError):
+        dmb.dropmatch_verify(runner.ctx, prm, hd, Wd, dr, al)
+    prm, keep = runner.params(wl, seeds)
+    with pytest.raises(dmb.DropMatchError):
+        dmb.dropmatch_verify(runner.ctx, prm, None, Wd, dr, al)
+    torch.cuda.synchronize()
