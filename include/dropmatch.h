@@ -152,6 +152,17 @@ dm_status dm_debug_masks(dm_ctx* ctx, const dm_params* prm, uint32_t* bits, void
 dm_status dm_debug_logits(dm_ctx* ctx, const dm_params* prm, const void* h, const void* W,
                           int32_t v0, int32_t v1, float* logits, void* stream);
 
+/* Measurement aid.  dm_set_profiling(ctx, 1) makes every following dropmatch_verify record HIP
+ * events on its stream before and after each of its three kernels (mask rows, LM-head
+ * contraction + argmax, vote/accept); events are created here, not in dropmatch_verify.  At
+ * most DM_PROFILE_MAX_CALLS calls are kept (later ones are not recorded).
+ * dm_get_profile waits for the last recorded event and returns the number of recorded calls
+ * and the mean duration of each kernel in milliseconds (any output pointer may be NULL);
+ * dm_set_profiling(ctx, 0) stops recording and forgets the samples. */
+#define DM_PROFILE_MAX_CALLS 512
+dm_status dm_set_profiling(dm_ctx* ctx, int32_t enabled);
+dm_status dm_get_profile(dm_ctx* ctx, int32_t* n_calls, float* ms_mask, float* ms_lmhead, float* ms_vote);
+
 /* Which contraction kernel a parameter block selects: 0 = generic fp32-FMA tiles (any
  * shape, f32 or bf16), 1 = bf16 MFMA kernel (bf16, d % 64 == 0).  Negative = dm_status. */
 int32_t dm_kernel_choice(const dm_params* prm);

@@ -20,7 +20,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdropmatch.so")
 
 EXPORTS = ("dm_create", "dm_destroy", "dm_last_error", "dm_validate", "dropmatch_verify",
-           "dm_debug_masks", "dm_debug_logits", "dm_kernel_choice")
+           "dm_debug_masks", "dm_debug_logits", "dm_kernel_choice", "dm_set_profiling", "dm_get_profile")
 
 
 class dm_params(C.Structure):
@@ -68,6 +68,10 @@ def load_library():
     lib.dm_debug_masks.restype = C.c_int
     lib.dm_debug_logits.argtypes = [vp, C.POINTER(dm_params), vp, vp, i32, i32, vp, vp]
     lib.dm_debug_logits.restype = C.c_int
+    lib.dm_set_profiling.argtypes = [vp, i32]
+    lib.dm_set_profiling.restype = C.c_int
+    lib.dm_get_profile.argtypes = [vp, C.POINTER(i32)] + [C.POINTER(C.c_float)] * 3
+    lib.dm_get_profile.restype = C.c_int
     _lib = lib
     return lib
 
@@ -143,3 +147,15 @@ def dm_debug_logits(ctx, prm: dm_params, h, W, v0: int, v1: int, logits, stream=
     st = load_library().dm_debug_logits(ctx, C.byref(prm), _ptr(h), _ptr(W), v0, v1, _ptr(logits),
                                         _stream_handle(stream))
     _check(ctx, st)
+
+
+def dm_set_profiling(ctx, enabled: bool) -> None:
+    _check(ctx, load_library().dm_set_profiling(ctx, 1 if enabled else 0))
+
+
+def dm_get_profile(ctx):
+    """Returns (n_calls, ms_mask, ms_lmhead, ms_vote): mean kernel durations from HIP events."""
+    n = C.c_int32()
+    a, b, c = C.c_float(), C.c_float(), C.c_float()
+    _check(ctx, load_library().dm_get_profile(ctx, C.byref(n), C.byref(a), C.byref(b), C.byref(c)))
+    return n.value, a.value, b.value, c.value

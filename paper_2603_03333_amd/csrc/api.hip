@@ -19,6 +19,10 @@ struct dm_ctx {
   void* a_ws = nullptr;               // masked rows
   unsigned long long* keys = nullptr; // packed (logit, index) argmax per row
   char err[512] = {0};
+  // measurement aid: 4 events per recorded call
+  hipEvent_t* ev = nullptr;
+  int prof_enabled = 0;
+  int prof_calls = 0;
 };
 
 namespace {
@@ -107,18 +111,30 @@ struct DeviceGuard {
 };
 
 // Eq. (1)-(3) + argmax keys; shared by dropmatch_verify and dm_debug_logits.
+// `ev` (optional): 3 events recorded before the mask kernel, between the two kernels, after.
 dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g, bool mfma, const void* h,
-                          const void* W, float* logits, int v0, int v1, hipStream_t s) {
+                          const void* W, float* logits, int v0, int v1, hipStream_t s, hipEvent_t* ev = nullptr) {
   const bool bf16 = p->dtype == DM_BF16;
+  if (ev) (void)hipEventRecord(ev[0], s);
   hipError_t e = dm::launch_mask_rows(h, ctx->a_ws, ctx->keys, p->seeds, g, bf16, mfma, s);
   if (e != hipSuccess) return fail_hip(ctx, "mask_rows launch", e);
+  if (ev) (void)hipEventRecord(ev[1], s);
   const float scale = (float)(1.0 / (1.0 - (double)p->p));
   if (mfma)
     e = dm::launch_lmhead_mfma(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, s);
   else
     e = dm::launch_lmhead_generic(W, ctx->a_ws, ctx->keys, g, p->V, bf16, logits, v0, v1, scale, s);
   if (e != hipSuccess) return fail_hip(ctx, "lmhead launch", e);
+  if (ev) (void)hipEventRecord(ev[2], s);
   return DM_OK;
+}
+
+void drop_events(dm_ctx* ctx) {
+  if (!ctx->ev) return;
+  for (int i = 0; i < 4 * DM_PROFILE_MAX_CALLS; ++i)
+    if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
+  delete[] ctx->ev;
+  ctx->ev = nullptr;
 }
 
 }  // namespace
@@ -188,6 +204,7 @@ dm_status dm_destroy(dm_ctx* ctx) {
   DeviceGuard guard(ctx->device);
   dm_status st = DM_OK;
   if (!guard.ok || hipDeviceSynchronize() != hipSuccess) st = fail(nullptr, DM_EHIP, "device synchronisation failed in dm_destroy");
+  drop_events(ctx);
   if (ctx->a_ws) (void)hipFree(ctx->a_ws);
   if (ctx->keys) (void)hipFree(ctx->keys);
   delete ctx;
@@ -209,10 +226,62 @@ dm_status dropmatch_verify(dm_ctx* ctx, const dm_params* prm, const void* h, con
   if (!guard.ok) return fail(ctx, DM_EHIP, "cannot select device %d", ctx->device);
   hipStream_t s = static_cast<hipStream_t>(stream);
 
-  if (dm_status st = run_contraction(ctx, prm, g, mfma, h, W, nullptr, 0, 0, s)) return st;
+  hipEvent_t* ev = nullptr;
+  if (ctx->prof_enabled && ctx->ev && ctx->prof_calls < DM_PROFILE_MAX_CALLS) ev = ctx->ev + 4 * ctx->prof_calls;
+  if (dm_status st = run_contraction(ctx, prm, g, mfma, h, W, nullptr, 0, 0, s, ev)) return st;
   dm::VoteOut out{accept_len, best_node, accept_mask, hit, path_ids, vote_ids, vote_cnt};
   hipError_t e = dm::launch_vote_accept(ctx->keys, draft_ids, prm->parent, prm->B, prm->T, prm->K, prm->rule, out, s);
   if (e != hipSuccess) return fail_hip(ctx, "vote_accept launch", e);
+  if (ev) {
+    (void)hipEventRecord(ev[3], s);
+    ++ctx->prof_calls;
+  }
+  return DM_OK;
+}
+
+dm_status dm_set_profiling(dm_ctx* ctx, int32_t enabled) {
+  if (!ctx) return fail(nullptr, DM_EINVAL, "ctx is NULL");
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return fail(ctx, DM_EHIP, "cannot select device %d", ctx->device);
+  ctx->prof_calls = 0;
+  ctx->prof_enabled = 0;
+  if (!enabled) return DM_OK;
+  if (!ctx->ev) {
+    ctx->ev = new (std::nothrow) hipEvent_t[4 * DM_PROFILE_MAX_CALLS]();
+    if (!ctx->ev) return fail(ctx, DM_ENOMEM, "host allocation failed");
+    for (int i = 0; i < 4 * DM_PROFILE_MAX_CALLS; ++i) {
+      const hipError_t e = hipEventCreate(&ctx->ev[i]);
+      if (e != hipSuccess) {
+        drop_events(ctx);
+        return fail_hip(ctx, "hipEventCreate", e);
+      }
+    }
+  }
+  ctx->prof_enabled = 1;
+  return DM_OK;
+}
+
+dm_status dm_get_profile(dm_ctx* ctx, int32_t* n_calls, float* ms_mask, float* ms_lmhead, float* ms_vote) {
+  if (!ctx) return fail(nullptr, DM_EINVAL, "ctx is NULL");
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return fail(ctx, DM_EHIP, "cannot select device %d", ctx->device);
+  const int n = ctx->prof_calls;
+  double sum[3] = {0, 0, 0};
+  if (n > 0) {
+    hipError_t e = hipEventSynchronize(ctx->ev[4 * (n - 1) + 3]);
+    if (e != hipSuccess) return fail_hip(ctx, "hipEventSynchronize", e);
+    for (int c = 0; c < n; ++c)
+      for (int k = 0; k < 3; ++k) {
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, ctx->ev[4 * c + k], ctx->ev[4 * c + k + 1]);
+        if (e != hipSuccess) return fail_hip(ctx, "hipEventElapsedTime", e);
+        sum[k] += ms;
+      }
+  }
+  if (n_calls) *n_calls = n;
+  if (ms_mask) *ms_mask = n ? (float)(sum[0] / n) : 0.f;
+  if (ms_lmhead) *ms_lmhead = n ? (float)(sum[1] / n) : 0.f;
+  if (ms_vote) *ms_vote = n ? (float)(sum[2] / n) : 0.f;
   return DM_OK;
 }
 

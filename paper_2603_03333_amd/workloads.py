@@ -77,6 +77,14 @@ def round_to_bf16(x: np.ndarray) -> np.ndarray:
     return bf16_to_f32(bf16_bits(x))
 
 
+def _round_to_bf16_inplace(x: np.ndarray) -> None:
+    u = x.view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    u += np.uint32(0x7FFF)
+    u += lsb
+    u &= np.uint32(0xFFFF0000)
+
+
 def _store(x: np.ndarray, dtype: str) -> np.ndarray:
     if dtype == "bf16":
         return round_to_bf16(x)
@@ -90,10 +98,18 @@ def _store(x: np.ndarray, dtype: str) -> np.ndarray:
 # --------------------------------------------------------------------------- #
 def make_weight(wl: Workload, sigma: float = 0.02) -> np.ndarray:
     """W[V, d] ~ N(0, sigma) as float32 holding values of the storage dtype."""
+    if wl.dtype not in ("bf16", "f32"):
+        raise ValueError(wl.dtype)
     rng = np.random.Generator(np.random.PCG64(wl.data_seed))
-    W = rng.standard_normal((wl.V, wl.d), dtype=np.float32)
-    W *= np.float32(sigma)
-    return _store(W, wl.dtype)
+    W = np.empty((wl.V, wl.d), dtype=np.float32)
+    step = 8192                      # row blocks: one sequential stream, no large temporaries
+    for r0 in range(0, wl.V, step):
+        blk = W[r0:r0 + step]
+        rng.standard_normal(out=blk, dtype=np.float32)
+        blk *= np.float32(sigma)
+        if wl.dtype == "bf16":
+            _round_to_bf16_inplace(blk)
+    return W
 
 
 def make_hidden(wl: Workload) -> np.ndarray:
