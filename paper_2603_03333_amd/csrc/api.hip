@@ -14,7 +14,7 @@ struct dm_ctx {
   int num_cu = 0;
   int64_t max_rows = 0;
   int32_t max_d = 0, max_V = 0;
-  int64_t rows_pad = 0;  // max_rows rounded up to 128
+  int64_t rows_pad = 0;  // max_rows rounded up to 256
   int32_t d_pad = 0;     // max_d rounded up to 64
   void* a_ws = nullptr;               // masked rows
   unsigned long long* keys = nullptr; // packed (logit, index) argmax per row
@@ -88,8 +88,8 @@ dm_status make_geom(dm_ctx* ctx, const dm_params* p, bool mfma, dm::RowGeom* g) 
   g->K = p->K;
   g->d = p->d;
   g->M = M;
-  // MFMA kernel: 32-row tiles, up to four per workgroup; beyond 128 rows whole groups of four
-  g->M_pad = mfma ? (M <= 128 ? round_up(M, 32) : round_up(M, 128)) : round_up(M, 128);
+  // MFMA kernels: up to 128 rows in 32-row tiles, beyond that in 256-row tiles
+  g->M_pad = mfma ? (M <= 128 ? round_up(M, 32) : round_up(M, 256)) : round_up(M, 128);
   g->d_pad = (int)round_up(p->d, 64);
   g->thr = (uint32_t)std::floor((double)p->p * 4294967296.0);
   g->step = p->step;
@@ -120,8 +120,10 @@ dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g,
   if (e != hipSuccess) return fail_hip(ctx, "mask_rows launch", e);
   if (ev) (void)hipEventRecord(ev[1], s);
   const float scale = (float)(1.0 / (1.0 - (double)p->p));
-  if (mfma)
+  if (mfma && g.M <= 128)
     e = dm::launch_lmhead_mfma(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, s);
+  else if (mfma)
+    e = dm::launch_lmhead_mfma_big(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, s);
   else
     e = dm::launch_lmhead_generic(W, ctx->a_ws, ctx->keys, g, p->V, bf16, logits, v0, v1, scale, s);
   if (e != hipSuccess) return fail_hip(ctx, "lmhead launch", e);
@@ -179,7 +181,7 @@ dm_status dm_create(dm_ctx** out, int device, int64_t max_rows, int32_t max_d, i
   ctx->max_rows = max_rows;
   ctx->max_d = max_d;
   ctx->max_V = max_V;
-  ctx->rows_pad = round_up(max_rows, 128);
+  ctx->rows_pad = round_up(max_rows, 256);
   ctx->d_pad = (int32_t)round_up(max_d, 64);
   const size_t a_bytes = (size_t)ctx->rows_pad * (size_t)ctx->d_pad * 4;
   if ((e = hipMalloc(&ctx->a_ws, a_bytes)) != hipSuccess ||
@@ -189,7 +191,8 @@ dm_status dm_create(dm_ctx** out, int device, int64_t max_rows, int32_t max_d, i
     delete ctx;
     return fail(nullptr, DM_ENOMEM, "workspace allocation of %zu bytes failed: %s", a_bytes, hipGetErrorString(e));
   }
-  if ((e = dm::prepare_lmhead_mfma()) != hipSuccess || (e = dm::prepare_vote_accept()) != hipSuccess) {
+  if ((e = dm::prepare_lmhead_mfma()) != hipSuccess || (e = dm::prepare_lmhead_mfma_big()) != hipSuccess ||
+      (e = dm::prepare_vote_accept()) != hipSuccess) {
     (void)hipFree(ctx->a_ws);
     (void)hipFree(ctx->keys);
     delete ctx;

@@ -43,6 +43,12 @@ hipError_t launch_lmhead_mfma(const void* W, const void* a_ws, unsigned long lon
                               hipStream_t stream);
 hipError_t prepare_lmhead_mfma();  // raises the dynamic-LDS limit of the kernels once per process
 
+// Same contract for more than 128 masked rows (256 x 256 tiles); needs M_pad % 256 == 0.
+hipError_t launch_lmhead_mfma_big(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g,
+                                  int V, int num_cu, float* logits, int v0, int v1, float scale,
+                                  hipStream_t stream);
+hipError_t prepare_lmhead_mfma_big();
+
 // Eq. (4)/(7), prefix / tree rule.  One workgroup per sequence.
 struct VoteOut {
   int32_t* accept_len;

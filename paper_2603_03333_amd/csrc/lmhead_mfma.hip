@@ -96,28 +96,51 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
     const int p = wave - 4;
     const int ld_row = lane >> 3;   // row (8*rb + lane/8) of this producer's 64, 16-byte piece lane%8
     const int ld_slot = lane & 7;
+    // Addresses are "uniform 64-bit base + 32-bit lane offset": the lane offsets are fixed for the
+    // whole kernel, the bases are scalar arithmetic, so a copy costs the producer no vector ALU work.
+    uint32_t woff[8];
+#pragma unroll
+    for (int rb = 0; rb < 8; ++rb) {
+      const int row = 8 * rb + ld_row;
+      const int piece = ld_slot ^ ((row >> 1) & 7);
+      woff[rb] = (uint32_t)row * (uint32_t)(2 * d) + (uint32_t)piece * 16u;
+    }
+    const uint32_t aoff = (uint32_t)lane * 16u;
+    const char* Wb = reinterpret_cast<const char*>(W);
+    const char* Ab = reinterpret_cast<const char*>(A_sw);
     auto issue = [&](int q) {
       const int n = q / nchunks;
       int c = q - n * nchunks + rot;
       c = c >= nchunks ? c - nchunks : c;
-      const int v0 = row_begin + n * BN;
+      const int v0 = row_begin + n * BN + 64 * p;  // first vocabulary row of this producer's 64
       unsigned char* stage = lds + (q % NS) * SLAB;
+      const char* wsrc = Wb + ((int64_t)v0 * d + (int64_t)c * BK) * 2;
+      if (v0 + 64 <= row_end) {
 #pragma unroll
-      for (int rb = 0; rb < 8; ++rb) {
-        const int row = 8 * rb + ld_row;
-        int vrow = v0 + 64 * p + row;
-        vrow = vrow < row_end ? vrow : row_end - 1;  // partial tile: re-read an own row, masked out later
-        const int piece = ld_slot ^ ((row >> 1) & 7);
-        const __bf16* src = W + (int64_t)vrow * d + c * BK + piece * 8;
-        __builtin_amdgcn_global_load_lds(DM_GLOBAL_PTR(src), DM_LDS_PTR(stage + p * 8192 + rb * 1024), 16, 0, 0);
+        for (int rb = 0; rb < 8; ++rb) {
+          uint32_t off = woff[rb];
+          asm volatile("" : "+v"(off));  // keep the 32-bit offset form: "scalar base + lane offset" addressing
+          __builtin_amdgcn_global_load_lds(DM_GLOBAL_PTR(wsrc + off), DM_LDS_PTR(stage + p * 8192 + rb * 1024), 16, 0,
+                                           0);
+        }
+      } else {  // partial tile: rows past the end re-read an own row, masked out later
+#pragma unroll
+        for (int rb = 0; rb < 8; ++rb) {
+          const int row = 8 * rb + ld_row;
+          const int vrow = (v0 + row < row_end) ? v0 + row : row_end - 1;
+          const int piece = ld_slot ^ ((row >> 1) & 7);
+          const __bf16* src = W + (int64_t)vrow * d + c * BK + piece * 8;
+          __builtin_amdgcn_global_load_lds(DM_GLOBAL_PTR(src), DM_LDS_PTR(stage + p * 8192 + rb * 1024), 16, 0, 0);
+        }
       }
+      const char* asrc = Ab + ((int64_t)(c * 4) * mt_total + mblk * MT) * 1024;
 #pragma unroll
       for (int x = 0; x < MT; ++x) {
         const int f = p + 4 * x;  // fragment index inside the slab: f = s * MT + mt
         const int s = f / MT;
         const int mt = f - s * MT;
-        const __bf16* src = A_sw + ((((int64_t)(c * 4 + s) * mt_total + mblk * MT + mt) * 64) + lane) * 8;
-        __builtin_amdgcn_global_load_lds(DM_GLOBAL_PTR(src), DM_LDS_PTR(stage + W_SLAB_BYTES + f * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(DM_GLOBAL_PTR(asrc + ((int64_t)s * mt_total + mt) * 1024 + aoff),
+                                         DM_LDS_PTR(stage + W_SLAB_BYTES + f * 1024), 16, 0, 0);
       }
     };
     if (total > 0) issue(0);

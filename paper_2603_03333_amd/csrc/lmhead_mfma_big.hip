@@ -1,0 +1,388 @@
+// Eq. (3) l = W h^(i) with a fused per-row argmax on the gfx950 matrix cores, for more than
+// 128 masked rows (the MFMA-bound regime: batches of sequences, draft trees).
+//
+// Same operand roles as the small-row kernel (W rows = MFMA "A" operand, masked rows = "B"
+// operand, so a lane owns one masked row and the vocabulary argmax is a per-lane compare),
+// but a 256 x 256 output tile per workgroup: at 256 x 128 a CU needs 47 B/clk from L2 to keep
+// its matrix cores busy, which the L2 fabric does not deliver to 256 CUs at once (measured:
+// 39 % of MFMA peak); 256 x 256 halves that.
+//
+// Workgroup = 768 threads = 12 wavefronts, three per SIMD:
+//   * 8 consumers: wavefront (wv, wm) owns vocabulary rows [64 wv, +64) x masked rows
+//     [128 wm, +128) of the tile: 2 x 4 accumulator tiles (128 VGPRs);
+//   * 4 producers: global -> LDS copies by LDS-DMA, so that a full memory queue stalls a
+//     producer and not the MFMA stream.
+// k advances in slabs of BK; NS slabs live in LDS (BK = 64: 2 x 64 KB, BK = 32: 4 x 32 KB).
+// W rows are stored in LDS with their 16-byte pieces XOR-swizzled by the row number so that
+// the MFMA fragment reads (32 rows, same piece) are bank-conflict free; masked rows arrive in
+// fragment order from the mask kernel.
+//
+// Tile order.  Workgroups are persistent; in one "round" the grid covers a block of
+// BVc x BMc tiles (BMc <= 16 row tiles wide).  Workgroup ids are dealt round-robin to the 8
+// XCDs, each with its own L2, so the 32 workgroups of an XCD take a compact patch of
+// sv x sm tiles (sm <= 4): a slab of masked rows is fetched into that L2 once per sv
+// workgroups and a slab of W once per sm workgroups.  Rounds sweep the vocabulary first, so
+// across the chip W streams from HBM once per sweep of up to 16 row tiles.
+#include "kernels.hpp"
+
+namespace dm {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BN = 256;  // vocabulary rows per tile
+constexpr int BM = 256;  // masked rows per tile
+constexpr int THREADS = 768;
+
+template <int BK>
+struct Cfg {
+  static constexpr int NS = (BK == 64) ? 2 : 4;        // slabs resident in LDS
+  static constexpr int PR = BK / 8;                    // 16-byte pieces per W row per slab
+  static constexpr int KSTEPS = BK / 16;               // MFMA k-steps per slab
+  static constexpr int ROW_BYTES = BK * 2;
+  static constexpr int W_SLAB = BN * ROW_BYTES;
+  static constexpr int A_SLAB = BM * ROW_BYTES;
+  static constexpr int SLAB = W_SLAB + A_SLAB;
+  static constexpr int W_INSTR = (64 * ROW_BYTES) / 1024;  // W copy instructions per producer per slab
+  static constexpr int A_INSTR = KSTEPS * 8 / 4;           // masked-row fragments per producer per slab
+  static constexpr int LOADS = W_INSTR + A_INSTR;
+  static constexpr int RED_BYTES = 4 * BM * 8;
+  static constexpr int LDS_BYTES = NS * SLAB + RED_BYTES;
+  static constexpr int SWZ_SHIFT = (BK == 64) ? 1 : 2;     // rows per 256-byte bank period: 2 or 4
+};
+
+#define DM_GLOBAL_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
+#define DM_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
+#define DM_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+#define DM_BARRIER()               \
+  do {                             \
+    asm volatile("" ::: "memory"); \
+    __builtin_amdgcn_s_barrier();  \
+    asm volatile("" ::: "memory"); \
+  } while (0)
+
+// How the persistent grid walks the NV x NMB tiles (filled on the host).
+struct TileWalk {
+  int NV, NMB;      // tiles along the vocabulary / along masked rows
+  int BVc, BMc;     // tiles covered by the whole grid in one round
+  int nvb, nmb;     // rounds along the vocabulary / along masked rows
+  int xcd_aware;    // deal compact sv x sm patches to the XCDs
+  int sv, sm, pm;   // patch shape, patches per block row
+};
+
+struct TilePos {
+  int dv, dm;
+  bool active;
+};
+
+__device__ __forceinline__ TilePos tile_pos(const TileWalk& w, int g) {
+  TilePos p;
+  if (w.xcd_aware) {
+    const int xcd = g & 7, slot = g >> 3;
+    const int pv = xcd / w.pm, pmi = xcd - pv * w.pm;
+    const int sl_v = slot / w.sm, sl_m = slot - sl_v * w.sm;
+    p.dv = pv * w.sv + sl_v;
+    p.dm = pmi * w.sm + sl_m;
+  } else {
+    p.dv = g / w.BMc;
+    p.dm = g - p.dv * w.BMc;
+  }
+  p.active = p.dv < w.BVc && p.dm < w.BMc;
+  return p;
+}
+
+// Tile of round `it` for a workgroup at block position p; false if it falls outside the problem.
+__device__ __forceinline__ bool tile_of(const TileWalk& w, const TilePos& p, int it, int& tv, int& tm) {
+  const int mB = it / w.nvb, vb = it - mB * w.nvb;
+  tv = vb * w.BVc + p.dv;
+  tm = mB * w.BMc + p.dm;
+  return p.active && tv < w.NV && tm < w.NMB;
+}
+
+template <int BK, bool DUMP>
+__global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf16* __restrict__ W,
+                                                                     const __bf16* __restrict__ A_sw,
+                                                                     unsigned long long* __restrict__ keys, int d,
+                                                                     int64_t M, int mt_total, int v_lo, int v_hi,
+                                                                     TileWalk walk, float* __restrict__ logits,
+                                                                     int dv0, int dv1, float scale) {
+  using C = Cfg<BK>;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nchunks = d / BK;
+  const TilePos pos = tile_pos(walk, (int)blockIdx.x);
+  const int nit = walk.nvb * walk.nmb;
+
+  int my_tiles = 0;
+  for (int it = 0; it < nit; ++it) {
+    int tv, tm;
+    my_tiles += tile_of(walk, pos, it, tv, tm) ? 1 : 0;
+  }
+  const int total = my_tiles * nchunks;
+  // k rotation: shared by the workgroups of one XCD (they reuse each other's slabs in L2 only if
+  // they want the same slab at about the same time), different between XCDs (so the XCDs do not
+  // all pull the same address bits, i.e. the same memory channels, at once)
+  const int rot = (int)(((blockIdx.x & 7u) * (unsigned)nchunks) / 8u);
+
+  if (wave >= 8) {
+    // ------------------------------------------------------------------ producer
+    __builtin_amdgcn_s_setprio(3);
+    const int p = wave - 8;
+    constexpr int RPI = 64 / C::PR;  // W rows per copy instruction
+    const int ld_row = lane / C::PR;
+    const int ld_slot = lane % C::PR;
+    // Addresses are "uniform 64-bit base + 32-bit lane offset": the lane offsets are fixed for the
+    // whole kernel, the bases are scalar arithmetic, so a copy costs the producer no vector ALU work.
+    uint32_t woff[C::W_INSTR];
+#pragma unroll
+    for (int rb = 0; rb < C::W_INSTR; ++rb) {
+      const int row = RPI * rb + ld_row;  // row inside this producer's 64
+      const int piece = ld_slot ^ ((row >> C::SWZ_SHIFT) & (C::PR - 1));
+      woff[rb] = (uint32_t)row * (uint32_t)(2 * d) + (uint32_t)piece * 16u;
+    }
+    const uint32_t aoff = (uint32_t)lane * 16u;
+    const char* Wb = reinterpret_cast<const char*>(W);
+    const char* Ab = reinterpret_cast<const char*>(A_sw);
+    int it_p = -1, c_p = nchunks, tv_p = 0, tm_p = 0;  // cursor of the next slab to issue
+    auto issue_next = [&](int q) {
+      if (c_p == nchunks) {  // move to the next tile of this workgroup
+        c_p = 0;
+        do {
+          ++it_p;
+        } while (!tile_of(walk, pos, it_p, tv_p, tm_p));
+      }
+      int c = c_p + rot;
+      c = c >= nchunks ? c - nchunks : c;
+      ++c_p;
+      const int v0 = v_lo + tv_p * BN + 64 * p;  // first vocabulary row of this producer's 64
+      unsigned char* stage = lds + (q % C::NS) * C::SLAB;
+      const char* wsrc = Wb + ((int64_t)v0 * d + (int64_t)c * BK) * 2;
+      if (v0 + 64 <= v_hi) {
+#pragma unroll
+        for (int rb = 0; rb < C::W_INSTR; ++rb) {
+          uint32_t off = woff[rb];
+          asm volatile("" : "+v"(off));  // keep the 32-bit offset form: "scalar base + lane offset" addressing
+          __builtin_amdgcn_global_load_lds(DM_GLOBAL_PTR(wsrc + off),
+                                           DM_LDS_PTR(stage + p * (64 * C::ROW_BYTES) + rb * 1024), 16, 0, 0);
+        }
+      } else {  // last vocabulary tile: rows past the end re-read the last row, masked out later
+#pragma unroll
+        for (int rb = 0; rb < C::W_INSTR; ++rb) {
+          const int row = RPI * rb + ld_row;
+          const int vrow = (v0 + row < v_hi) ? v0 + row : v_hi - 1;
+          const int piece = ld_slot ^ ((row >> C::SWZ_SHIFT) & (C::PR - 1));
+          const __bf16* src = W + (int64_t)vrow * d + c * BK + piece * 8;
+          __builtin_amdgcn_global_load_lds(DM_GLOBAL_PTR(src),
+                                           DM_LDS_PTR(stage + p * (64 * C::ROW_BYTES) + rb * 1024), 16, 0, 0);
+        }
+      }
+      const char* asrc = Ab + ((int64_t)(c * C::KSTEPS) * mt_total + tm_p * 8) * 1024;
+#pragma unroll
+      for (int x = 0; x < C::A_INSTR; ++x) {
+        const int f = p + 4 * x;  // fragment index inside the slab: f = s * 8 + mt
+        const int s = f >> 3, mt = f & 7;
+        __builtin_amdgcn_global_load_lds(DM_GLOBAL_PTR(asrc + ((int64_t)s * mt_total + mt) * 1024 + aoff),
+                                         DM_LDS_PTR(stage + C::W_SLAB + f * 1024), 16, 0, 0);
+      }
+    };
+    int issued = 0;
+    for (; issued < C::NS - 1 && issued < total; ++issued) issue_next(issued);
+    for (int q = 0; q < total; ++q) {
+      // own copies of slab q have landed; up to NS-2 younger slabs may still be in flight
+      const int younger = (total - 1 - q) < (C::NS - 2) ? (total - 1 - q) : (C::NS - 2);
+      if (younger >= 2) {
+        DM_WAIT_VMCNT(2 * C::LOADS);
+      } else if (younger == 1) {
+        DM_WAIT_VMCNT(C::LOADS);
+      } else {
+        DM_WAIT_VMCNT(0);
+      }
+      DM_BARRIER();  // slab q complete for everyone; slab q-1 consumed by everyone
+      if (issued < total) {
+        issue_next(issued);
+        ++issued;
+      }
+      if (!DUMP && (q % nchunks) == nchunks - 1) DM_BARRIER();  // pairs with the consumers' tile-end barrier
+    }
+    return;
+  }
+
+  // -------------------------------------------------------------------- consumer
+  const int wv = wave & 3, wm = wave >> 2;
+  const int i32 = lane & 31;
+  const int hb = lane >> 5;
+  const int swz = (i32 >> C::SWZ_SHIFT) & (C::PR - 1);
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mt][vt][r] = 0.f;
+
+  int it_c = -1, tv_c = 0, tm_c = 0;
+  for (int q = 0; q < total; ++q) {
+    DM_BARRIER();
+    const unsigned char* stage = lds + (q % C::NS) * C::SLAB;
+    const unsigned char* wbase = stage + wv * (64 * C::ROW_BYTES) + i32 * C::ROW_BYTES;
+    const unsigned char* abase = stage + C::W_SLAB + (4 * wm) * 1024 + lane * 16;
+#pragma unroll
+    for (int s = 0; s < C::KSTEPS; ++s) {
+      bf16x8 wf[2], af[4];
+#pragma unroll
+      for (int vt = 0; vt < 2; ++vt)
+        wf[vt] = *reinterpret_cast<const bf16x8*>(wbase + vt * (32 * C::ROW_BYTES) + 16 * ((2 * s + hb) ^ swz));
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) af[mt] = *reinterpret_cast<const bf16x8*>(abase + (s * 8 + mt) * 1024);
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int vt = 0; vt < 2; ++vt)
+          acc[mt][vt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[vt], af[mt], acc[mt][vt], 0, 0, 0);
+    }
+    asm volatile("" ::: "memory");
+
+    if ((q % nchunks) != nchunks - 1) continue;
+
+    // ---- tile finished ----
+    do {
+      ++it_c;
+    } while (!tile_of(walk, pos, it_c, tv_c, tm_c));
+    const int v0 = v_lo + tv_c * BN;
+    // accumulator (mt, vt, r): v = v0 + 64 wv + 32 vt + 8 (r/4) + 4 hb + r%4,  m = 256 tm + 128 wm + 32 mt + lane%32
+    if (DUMP) {
+      const int nv = dv1 - dv0;
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+        const int64_t m = (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32;
+#pragma unroll
+        for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int v = v0 + 64 * wv + 32 * vt + 8 * (r >> 2) + 4 * hb + (r & 3);
+            if (m < M && v >= dv0 && v < dv1 && v < v_hi) logits[m * nv + (v - dv0)] = scale * acc[mt][vt][r];
+            acc[mt][vt][r] = 0.f;
+          }
+      }
+      continue;
+    }
+
+    unsigned long long* red = reinterpret_cast<unsigned long long*>(lds + C::NS * C::SLAB);  // [4 wv][256 m]
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+      float best = -INFINITY;
+      uint32_t bv = 0xFFFFFFFFu;
+#pragma unroll
+      for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {  // ascending v for this lane: strict > keeps the smallest index
+          const int v = v0 + 64 * wv + 32 * vt + 8 * (r >> 2) + 4 * hb + (r & 3);
+          const float val = acc[mt][vt][r] + 0.0f;
+          if (v < v_hi && (bv == 0xFFFFFFFFu || val > best)) {
+            best = val;
+            bv = (uint32_t)v;
+          }
+          acc[mt][vt][r] = 0.f;
+        }
+      unsigned long long key = (bv == 0xFFFFFFFFu) ? 0ull : pack_key(best, bv);
+      const unsigned long long other = __shfl_xor(key, 32, 64);
+      key = other > key ? other : key;
+      if (hb == 0) red[wv * BM + wm * 128 + mt * 32 + i32] = key;
+    }
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    DM_BARRIER();
+    if (tid < BM) {
+      unsigned long long key = red[tid];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) {
+        const unsigned long long other = red[w * BM + tid];
+        key = other > key ? other : key;
+      }
+      const int64_t m = (int64_t)tm_c * BM + tid;
+      if (m < M && key != 0ull) atomicMax(&keys[m], key);
+    }
+  }
+}
+
+int pow2_at_most(int x) {
+  int p = 1;
+  while (2 * p <= x) p *= 2;
+  return p;
+}
+
+TileWalk make_walk(int NV, int NMB, int G) {
+  TileWalk w{};
+  w.NV = NV;
+  w.NMB = NMB;
+  int bmc = pow2_at_most(NMB < 16 ? NMB : 16);
+  if (bmc > G) bmc = pow2_at_most(G);
+  w.BMc = bmc;
+  w.xcd_aware = 0;
+  w.sv = w.sm = w.pm = 1;
+  if (G % 8 == 0) {
+    const int S = G / 8;
+    const int sm = bmc < 4 ? bmc : 4;
+    if (S % sm == 0) {
+      w.xcd_aware = 1;
+      w.sm = sm;
+      w.sv = S / sm;
+      w.pm = bmc / sm;
+      w.BVc = (8 / w.pm) * w.sv;
+    }
+  }
+  if (!w.xcd_aware) w.BVc = G / bmc;
+  w.nvb = (NV + w.BVc - 1) / w.BVc;
+  w.nmb = (NMB + w.BMc - 1) / w.BMc;
+  return w;
+}
+
+template <int BK>
+hipError_t run_big(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V, int num_cu,
+                   float* logits, int v0, int v1, float scale, hipStream_t stream) {
+  const bool dump = logits != nullptr;
+  const int v_lo = dump ? v0 : 0;
+  const int v_hi = dump ? v1 : V;
+  if (v_hi <= v_lo) return hipSuccess;
+  const int NV = (v_hi - v_lo + BN - 1) / BN;
+  const int NMB = (int)(g.M_pad / BM);
+  const int64_t ntiles = (int64_t)NV * NMB;
+  int G = ntiles < num_cu ? (int)ntiles : num_cu;
+  if (G >= 8) G -= G % 8;
+  const TileWalk walk = make_walk(NV, NMB, G);
+  const dim3 grid((unsigned)G), block(THREADS);
+  const int mt_total = (int)(g.M_pad >> 5);
+  if (dump)
+    lmhead_mfma_big_kernel<BK, true><<<grid, block, Cfg<BK>::LDS_BYTES, stream>>>(
+        static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo, v_hi, walk,
+        logits, v0, v1, scale);
+  else
+    lmhead_mfma_big_kernel<BK, false><<<grid, block, Cfg<BK>::LDS_BYTES, stream>>>(
+        static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo, v_hi, walk,
+        logits, v0, v1, scale);
+  return hipGetLastError();
+}
+
+constexpr int kBigBK = 64;
+
+}  // namespace
+
+hipError_t prepare_lmhead_mfma_big() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_mfma_big_kernel<kBigBK, false>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, Cfg<kBigBK>::LDS_BYTES);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_mfma_big_kernel<kBigBK, true>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, Cfg<kBigBK>::LDS_BYTES);
+}
+
+hipError_t launch_lmhead_mfma_big(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V,
+                                  int num_cu, float* logits, int v0, int v1, float scale, hipStream_t stream) {
+  if (g.M_pad % BM != 0) return hipErrorInvalidValue;
+  return run_big<kBigBK>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, stream);
+}
+
+}  // namespace dm

@@ -88,7 +88,9 @@ def test_tiny_config_fp32(runner):
     (512, 2049, 2, 6, 8, 0.2),     # M=96 -> three row tiles; V = 8 tiles + 1 row
     (256, 4096, 1, 8, 16, 0.1),    # M=128 exactly
     (192, 1500, 3, 6, 8, 0.05),    # M=144 -> two row blocks of 128
-    (64, 300, 5, 7, 9, 0.5),       # M=315, one k slab only
+    (64, 300, 5, 7, 9, 0.5),       # M=315, one k slab only; two 256-row tiles
+    (256, 3000, 4, 8, 20, 0.1),    # M=640 -> three 256-row tiles x 12 vocabulary tiles, several rounds
+    (128, 5000, 9, 8, 32, 0.2),    # M=2304 -> nine 256-row tiles
 ])
 @pytest.mark.parametrize("rule", [orc.RULE_ANY, orc.RULE_MAJORITY])
 def test_bf16_mfma_matches_oracle(runner, d, V, B, T, K, p, rule):
@@ -115,8 +117,9 @@ def test_generic_odd_shapes(runner, d, V):
         _check_against_oracle(res, ref, draft, orc.RULE_ANY, label=f"generic {dtype} d={d} V={V}")
 
 
-def test_logits_values_mfma_and_generic(runner):
-    wl, W, h, seeds, draft = _problem("l", 512, 1200, "bf16", 2, 4, 8, 0.1, seed=5)
+@pytest.mark.parametrize("B,T,K", [(2, 4, 8), (5, 8, 8)])      # 64 rows (small-row kernel), 320 rows (256-row tiles)
+def test_logits_values_mfma_and_generic(runner, B, T, K):
+    wl, W, h, seeds, draft = _problem("l", 512, 1200, "bf16", B, T, K, 0.1, seed=5)
     v0, v1 = 250, 1200      # crosses tile borders, ends at the ragged tail
     ref = orc.verify(h, W, draft, seeds, wl.K, wl.p, want_logits=(v0, v1))["logits"]
     hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
