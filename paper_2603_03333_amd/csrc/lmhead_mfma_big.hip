@@ -62,6 +62,20 @@ struct Cfg {
     asm volatile("" ::: "memory"); \
   } while (0)
 
+// One LDS-DMA copy instruction: every lane moves 16 bytes from (uniform base + its 32-bit offset)
+// to LDS address (uniform dst + 16 * lane).  Written out so that the address needs no vector ALU
+// instruction: producers share their SIMD with wavefronts that keep the vector ALU busy with MFMAs.
+__device__ __forceinline__ void dma_copy16(const char* base, uint32_t lane_off, unsigned char* lds_dst) {
+  const uint32_t dst = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_dst;
+  asm volatile(
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, %1"
+      :
+      : "v"(lane_off), "s"(base), "s"(dst)
+      : "memory", "m0");
+}
+
 // How the persistent grid walks the NV x NMB tiles (filled on the host).
 struct TileWalk {
   int NV, NMB;      // tiles along the vocabulary / along masked rows
@@ -162,12 +176,8 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
       const char* wsrc = Wb + ((int64_t)v0 * d + (int64_t)c * BK) * 2;
       if (v0 + 64 <= v_hi) {
 #pragma unroll
-        for (int rb = 0; rb < C::W_INSTR; ++rb) {
-          uint32_t off = woff[rb];
-          asm volatile("" : "+v"(off));  // keep the 32-bit offset form: "scalar base + lane offset" addressing
-          __builtin_amdgcn_global_load_lds(DM_GLOBAL_PTR(wsrc + off),
-                                           DM_LDS_PTR(stage + p * (64 * C::ROW_BYTES) + rb * 1024), 16, 0, 0);
-        }
+        for (int rb = 0; rb < C::W_INSTR; ++rb)
+          dma_copy16(wsrc, woff[rb], stage + p * (64 * C::ROW_BYTES) + rb * 1024);
       } else {  // last vocabulary tile: rows past the end re-read the last row, masked out later
 #pragma unroll
         for (int rb = 0; rb < C::W_INSTR; ++rb) {
@@ -184,8 +194,7 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
       for (int x = 0; x < C::A_INSTR; ++x) {
         const int f = p + 4 * x;  // fragment index inside the slab: f = s * 8 + mt
         const int s = f >> 3, mt = f & 7;
-        __builtin_amdgcn_global_load_lds(DM_GLOBAL_PTR(asrc + ((int64_t)s * mt_total + mt) * 1024 + aoff),
-                                         DM_LDS_PTR(stage + C::W_SLAB + f * 1024), 16, 0, 0);
+        dma_copy16(asrc + ((int64_t)s * mt_total + mt) * 1024, aoff, stage + C::W_SLAB + f * 1024);
       }
     };
     int issued = 0;
