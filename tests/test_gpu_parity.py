@@ -253,3 +253,50 @@ def test_argument_errors_enqueue_nothing(runner):
     with pytest.raises(dmb.DropMatchError):
         dmb.dropmatch_verify(runner.ctx, prm, None, Wd, dr, al)
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ edges of the shape space
+@pytest.mark.parametrize("d,V,B,T,K", [
+    (64, 1, 1, 1, 1),        # a single vocabulary row, a single path
+    (64, 31, 1, 2, 3),       # less than one MFMA tile of vocabulary rows
+    (128, 257, 1, 1, 128),   # exactly 128 rows, K larger than a wavefront
+    (128, 600, 1, 1, 129),   # 129 rows: first size served by the 256-row tiles
+    (64, 520, 1, 2, 128),    # exactly 256 rows
+    (64, 520, 1, 1, 257),    # 257 rows -> two row tiles, second almost empty
+    (64, 900, 2, 300, 1),    # many rows per sequence, one path each
+])
+def test_shape_edges(runner, d, V, B, T, K):
+    wl, W, h, seeds, draft = _problem("edge", d, V, "bf16", B, T, K, 0.2, seed=7 * d + V + K)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    for rule in (orc.RULE_ANY, orc.RULE_MAJORITY):
+        ref = orc.verify(h, W, draft, seeds, K, wl.p, rule=rule)
+        res = runner.verify(wl, hd, Wd, draft, seeds, rule=rule)
+        _check_against_oracle(res, ref, draft, rule, label=f"edge d={d} V={V} B={B} T={T} K={K} rule={rule}")
+
+
+def test_many_paths_vote(runner):
+    # K = 200 paths per row on a tiny vocabulary: many repeated tokens, modes with ties
+    wl, W, h, seeds, draft = _problem("vote", 64, 7, "bf16", 2, 3, 200, 0.5, seed=99)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    for rule in (orc.RULE_ANY, orc.RULE_MAJORITY):
+        ref = orc.verify(h, W, draft, seeds, 200, wl.p, rule=rule)
+        res = runner.verify(wl, hd, Wd, draft, seeds, rule=rule)
+        _check_against_oracle(res, ref, draft, rule, label=f"K=200 rule={rule}")
+    assert res["vote_cnt"].max() > 50
+
+
+def test_deep_chain_tree(runner):
+    # a tree that is one long path (every node's parent is its predecessor), T = 200 nodes
+    wl = wk.Workload("deep", d=64, V=50, dtype="bf16", B=2, T=200, K=4, p=0.1, tree=True, data_seed=5)
+    W, h, seeds = wk.make_weight(wl), wk.make_hidden(wl), wk.make_seeds(wl)
+    parent = np.tile(np.arange(-1, wl.T - 1, dtype=np.int32), (wl.B, 1))
+    paths = orc.verify(h, W, np.zeros((wl.B, wl.T), int), seeds, wl.K, wl.p)["path_ids"]
+    draft = np.full((wl.B, wl.T), -1, dtype=np.int32)
+    for b in range(wl.B):
+        for n in range(1, wl.T):
+            draft[b, n] = paths[b, n - 1, n % wl.K]
+    draft[0, 150] = 50          # sequence 0 breaks at depth 150
+    ref = orc.verify(h, W, draft, seeds, wl.K, wl.p, parent=parent)
+    res = runner.verify(wl, to_device(h, "bf16"), to_device(W, "bf16"), draft, seeds, parent=parent)
+    _check_against_oracle(res, ref, draft, orc.RULE_ANY, parent=parent, label="deep tree")
+    assert res["accept_len"].tolist() == [149, 199]
