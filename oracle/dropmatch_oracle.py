@@ -16,6 +16,11 @@ What the paper fixes (Methodology, "Multi-Sample LM Head via MC Dropout" and
   y_t^(i) = argmax_v l_t^(i)[v]                          (token of path i; softmax is monotone)
   Eq. (4)  naive token matching: accept iff draft token is in {y_t^(i)}
   Eq. (7)  majority rule: accept iff majority({y_t^(i)}) equals the draft token
+  Eq. (3)  p_t^(i) = Softmax(l_t^(i))                    (second half of Eq. (3))
+  Eq. (5)  centroid  pbar_t = Softmax((1/K) sum_i l_t^(i))   (mean of LOGITS, then softmax)
+  Eq. (6)  JS rule: accept iff JS(phat_t || pbar_t) <= max_i JS(p_t^(i) || pbar_t),
+           phat_t being the draft model's distribution at that position
+  Alg. 1   accept iff Eq. (6) holds, else iff Eq. (7) holds, else reject
   a rejected position rejects every later one; the count of accepted draft
   tokens is the acceptance length (Metrics paragraph, "Mean Acceptance Length").
 
@@ -31,6 +36,12 @@ listed with its reason in the design notes of the repository):
     tokens (the paper's agreement table lists majority sizes 1..5 for K = 5),
     ties between modes -> smallest token id;
   * draft id < 0 means "no draft token at this row" and never matches;
+  * Jensen-Shannon divergence (the paper names it without a formula): the standard
+    JS(P||Q) = KL(P||M)/2 + KL(Q||M)/2 with M = (P+Q)/2, natural logarithm,
+    0 log 0 = 0; the two sides of Eq. (6) are compared after rounding each to
+    float32 (the precision the HIP path reports them in);
+  * the JS rule and Alg. 1 are defined for chains only (the paper uses tree
+    decoding only together with naive token matching);
   * tree verification: parent[n] < n, node 0 is the root (always accepted); node n
     is accepted iff its parent is accepted and the rule holds for draft[n] against
     the K path tokens of row parent[n]; result = depth of the deepest accepted node.
@@ -41,6 +52,11 @@ arithmetic; keep-rate and E[h^(i)] = h statistics; p = 0 reducing to plain greed
 verification through a separate library matmul; hand-checkable integer cases by
 brute force in exact rational arithmetic; identical masks -> identical paths;
 rule set-relations; chain/tree equivalence; batch independence.
+JS part: JS against scipy's Jensen-Shannon distance and entropy routines, the
+closed form 3/4 ln(4/3), disjoint/identical supports, the centroid against a hand
+case where the mean of logits and the mean of probabilities differ, Alg. 1's
+truth table, K = 1 and p = 0 special cases, and the whole JS step against a
+separate scipy computation from the (separately pinned) path logits.
 Parity unpinned: nothing in this file.  (Task quality on real text - accuracy,
 acceptance length on benchmarks - is not computed here at all.)
 """
@@ -50,6 +66,8 @@ import numpy as np
 
 RULE_ANY = 0       # Eq. (4): draft token is one of the K path tokens
 RULE_MAJORITY = 1  # Eq. (7): draft token is the most frequent path token
+RULE_JS = 2           # Eq. (6) alone: draft distribution within the cluster of head distributions
+RULE_JS_OR_MAJORITY = 3  # Algorithm 1: Eq. (6), else Eq. (7)
 
 _PHILOX_M0 = np.uint64(0xD2511F53)
 _PHILOX_M1 = np.uint64(0xCD9E8D57)
@@ -207,6 +225,127 @@ def accept_tree(edge_hit, parent):
         if acc[n] and depth[n] > best_depth:
             best_depth, best = int(depth[n]), n
     return best_depth, best, acc
+
+
+# --------------------------------------------------------------------------- #
+# Eq. (3) softmax, Eq. (5) centroid, Eq. (6) JS rule, Algorithm 1
+# --------------------------------------------------------------------------- #
+def softmax(l: np.ndarray) -> np.ndarray:
+    """Softmax over the last axis, float64 (second half of Eq. (3))."""
+    l = np.asarray(l, dtype=np.float64)
+    e = np.exp(l - np.max(l, axis=-1, keepdims=True))
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def centroid(L: np.ndarray) -> np.ndarray:
+    """Eq. (5): pbar = Softmax of the MEAN over the K paths of their logits.  L is [K, V]."""
+    L = np.asarray(L, dtype=np.float64)
+    return softmax(np.sum(L, axis=0) / L.shape[0])
+
+
+def kl_divergence(P: np.ndarray, Q: np.ndarray) -> float:
+    """KL(P || Q) = sum_v P[v] ln(P[v] / Q[v]), terms with P[v] = 0 contribute 0."""
+    P = np.asarray(P, dtype=np.float64)
+    Q = np.asarray(Q, dtype=np.float64)
+    nz = P > 0
+    return float(np.sum(P[nz] * (np.log(P[nz]) - np.log(Q[nz]))))
+
+
+def js_divergence(P: np.ndarray, Q: np.ndarray) -> float:
+    """Jensen-Shannon divergence JS(P || Q) = KL(P || M)/2 + KL(Q || M)/2, M = (P + Q)/2."""
+    P = np.asarray(P, dtype=np.float64)
+    Q = np.asarray(Q, dtype=np.float64)
+    M = 0.5 * (P + Q)
+    return 0.5 * kl_divergence(P, M) + 0.5 * kl_divergence(Q, M)
+
+
+def js_rule(p_hat: np.ndarray, L: np.ndarray):
+    """Eq. (6) for one position.  p_hat[V]: draft distribution; L[K, V]: path logits.
+    Returns (hit, js_draft, js_heads[K]).  The comparison is made on the float32
+    roundings of both sides."""
+    pbar = centroid(L)
+    js_heads = np.array([js_divergence(softmax(L[i]), pbar) for i in range(L.shape[0])])
+    js_draft = js_divergence(np.asarray(p_hat, dtype=np.float64), pbar)
+    hit = bool(np.float32(js_draft) <= np.float32(np.max(js_heads)))
+    return hit, js_draft, js_heads
+
+
+def algorithm1_hit(draft: int, p_hat: np.ndarray, L: np.ndarray, ids) -> bool:
+    """Algorithm 1 for one position: accept by Eq. (6); otherwise accept by Eq. (7);
+    otherwise reject.  (A row without a draft token never hits.)"""
+    if int(draft) < 0:
+        return False
+    if js_rule(p_hat, L)[0]:
+        return True
+    return rule_hit(draft, ids, RULE_MAJORITY)
+
+
+def verify_js(h, W, draft_ids, draft_probs, seeds, K: int, p, step: int = 0,
+              rule: int = RULE_JS_OR_MAJORITY, share_mask_across_pos: bool = False):
+    """One verification step with the distribution-level rule (chains only).
+
+    draft_probs [B, T, V]: the draft model's distribution for the token row t verifies
+    (ignored at rows whose draft id is < 0).  rule: RULE_JS (Eq. (6) alone) or
+    RULE_JS_OR_MAJORITY (Algorithm 1).
+
+    Returns what verify() returns plus js_draft[B,T] (-1 at rows without a draft
+    token), js_heads[B,T,K], and js_margin[B,T] = max_i js_heads - js_draft (the
+    distance of the Eq. (6) decision from a tie; +inf at rows without a draft token).
+    """
+    if rule not in (RULE_JS, RULE_JS_OR_MAJORITY):
+        raise ValueError("verify_js takes RULE_JS or RULE_JS_OR_MAJORITY")
+    h = np.asarray(h, dtype=np.float64)
+    W64 = np.asarray(W, dtype=np.float64)
+    draft_ids = np.asarray(draft_ids)
+    B, T, d = h.shape
+    V = W64.shape[0]
+    draft_probs = np.asarray(draft_probs)
+    if W64.shape[1] != d or draft_ids.shape != (B, T) or draft_probs.shape != (B, T, V) or len(seeds) != B:
+        raise ValueError("shape mismatch")
+
+    path_ids = np.zeros((B, T, K), dtype=np.int32)
+    gap = np.zeros((B, T, K), dtype=np.float64)
+    js_draft = np.full((B, T), -1.0)
+    js_heads = np.zeros((B, T, K))
+    js_margin = np.full((B, T), np.inf)
+    hit = np.zeros((B, T), dtype=np.uint8)
+    for b in range(B):
+        for t in range(T):
+            tt = 0 if share_mask_across_pos else t
+            Hm = np.stack([masked_state(h[b, t], keep_mask(seeds[b], step, tt, i, d, p), p)
+                           for i in range(K)], axis=0)          # Eq. (1)-(2), [K, d]
+            L = (W64 @ Hm.T).T                                   # Eq. (3), [K, V]
+            for i in range(K):
+                path_ids[b, t, i], gap[b, t, i] = path_token(L[i])
+            g = int(draft_ids[b, t])
+            js_hit, jd, jh = js_rule(draft_probs[b, t], L)
+            js_heads[b, t] = jh
+            if g < 0:
+                continue
+            js_draft[b, t] = jd
+            js_margin[b, t] = float(np.max(jh)) - jd
+            if rule == RULE_JS:
+                hit[b, t] = js_hit
+            else:
+                hit[b, t] = js_hit or rule_hit(g, path_ids[b, t], RULE_MAJORITY)
+
+    out = acceptance_from_hits(hit)
+    votes = acceptance_from_path_ids(path_ids, draft_ids, RULE_MAJORITY)
+    out.update(vote_ids=votes["vote_ids"], vote_cnt=votes["vote_cnt"], path_ids=path_ids, gap=gap,
+               js_draft=js_draft, js_heads=js_heads, js_margin=js_margin)
+    return out
+
+
+def acceptance_from_hits(hit):
+    """Prefix rule applied to given per-row decisions hit[B, T] (chain)."""
+    hit = np.asarray(hit, dtype=np.uint8)
+    B, T = hit.shape
+    accept_mask = np.zeros((B, T), dtype=np.uint8)
+    accept_len = np.zeros(B, dtype=np.int32)
+    best_node = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        accept_len[b], best_node[b], accept_mask[b] = accept_chain(hit[b])
+    return dict(hit=hit, accept_mask=accept_mask, accept_len=accept_len, best_node=best_node)
 
 
 # --------------------------------------------------------------------------- #

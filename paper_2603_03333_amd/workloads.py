@@ -155,6 +155,36 @@ def make_draft_ids(wl: Workload, greedy: Optional[np.ndarray]) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------- #
+# draft distributions (inputs of the distribution-level rule)
+# --------------------------------------------------------------------------- #
+DRAFT_NOISE_LEVELS = (0.1, 0.3, 0.42, 0.6)
+
+
+def make_draft_probs(wl: Workload, clean_logits: np.ndarray, topk: int = 0) -> np.ndarray:
+    """draft_probs[B, T, V] float32: a stand-in for the draft model's next-token
+    distribution at every row.  The caller supplies the undropped head logits of the
+    row (clean_logits[B, T, V]); the draft is that plus i.i.d. Gaussian noise whose
+    standard deviation is drawn per row from DRAFT_NOISE_LEVELS (close drafts and far
+    drafts in one batch), normalised to a distribution.  With topk > 0 everything but
+    the topk largest entries is set to exactly 0 and the rest renormalised (drafts that
+    sample from a truncated distribution)."""
+    rng = np.random.Generator(np.random.PCG64(wl.data_seed + 86028121))
+    B, T, V = clean_logits.shape
+    out = np.empty((B, T, V), dtype=np.float32)
+    levels = rng.integers(0, len(DRAFT_NOISE_LEVELS), size=(B, T))
+    for b in range(B):
+        for t in range(T):
+            z = clean_logits[b, t].astype(np.float64)
+            z = z + DRAFT_NOISE_LEVELS[int(levels[b, t])] * rng.standard_normal(V)
+            e = np.exp(z - z.max())
+            if 0 < topk < V:
+                cut = np.partition(e, V - topk)[V - topk]
+                e[e < cut] = 0.0
+            out[b, t] = (e / e.sum()).astype(np.float32)
+    return out
+
+
+# --------------------------------------------------------------------------- #
 # draft trees
 # --------------------------------------------------------------------------- #
 def make_tree_parents(wl: Workload, max_depth: int = 6, max_branch: int = 4) -> np.ndarray:
