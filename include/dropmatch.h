@@ -52,9 +52,11 @@ typedef enum {
 typedef enum { DM_F32 = 0, DM_BF16 = 1 } dm_dtype; /* storage type of BOTH h and W */
 
 typedef enum {
-  DM_RULE_ANY = 0,      /* Eq. 4: draft token is among the K path tokens */
-  DM_RULE_MAJORITY = 1  /* Eq. 7: draft token equals the mode of the K path tokens */
-} dm_rule;
+  DM_RULE_ANY = 0,            /* Eq. 4: draft token is among the K path tokens */
+  DM_RULE_MAJORITY = 1,       /* Eq. 7: draft token equals the mode of the K path tokens */
+  DM_RULE_JS = 2,             /* Eq. 6 alone: JS(draft dist. || centroid) <= max_i JS(head i || centroid) */
+  DM_RULE_JS_OR_MAJORITY = 3  /* Algorithm 1: Eq. 6, else Eq. 7 */
+} dm_rule;                    /* rules 2 and 3 go through dropmatch_verify_js */
 
 /* One mask per path shared by all rows of a sequence ("K persistent heads"): the row word
  * of the Philox counter is forced to 0.  Default (flag clear): a fresh mask per (path, row). */
@@ -67,6 +69,7 @@ typedef enum {
 #define DM_MAX_K 1024            /* paths per row */
 #define DM_MAX_ROWS_PER_SEQ 4096 /* T */
 #define DM_MAX_TK 16384          /* T*K per sequence (path tokens of a sequence live in LDS) */
+#define DM_MAX_K_JS 64           /* paths per row with the distribution-level rules */
 
 typedef struct {
   int32_t B;       /* sequences, >= 1 */
@@ -141,6 +144,49 @@ dm_status dropmatch_verify(dm_ctx* ctx, const dm_params* prm,
                            int32_t* vote_cnt,        /* DEVICE [B,T] or NULL */
                            void* stream);
 
+/*
+ * Distribution-level acceptance (paper: "JS-Divergence-Based Criterion", Eq. 5, Eq. 6, Algorithm 1).
+ * With p_t^(i) = Softmax(l_t^(i)) (Eq. 3; here the factor 1/(1-p) of Eq. 2 IS applied, softmax is
+ * not scale invariant), the centroid pbar_t = Softmax((1/K) sum_i l_t^(i)) (Eq. 5) and the draft
+ * model's distribution phat_t, row t hits iff
+ *     JS(phat_t || pbar_t) <= max_i JS(p_t^(i) || pbar_t)                        (Eq. 6, rule DM_RULE_JS)
+ * or, under DM_RULE_JS_OR_MAJORITY (Algorithm 1), iff Eq. 6 holds or else Eq. 7 holds.
+ * JS(P||Q) = KL(P||M)/2 + KL(Q||M)/2, M = (P+Q)/2, natural logarithm, 0 ln 0 = 0; both sides of
+ * Eq. 6 are compared as float.  Chains only (prm->parent must be NULL; the paper pairs tree decoding
+ * with naive matching only), K <= DM_MAX_K_JS.  A row with draft id < 0 never hits.
+ *
+ * dm_reserve_js allocates, once, what these rules need beyond dm_create: the logits of every path
+ * (max_positions * max_V * roundup(max_K, 4) floats; unlike on the token-level path they are stored,
+ * because Eq. 6 needs the normalisers before it can form its sums) and two small arrays of partial
+ * sums.  It synchronises the device and may be called again to resize.  B*T <= max_positions and
+ * K <= max_K must then hold for every dropmatch_verify_js on this context.
+ *
+ * dropmatch_verify_js: same contract and outputs as dropmatch_verify, plus
+ *   draft_probs  DEVICE float [B,T,V]: phat of the token that row t verifies (probabilities, >= 0,
+ *                summing to 1; exact zeros are allowed; not read at rows with draft id < 0)
+ *   js_draft     DEVICE float [B,T] or NULL: JS(phat_t || pbar_t); -1 at rows with draft id < 0
+ *   js_heads     DEVICE float [B,T,K] or NULL: JS(p_t^(i) || pbar_t)
+ * Arithmetic: logits from the same contraction kernels (storage type products, fp32 accumulation,
+ * times (float)(1/(1-p))), exp/log and all sums in fp32 with partial sums added in a fixed order
+ * (chunk totals in double), so results are reproducible run to run.
+ */
+dm_status dm_reserve_js(dm_ctx* ctx, int64_t max_positions, int32_t max_K);
+dm_status dropmatch_verify_js(dm_ctx* ctx, const dm_params* prm,
+                              const void* h,            /* DEVICE [B,T,d] contiguous */
+                              const void* W,            /* DEVICE [V,d] row-major contiguous */
+                              const int32_t* draft_ids, /* DEVICE [B,T] */
+                              const float* draft_probs, /* DEVICE [B,T,V] */
+                              int32_t* accept_len,      /* DEVICE [B], required */
+                              int32_t* best_node,       /* DEVICE [B] or NULL */
+                              uint8_t* accept_mask,     /* DEVICE [B,T] or NULL */
+                              uint8_t* hit,             /* DEVICE [B,T] or NULL */
+                              int32_t* path_ids,        /* DEVICE [B,T,K] or NULL */
+                              int32_t* vote_ids,        /* DEVICE [B,T] or NULL */
+                              int32_t* vote_cnt,        /* DEVICE [B,T] or NULL */
+                              float* js_draft,          /* DEVICE [B,T] or NULL */
+                              float* js_heads,          /* DEVICE [B,T,K] or NULL */
+                              void* stream);
+
 /* Debug: the keep-masks of Eq. 1 exactly as dropmatch_verify draws them, bit-packed.
  * bits: DEVICE uint32 [B,T,K,ceil(d/32)]; word w of a row holds dimensions 32w..32w+31,
  * bit (j & 31) = keep(j); bits past d are 0. */
@@ -152,16 +198,20 @@ dm_status dm_debug_masks(dm_ctx* ctx, const dm_params* prm, uint32_t* bits, void
 dm_status dm_debug_logits(dm_ctx* ctx, const dm_params* prm, const void* h, const void* W,
                           int32_t v0, int32_t v1, float* logits, void* stream);
 
-/* Measurement aid.  dm_set_profiling(ctx, 1) makes every following dropmatch_verify record HIP
- * events on its stream before and after each of its three kernels (mask rows, LM-head
- * contraction + argmax, vote/accept); events are created here, not in dropmatch_verify.  At
- * most DM_PROFILE_MAX_CALLS calls are kept (later ones are not recorded).
- * dm_get_profile waits for the last recorded event and returns the number of recorded calls
- * and the mean duration of each kernel in milliseconds (any output pointer may be NULL);
- * dm_set_profiling(ctx, 0) stops recording and forgets the samples. */
+/* Measurement aid.  dm_set_profiling(ctx, 1) makes every following dropmatch_verify /
+ * dropmatch_verify_js record HIP events on its stream before and after each of its kernels
+ * (mask rows, LM-head contraction + argmax, [JS pass 1, JS pass 2,] vote/accept); events are
+ * created here, not in the verify calls.  At most DM_PROFILE_MAX_CALLS calls are kept (later
+ * ones are not recorded).  dm_get_profile waits for the last recorded event and returns the
+ * number of recorded calls and the mean duration of the three kernels of the token-level path
+ * in milliseconds (any output pointer may be NULL); dm_get_profile_stages returns all five
+ * stage means in ms[0..4] = mask rows, LM head, JS pass 1, JS pass 2, vote/accept (the JS
+ * stages are 0 for dropmatch_verify).  dm_set_profiling(ctx, 0) stops recording and forgets
+ * the samples. */
 #define DM_PROFILE_MAX_CALLS 512
 dm_status dm_set_profiling(dm_ctx* ctx, int32_t enabled);
 dm_status dm_get_profile(dm_ctx* ctx, int32_t* n_calls, float* ms_mask, float* ms_lmhead, float* ms_vote);
+dm_status dm_get_profile_stages(dm_ctx* ctx, int32_t* n_calls, float* ms /* HOST [5] */);
 
 /* Which contraction kernel a parameter block selects: 0 = generic fp32-FMA tiles (any
  * shape, f32 or bf16), 1 = bf16 MFMA kernel (bf16, d % 64 == 0).  Negative = dm_status. */

@@ -13,14 +13,15 @@ from typing import Optional, Sequence
 
 DM_OK, DM_EINVAL, DM_ENOMEM, DM_EHIP, DM_EUNSUPPORTED = 0, -1, -2, -3, -4
 DM_F32, DM_BF16 = 0, 1
-DM_RULE_ANY, DM_RULE_MAJORITY = 0, 1
+DM_RULE_ANY, DM_RULE_MAJORITY, DM_RULE_JS, DM_RULE_JS_OR_MAJORITY = 0, 1, 2, 3
 DM_FLAG_SHARE_MASK_ACROSS_POS, DM_FLAG_FORCE_GENERIC = 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdropmatch.so")
 
 EXPORTS = ("dm_create", "dm_destroy", "dm_last_error", "dm_validate", "dropmatch_verify",
-           "dm_debug_masks", "dm_debug_logits", "dm_kernel_choice", "dm_set_profiling", "dm_get_profile")
+           "dm_debug_masks", "dm_debug_logits", "dm_kernel_choice", "dm_set_profiling", "dm_get_profile",
+           "dm_get_profile_stages", "dm_reserve_js", "dropmatch_verify_js")
 
 
 class dm_params(C.Structure):
@@ -72,6 +73,12 @@ def load_library():
     lib.dm_set_profiling.restype = C.c_int
     lib.dm_get_profile.argtypes = [vp, C.POINTER(i32)] + [C.POINTER(C.c_float)] * 3
     lib.dm_get_profile.restype = C.c_int
+    lib.dm_get_profile_stages.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_float)]
+    lib.dm_get_profile_stages.restype = C.c_int
+    lib.dm_reserve_js.argtypes = [vp, i64, i32]
+    lib.dm_reserve_js.restype = C.c_int
+    lib.dropmatch_verify_js.argtypes = [vp, C.POINTER(dm_params)] + [vp] * 14
+    lib.dropmatch_verify_js.restype = C.c_int
     _lib = lib
     return lib
 
@@ -138,6 +145,21 @@ def dropmatch_verify(ctx, prm: dm_params, h, W, draft_ids, accept_len, best_node
     _check(ctx, st)
 
 
+def dm_reserve_js(ctx, max_positions: int, max_K: int) -> None:
+    _check(ctx, load_library().dm_reserve_js(ctx, max_positions, max_K))
+
+
+def dropmatch_verify_js(ctx, prm: dm_params, h, W, draft_ids, draft_probs, accept_len, best_node=None,
+                        accept_mask=None, hit=None, path_ids=None, vote_ids=None, vote_cnt=None, js_draft=None,
+                        js_heads=None, stream=None) -> None:
+    """Enqueue one verification step with a distribution-level rule (Eq. 6 / Algorithm 1)."""
+    st = load_library().dropmatch_verify_js(ctx, C.byref(prm), _ptr(h), _ptr(W), _ptr(draft_ids), _ptr(draft_probs),
+                                            _ptr(accept_len), _ptr(best_node), _ptr(accept_mask), _ptr(hit),
+                                            _ptr(path_ids), _ptr(vote_ids), _ptr(vote_cnt), _ptr(js_draft),
+                                            _ptr(js_heads), _stream_handle(stream))
+    _check(ctx, st)
+
+
 def dm_debug_masks(ctx, prm: dm_params, bits, stream=None) -> None:
     st = load_library().dm_debug_masks(ctx, C.byref(prm), _ptr(bits), _stream_handle(stream))
     _check(ctx, st)
@@ -159,3 +181,11 @@ def dm_get_profile(ctx):
     a, b, c = C.c_float(), C.c_float(), C.c_float()
     _check(ctx, load_library().dm_get_profile(ctx, C.byref(n), C.byref(a), C.byref(b), C.byref(c)))
     return n.value, a.value, b.value, c.value
+
+
+def dm_get_profile_stages(ctx):
+    """Returns (n_calls, [ms_mask, ms_lmhead, ms_js_pass1, ms_js_pass2, ms_vote])."""
+    n = C.c_int32()
+    ms = (C.c_float * 5)()
+    _check(ctx, load_library().dm_get_profile_stages(ctx, C.byref(n), ms))
+    return n.value, [float(x) for x in ms]

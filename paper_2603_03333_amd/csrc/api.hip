@@ -18,14 +18,22 @@ struct dm_ctx {
   int32_t d_pad = 0;     // max_d rounded up to 64
   void* a_ws = nullptr;               // masked rows
   unsigned long long* keys = nullptr; // packed (logit, index) argmax per row
+  // distribution-level rule (dm_reserve_js): stored logits and per-chunk partial sums
+  float* lt = nullptr;
+  size_t lt_floats = 0;
+  float* part_a = nullptr;
+  float* part_b = nullptr;
+  size_t part_floats = 0;
   char err[512] = {0};
-  // measurement aid: 4 events per recorded call
+  // measurement aid: kEv events per recorded call
   hipEvent_t* ev = nullptr;
   int prof_enabled = 0;
   int prof_calls = 0;
 };
 
 namespace {
+
+constexpr int kEv = 6;  // events per recorded call: before mask | lmhead | js_stats | js_terms | vote | end
 
 char g_err[512] = {0};  // failures that have no context (dm_create, NULL ctx)
 
@@ -63,7 +71,13 @@ const char* check_params(const dm_params* p, char* scratch, size_t n) {
   if ((int64_t)p->B * p->T * p->K > (int64_t)1 << 40) return "B*T*K too large";
   if (p->dtype != DM_F32 && p->dtype != DM_BF16) return "dtype must be DM_F32 or DM_BF16";
   if (!(p->p >= 0.0f && p->p < 1.0f)) return "p must satisfy 0 <= p < 1";
-  if (p->rule != DM_RULE_ANY && p->rule != DM_RULE_MAJORITY) return "rule must be DM_RULE_ANY or DM_RULE_MAJORITY";
+  if (p->rule < DM_RULE_ANY || p->rule > DM_RULE_JS_OR_MAJORITY) return "rule must be one of the DM_RULE_* values";
+  if (p->rule >= DM_RULE_JS && p->K > DM_MAX_K_JS) {
+    snprintf(scratch, n, "the distribution-level rules take K <= %d", DM_MAX_K_JS);
+    return scratch;
+  }
+  if (p->rule >= DM_RULE_JS && p->parent != nullptr)
+    return "the distribution-level rules are defined for chains only (parent must be NULL)";
   if (p->flags & ~(DM_FLAG_SHARE_MASK_ACROSS_POS | DM_FLAG_FORCE_GENERIC)) return "unknown bits in flags";
   if (!p->seeds) return "seeds is NULL";
   return nullptr;
@@ -113,7 +127,8 @@ struct DeviceGuard {
 // Eq. (1)-(3) + argmax keys; shared by dropmatch_verify and dm_debug_logits.
 // `ev` (optional): 3 events recorded before the mask kernel, between the two kernels, after.
 dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g, bool mfma, const void* h,
-                          const void* W, float* logits, int v0, int v1, hipStream_t s, hipEvent_t* ev = nullptr) {
+                          const void* W, float* logits, int v0, int v1, hipStream_t s, hipEvent_t* ev = nullptr,
+                          const dm::LogitStore& store = dm::LogitStore{nullptr, 0, 0, 0}) {
   const bool bf16 = p->dtype == DM_BF16;
   if (ev) (void)hipEventRecord(ev[0], s);
   hipError_t e = dm::launch_mask_rows(h, ctx->a_ws, ctx->keys, p->seeds, g, bf16, mfma, s);
@@ -121,11 +136,11 @@ dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g,
   if (ev) (void)hipEventRecord(ev[1], s);
   const float scale = (float)(1.0 / (1.0 - (double)p->p));
   if (mfma && g.M <= 128)
-    e = dm::launch_lmhead_mfma(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, s);
+    e = dm::launch_lmhead_mfma(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, store, s);
   else if (mfma)
-    e = dm::launch_lmhead_mfma_big(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, s);
+    e = dm::launch_lmhead_mfma_big(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, store, s);
   else
-    e = dm::launch_lmhead_generic(W, ctx->a_ws, ctx->keys, g, p->V, bf16, logits, v0, v1, scale, s);
+    e = dm::launch_lmhead_generic(W, ctx->a_ws, ctx->keys, g, p->V, bf16, logits, v0, v1, scale, store, s);
   if (e != hipSuccess) return fail_hip(ctx, "lmhead launch", e);
   if (ev) (void)hipEventRecord(ev[2], s);
   return DM_OK;
@@ -133,10 +148,70 @@ dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g,
 
 void drop_events(dm_ctx* ctx) {
   if (!ctx->ev) return;
-  for (int i = 0; i < 4 * DM_PROFILE_MAX_CALLS; ++i)
+  for (int i = 0; i < kEv * DM_PROFILE_MAX_CALLS; ++i)
     if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
   delete[] ctx->ev;
   ctx->ev = nullptr;
+}
+
+// The verification step; draft_probs != nullptr selects the distribution-level rules.
+dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const void* W, const int32_t* draft_ids,
+                      const float* draft_probs, int32_t* accept_len, int32_t* best_node, uint8_t* accept_mask,
+                      uint8_t* hit, int32_t* path_ids, int32_t* vote_ids, int32_t* vote_cnt, float* js_draft,
+                      float* js_heads, void* stream) {
+  if (!ctx) return fail(nullptr, DM_EINVAL, "ctx is NULL");
+  if (!prm) return fail(ctx, DM_EINVAL, "params is NULL");
+  if (!h || !W || !draft_ids || !accept_len) return fail(ctx, DM_EINVAL, "h, W, draft_ids and accept_len are required");
+  if (((uintptr_t)h | (uintptr_t)W) & 15) return fail(ctx, DM_EINVAL, "h and W must be 16-byte aligned");
+  const bool mfma = use_mfma(prm);
+  dm::RowGeom g;
+  if (dm_status st = make_geom(ctx, prm, mfma, &g)) return st;
+  const bool js = draft_probs != nullptr;
+  dm::JsGeom jg{};
+  dm::LogitStore store{nullptr, 0, 0, 0};
+  if (js) {
+    jg.P = prm->B * prm->T;
+    jg.K = prm->K;
+    jg.K4 = (int)round_up(prm->K, 4);
+    jg.V = prm->V;
+    jg.NC = (prm->V + dm::kJsChunk - 1) / dm::kJsChunk;
+    jg.KS = jg.K4 + 4;
+    if ((int64_t)prm->B * prm->T > 0x7FFFFFFF) return fail(ctx, DM_EINVAL, "B*T too large");
+    if (!ctx->lt) return fail(ctx, DM_EINVAL, "call dm_reserve_js before dropmatch_verify_js");
+    if ((size_t)jg.P * (size_t)jg.V * (size_t)jg.K4 > ctx->lt_floats ||
+        (size_t)jg.P * (size_t)jg.NC * (size_t)jg.KS > ctx->part_floats)
+      return fail(ctx, DM_EINVAL, "B*T = %d positions with K = %d exceed what dm_reserve_js reserved", jg.P, jg.K);
+    store = dm::LogitStore{ctx->lt, jg.K, jg.K4, jg.V};
+  }
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return fail(ctx, DM_EHIP, "cannot select device %d", ctx->device);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  hipEvent_t* ev = nullptr;
+  if (ctx->prof_enabled && ctx->ev && ctx->prof_calls < DM_PROFILE_MAX_CALLS) ev = ctx->ev + kEv * ctx->prof_calls;
+  if (dm_status st = run_contraction(ctx, prm, g, mfma, h, W, nullptr, 0, 0, s, ev, store)) return st;
+  hipError_t e;
+  if (js) {
+    const float scale = (float)(1.0 / (1.0 - (double)prm->p));
+    e = dm::launch_js_stats(ctx->lt, ctx->keys, ctx->part_a, jg, scale, s);
+    if (e != hipSuccess) return fail_hip(ctx, "js_stats launch", e);
+    if (ev) (void)hipEventRecord(ev[3], s);
+    e = dm::launch_js_terms(ctx->lt, ctx->keys, ctx->part_a, draft_probs, draft_ids, ctx->part_b, jg, scale, s);
+    if (e != hipSuccess) return fail_hip(ctx, "js_terms launch", e);
+    if (ev) (void)hipEventRecord(ev[4], s);
+  } else if (ev) {
+    (void)hipEventRecord(ev[3], s);
+    (void)hipEventRecord(ev[4], s);
+  }
+  dm::VoteOut out{accept_len, best_node, accept_mask, hit, path_ids, vote_ids, vote_cnt, js_draft, js_heads};
+  e = dm::launch_vote_accept(ctx->keys, draft_ids, prm->parent, prm->B, prm->T, prm->K, prm->rule, out,
+                             js ? ctx->part_b : nullptr, js ? &jg : nullptr, s);
+  if (e != hipSuccess) return fail_hip(ctx, "vote_accept launch", e);
+  if (ev) {
+    (void)hipEventRecord(ev[5], s);
+    ++ctx->prof_calls;
+  }
+  return DM_OK;
 }
 
 }  // namespace
@@ -210,6 +285,9 @@ dm_status dm_destroy(dm_ctx* ctx) {
   drop_events(ctx);
   if (ctx->a_ws) (void)hipFree(ctx->a_ws);
   if (ctx->keys) (void)hipFree(ctx->keys);
+  if (ctx->lt) (void)hipFree(ctx->lt);
+  if (ctx->part_a) (void)hipFree(ctx->part_a);
+  if (ctx->part_b) (void)hipFree(ctx->part_b);
   delete ctx;
   return st;
 }
@@ -218,27 +296,52 @@ dm_status dropmatch_verify(dm_ctx* ctx, const dm_params* prm, const void* h, con
                            const int32_t* draft_ids, int32_t* accept_len, int32_t* best_node,
                            uint8_t* accept_mask, uint8_t* hit, int32_t* path_ids, int32_t* vote_ids,
                            int32_t* vote_cnt, void* stream) {
+  if (ctx && prm && prm->rule >= DM_RULE_JS)
+    return fail(ctx, DM_EINVAL, "rules DM_RULE_JS and DM_RULE_JS_OR_MAJORITY need the draft distribution: call dropmatch_verify_js");
+  return verify_impl(ctx, prm, h, W, draft_ids, nullptr, accept_len, best_node, accept_mask, hit, path_ids, vote_ids,
+                     vote_cnt, nullptr, nullptr, stream);
+}
+
+dm_status dropmatch_verify_js(dm_ctx* ctx, const dm_params* prm, const void* h, const void* W,
+                              const int32_t* draft_ids, const float* draft_probs, int32_t* accept_len,
+                              int32_t* best_node, uint8_t* accept_mask, uint8_t* hit, int32_t* path_ids,
+                              int32_t* vote_ids, int32_t* vote_cnt, float* js_draft, float* js_heads,
+                              void* stream) {
+  if (ctx && prm && prm->rule < DM_RULE_JS)
+    return fail(ctx, DM_EINVAL, "dropmatch_verify_js takes DM_RULE_JS or DM_RULE_JS_OR_MAJORITY");
+  if (ctx && !draft_probs) return fail(ctx, DM_EINVAL, "draft_probs is required");
+  return verify_impl(ctx, prm, h, W, draft_ids, draft_probs, accept_len, best_node, accept_mask, hit, path_ids,
+                     vote_ids, vote_cnt, js_draft, js_heads, stream);
+}
+
+dm_status dm_reserve_js(dm_ctx* ctx, int64_t max_positions, int32_t max_K) {
   if (!ctx) return fail(nullptr, DM_EINVAL, "ctx is NULL");
-  if (!prm) return fail(ctx, DM_EINVAL, "params is NULL");
-  if (!h || !W || !draft_ids || !accept_len) return fail(ctx, DM_EINVAL, "h, W, draft_ids and accept_len are required");
-  if (((uintptr_t)h | (uintptr_t)W) & 15) return fail(ctx, DM_EINVAL, "h and W must be 16-byte aligned");
-  const bool mfma = use_mfma(prm);
-  dm::RowGeom g;
-  if (dm_status st = make_geom(ctx, prm, mfma, &g)) return st;
+  if (max_positions < 1 || max_K < 1 || max_K > DM_MAX_K_JS)
+    return fail(ctx, DM_EINVAL, "need max_positions >= 1 and 1 <= max_K <= %d", DM_MAX_K_JS);
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return fail(ctx, DM_EHIP, "cannot select device %d", ctx->device);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-
-  hipEvent_t* ev = nullptr;
-  if (ctx->prof_enabled && ctx->ev && ctx->prof_calls < DM_PROFILE_MAX_CALLS) ev = ctx->ev + 4 * ctx->prof_calls;
-  if (dm_status st = run_contraction(ctx, prm, g, mfma, h, W, nullptr, 0, 0, s, ev)) return st;
-  dm::VoteOut out{accept_len, best_node, accept_mask, hit, path_ids, vote_ids, vote_cnt};
-  hipError_t e = dm::launch_vote_accept(ctx->keys, draft_ids, prm->parent, prm->B, prm->T, prm->K, prm->rule, out, s);
-  if (e != hipSuccess) return fail_hip(ctx, "vote_accept launch", e);
-  if (ev) {
-    (void)hipEventRecord(ev[3], s);
-    ++ctx->prof_calls;
+  if (hipDeviceSynchronize() != hipSuccess) return fail(ctx, DM_EHIP, "device synchronisation failed in dm_reserve_js");
+  if (ctx->lt) (void)hipFree(ctx->lt);
+  if (ctx->part_a) (void)hipFree(ctx->part_a);
+  if (ctx->part_b) (void)hipFree(ctx->part_b);
+  ctx->lt = ctx->part_a = ctx->part_b = nullptr;
+  ctx->lt_floats = ctx->part_floats = 0;
+  const size_t K4 = (size_t)round_up(max_K, 4);
+  const size_t lt_floats = (size_t)max_positions * (size_t)ctx->max_V * K4;
+  const size_t nc = (size_t)((ctx->max_V + dm::kJsChunk - 1) / dm::kJsChunk);
+  const size_t part_floats = (size_t)max_positions * nc * (K4 + 4);
+  hipError_t e;
+  if ((e = hipMalloc((void**)&ctx->lt, lt_floats * 4)) != hipSuccess ||
+      (e = hipMalloc((void**)&ctx->part_a, part_floats * 4)) != hipSuccess ||
+      (e = hipMalloc((void**)&ctx->part_b, part_floats * 4)) != hipSuccess) {
+    (void)hipGetLastError();
+    if (ctx->lt) (void)hipFree(ctx->lt);
+    if (ctx->part_a) (void)hipFree(ctx->part_a);
+    ctx->lt = ctx->part_a = ctx->part_b = nullptr;
+    return fail(ctx, DM_ENOMEM, "logit store of %zu bytes could not be allocated: %s", lt_floats * 4, hipGetErrorString(e));
   }
+  ctx->lt_floats = lt_floats;
+  ctx->part_floats = part_floats;
   return DM_OK;
 }
 
@@ -250,9 +353,9 @@ dm_status dm_set_profiling(dm_ctx* ctx, int32_t enabled) {
   ctx->prof_enabled = 0;
   if (!enabled) return DM_OK;
   if (!ctx->ev) {
-    ctx->ev = new (std::nothrow) hipEvent_t[4 * DM_PROFILE_MAX_CALLS]();
+    ctx->ev = new (std::nothrow) hipEvent_t[kEv * DM_PROFILE_MAX_CALLS]();
     if (!ctx->ev) return fail(ctx, DM_ENOMEM, "host allocation failed");
-    for (int i = 0; i < 4 * DM_PROFILE_MAX_CALLS; ++i) {
+    for (int i = 0; i < kEv * DM_PROFILE_MAX_CALLS; ++i) {
       const hipError_t e = hipEventCreate(&ctx->ev[i]);
       if (e != hipSuccess) {
         drop_events(ctx);
@@ -264,27 +367,35 @@ dm_status dm_set_profiling(dm_ctx* ctx, int32_t enabled) {
   return DM_OK;
 }
 
-dm_status dm_get_profile(dm_ctx* ctx, int32_t* n_calls, float* ms_mask, float* ms_lmhead, float* ms_vote) {
+dm_status dm_get_profile_stages(dm_ctx* ctx, int32_t* n_calls, float* ms /* [5] */) {
   if (!ctx) return fail(nullptr, DM_EINVAL, "ctx is NULL");
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return fail(ctx, DM_EHIP, "cannot select device %d", ctx->device);
   const int n = ctx->prof_calls;
-  double sum[3] = {0, 0, 0};
+  double sum[kEv - 1] = {0, 0, 0, 0, 0};
   if (n > 0) {
-    hipError_t e = hipEventSynchronize(ctx->ev[4 * (n - 1) + 3]);
+    hipError_t e = hipEventSynchronize(ctx->ev[kEv * (n - 1) + kEv - 1]);
     if (e != hipSuccess) return fail_hip(ctx, "hipEventSynchronize", e);
     for (int c = 0; c < n; ++c)
-      for (int k = 0; k < 3; ++k) {
-        float ms = 0.f;
-        e = hipEventElapsedTime(&ms, ctx->ev[4 * c + k], ctx->ev[4 * c + k + 1]);
+      for (int k = 0; k < kEv - 1; ++k) {
+        float t = 0.f;
+        e = hipEventElapsedTime(&t, ctx->ev[kEv * c + k], ctx->ev[kEv * c + k + 1]);
         if (e != hipSuccess) return fail_hip(ctx, "hipEventElapsedTime", e);
-        sum[k] += ms;
+        sum[k] += t;
       }
   }
   if (n_calls) *n_calls = n;
-  if (ms_mask) *ms_mask = n ? (float)(sum[0] / n) : 0.f;
-  if (ms_lmhead) *ms_lmhead = n ? (float)(sum[1] / n) : 0.f;
-  if (ms_vote) *ms_vote = n ? (float)(sum[2] / n) : 0.f;
+  if (ms)
+    for (int k = 0; k < kEv - 1; ++k) ms[k] = n ? (float)(sum[k] / n) : 0.f;
+  return DM_OK;
+}
+
+dm_status dm_get_profile(dm_ctx* ctx, int32_t* n_calls, float* ms_mask, float* ms_lmhead, float* ms_vote) {
+  float ms[kEv - 1];
+  if (dm_status st = dm_get_profile_stages(ctx, n_calls, ms)) return st;
+  if (ms_mask) *ms_mask = ms[0];
+  if (ms_lmhead) *ms_lmhead = ms[1];
+  if (ms_vote) *ms_vote = ms[4];
   return DM_OK;
 }
 

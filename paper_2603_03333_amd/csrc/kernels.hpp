@@ -31,25 +31,55 @@ hipError_t launch_mask_rows(const void* h, void* a_ws, unsigned long long* keys,
 // Eq. (1) only, bit-packed [M, ceil(d/32)].
 hipError_t launch_mask_bits(uint32_t* bits, const uint64_t* seeds_host, const RowGeom& g, hipStream_t stream);
 
+// Where the contraction kernels put every scaled logit when the distribution-level rule needs them
+// (Eq. (5), (6)): lt[(pos * V + v) * K4 + i] = logit of path i of position pos at vocabulary row v,
+// pos = b * T + t, K4 = K rounded up to a multiple of 4 (16-byte aligned groups; the padding is never
+// read as data).  lt == nullptr: nothing is stored.
+struct LogitStore {
+  float* lt;
+  int K, K4, V;
+};
+
 // Eq. (3) + per-row argmax, generic fp32-FMA tiles.  a_ws plain layout.  If logits != null the
 // kernel instead stores scale * accumulator for v in [v0, v1) and touches no keys.
 hipError_t launch_lmhead_generic(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g,
                                  int V, bool is_bf16, float* logits, int v0, int v1, float scale,
-                                 hipStream_t stream);
+                                 const LogitStore& store, hipStream_t stream);
 
 // Eq. (3) + per-row argmax on bf16 MFMA; a_ws swizzled layout; d % 64 == 0.
 hipError_t launch_lmhead_mfma(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g,
                               int V, int num_cu, float* logits, int v0, int v1, float scale,
-                              hipStream_t stream);
+                              const LogitStore& store, hipStream_t stream);
 hipError_t prepare_lmhead_mfma();  // raises the dynamic-LDS limit of the kernels once per process
 
 // Same contract for more than 128 masked rows (256 x 256 tiles); needs M_pad % 256 == 0.
 hipError_t launch_lmhead_mfma_big(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g,
                                   int V, int num_cu, float* logits, int v0, int v1, float scale,
-                                  hipStream_t stream);
+                                  const LogitStore& store, hipStream_t stream);
 hipError_t prepare_lmhead_mfma_big();
 
-// Eq. (4)/(7), prefix / tree rule.  One workgroup per sequence.
+// Distribution-level rule (Eq. (5), (6)) over the stored logits, in two passes over the vocabulary;
+// each workgroup takes kJsChunk vocabulary rows of one position and leaves partial sums that the
+// next kernel adds up in a fixed order (so results do not depend on scheduling).
+constexpr int kJsChunk = 2048;  // vocabulary rows per workgroup
+constexpr int kJsMaxK = 64;     // paths per row the distribution-level rule takes
+struct JsGeom {
+  int P;    // positions B*T
+  int K, K4;
+  int V;
+  int NC;   // ceil(V / kJsChunk)
+  int KS;   // floats per (position, chunk) record in part_a / part_b: K4 + 4
+};
+// Pass 1: part_a[pos][c][i] = sum over the chunk of exp(l_i[v] - max_v l_i) for path i < K;
+// [K4] / [K4+1] = running (max, sum of exp) of the mean logits of the chunk.
+hipError_t launch_js_stats(const float* lt, const unsigned long long* keys, float* part_a, const JsGeom& g,
+                           float scale, hipStream_t stream);
+// Pass 2: part_b[pos][c][i] = chunk's share of JS(p^(i) || pbar) for i < K; [K4] = of JS(phat || pbar).
+hipError_t launch_js_terms(const float* lt, const unsigned long long* keys, const float* part_a,
+                           const float* draft_probs, const int32_t* draft_ids, float* part_b, const JsGeom& g,
+                           float scale, hipStream_t stream);
+
+// Eq. (4)/(7), Eq. (6), Alg. 1, prefix / tree rule.  One workgroup per sequence.
 struct VoteOut {
   int32_t* accept_len;
   int32_t* best_node;
@@ -58,9 +88,13 @@ struct VoteOut {
   int32_t* path_ids;
   int32_t* vote_ids;
   int32_t* vote_cnt;
+  float* js_draft;  // [B,T]   (distribution-level rules only)
+  float* js_heads;  // [B,T,K]
 };
+// part_b / jg: partial JS sums of launch_js_terms (rules 2 and 3), else nullptr.
 hipError_t launch_vote_accept(const unsigned long long* keys, const int32_t* draft_ids, const int32_t* parent,
-                              int B, int T, int K, int rule, const VoteOut& out, hipStream_t stream);
+                              int B, int T, int K, int rule, const VoteOut& out, const float* part_b,
+                              const JsGeom* jg, hipStream_t stream);
 hipError_t prepare_vote_accept();
 
 // Packed argmax key: larger logit wins, then smaller vocabulary index.  Key 0 = "nothing yet".

@@ -15,12 +15,15 @@ __device__ __forceinline__ float to_f32(uint16_t x) { return __uint_as_float((ui
 constexpr int GT = 64;  // tile edge
 constexpr int GK = 16;  // k slab
 
-template <typename T, bool DUMP>
+// MODE 0: argmax keys; MODE 1: debug dump of logits[M, dv1 - dv0]; MODE 2: argmax keys and every scaled
+// logit stored as [position][vocabulary row][path] for the distribution-level rule.
+template <typename T, int MODE>
 __global__ __launch_bounds__(256) void lmhead_generic_kernel(const T* __restrict__ W, const T* __restrict__ A,
                                                              unsigned long long* __restrict__ keys, int64_t M,
                                                              int d, int d_pad, int V, int vtile0,
                                                              float* __restrict__ logits, int dv0, int dv1,
-                                                             float scale) {
+                                                             float scale, LogitStore store) {
+  constexpr bool DUMP = MODE == 1;
   __shared__ __attribute__((aligned(16))) float As[GK][GT + 4];
   __shared__ __attribute__((aligned(16))) float Ws[GK][GT + 4];
   const int tid = threadIdx.x;
@@ -76,6 +79,21 @@ __global__ __launch_bounds__(256) void lmhead_generic_kernel(const T* __restrict
     return;
   }
 
+  if (MODE == 2) {
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const int64_t m = m0 + ty * 4 + x;
+      if (m >= M) continue;
+      const int64_t pos = m / store.K;
+      float* row = store.lt + pos * store.V * (int64_t)store.K4 + (m - pos * store.K);
+#pragma unroll
+      for (int y = 0; y < 4; ++y) {
+        const int v = v0 + tx * 4 + y;
+        if (v < V) row[(int64_t)v * store.K4] = scale * acc[x][y];
+      }
+    }
+  }
+
 #pragma unroll
   for (int x = 0; x < 4; ++x) {
     float best = -INFINITY;
@@ -105,7 +123,7 @@ __global__ __launch_bounds__(256) void lmhead_generic_kernel(const T* __restrict
 
 hipError_t launch_lmhead_generic(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g,
                                  int V, bool is_bf16, float* logits, int v0, int v1, float scale,
-                                 hipStream_t stream) {
+                                 const LogitStore& store, hipStream_t stream) {
   const bool dump = logits != nullptr;
   const int tile0 = dump ? v0 / GT : 0;
   const int tile1 = dump ? (v1 + GT - 1) / GT : (V + GT - 1) / GT;
@@ -113,14 +131,15 @@ hipError_t launch_lmhead_generic(const void* W, const void* a_ws, unsigned long 
   const int64_t mtiles = (g.M + GT - 1) / GT;
   if (mtiles > 65535) return hipErrorInvalidValue;
   const dim3 grid((unsigned)(tile1 - tile0), (unsigned)mtiles), block(256);
-#define DM_GEN(T, DUMPV)                                                                                  \
-  lmhead_generic_kernel<T, DUMPV><<<grid, block, 0, stream>>>(static_cast<const T*>(W),                   \
-                                                              static_cast<const T*>(a_ws), keys, g.M, g.d, \
-                                                              g.d_pad, V, tile0, logits, v0, v1, scale)
+  const int mode = dump ? 1 : (store.lt != nullptr ? 2 : 0);
+#define DM_GEN(T, MODE)                                                                                  \
+  lmhead_generic_kernel<T, MODE><<<grid, block, 0, stream>>>(static_cast<const T*>(W),                   \
+                                                             static_cast<const T*>(a_ws), keys, g.M, g.d, \
+                                                             g.d_pad, V, tile0, logits, v0, v1, scale, store)
   if (is_bf16) {
-    if (dump) DM_GEN(uint16_t, true); else DM_GEN(uint16_t, false);
+    if (mode == 1) DM_GEN(uint16_t, 1); else if (mode == 2) DM_GEN(uint16_t, 2); else DM_GEN(uint16_t, 0);
   } else {
-    if (dump) DM_GEN(float, true); else DM_GEN(float, false);
+    if (mode == 1) DM_GEN(float, 1); else if (mode == 2) DM_GEN(float, 2); else DM_GEN(float, 0);
   }
 #undef DM_GEN
   return hipGetLastError();

@@ -97,13 +97,18 @@ __device__ __forceinline__ void dma_copy16_stream(const char* base, uint32_t lan
 }
 
 // Rows [v_lo, v_hi) of W are covered by the grid; workgroup g owns rows_per_wg of them.
-template <int MT, bool DUMP>
+// MODE 0: per-row argmax keys only (the verify path of the token-level rules).
+// MODE 1: debug dump of scaled logits for vocabulary rows [dv0, dv1) into logits[M, dv1 - dv0].
+// MODE 2: argmax keys AND every scaled logit stored for the distribution-level rule, in the
+//         layout [position][vocabulary row][path] (store.lt, see LogitStore).
+template <int MT, int MODE>
 __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* __restrict__ W,
                                                                  const __bf16* __restrict__ A_sw,
                                                                  unsigned long long* __restrict__ keys, int d,
                                                                  int64_t M, int mt_total, int v_lo, int v_hi,
                                                                  int rows_per_wg, float* __restrict__ logits,
-                                                                 int dv0, int dv1, float scale) {
+                                                                 int dv0, int dv1, float scale, LogitStore store) {
+  constexpr bool DUMP = MODE == 1;
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   constexpr int SLAB = slab_bytes(MT);
   constexpr int LOADS_PER_SLAB = 8 + MT;  // DMA instructions one producer lane issues per slab
@@ -179,7 +184,7 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
       DM_BARRIER();                     // slab q complete for everyone; slab q-1 consumed by everyone
       if (q + 2 < total) issue(q + 2);  // into the buffer of slab q-1
       const int n = q / nchunks;
-      if (!DUMP && q - n * nchunks == nchunks - 1) DM_BARRIER();  // pairs with the consumers' tile-end barrier
+      if (MODE != 1 && q - n * nchunks == nchunks - 1) DM_BARRIER();  // pairs with the consumers' tile-end barrier
     }
     return;
   }
@@ -196,6 +201,17 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
     for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mt][vt][r] = 0.f;
+
+  // MODE 2: where this lane's masked rows live in the logit store (row m = path m % K of position m / K)
+  float* lt_row[MT];
+  if (MODE == 2) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int64_t m = (int64_t)(mblk * MT + mt) * 32 + i32;
+      const int64_t pos = m / store.K;
+      lt_row[mt] = (m < M) ? store.lt + pos * store.V * (int64_t)store.K4 + (m - pos * store.K) : nullptr;
+    }
+  }
 
   for (int q = 0; q < total; ++q) {
     DM_BARRIER();
@@ -241,6 +257,20 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
       continue;
     }
 
+    if (MODE == 2) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        if (lt_row[mt] == nullptr) continue;
+#pragma unroll
+        for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int v = v0 + 64 * wave + 32 * vt + 8 * (r >> 2) + 4 * hb + (r & 3);
+            if (v < row_end) lt_row[mt][(int64_t)v * store.K4] = scale * acc[mt][vt][r];
+          }
+      }
+    }
+
     unsigned long long* red = reinterpret_cast<unsigned long long*>(lds + NS * SLAB);  // [4][MT*32]
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -281,7 +311,7 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
 
 template <int MT>
 hipError_t run(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V, int num_cu,
-               float* logits, int v0, int v1, float scale, hipStream_t stream) {
+               float* logits, int v0, int v1, float scale, const LogitStore& store, hipStream_t stream) {
   const bool dump = logits != nullptr;
   const int v_lo = dump ? v0 : 0;
   const int v_hi = dump ? v1 : V;
@@ -295,20 +325,23 @@ hipError_t run(const void* W, const void* a_ws, unsigned long long* keys, const 
   if (gx > cap) gx = cap;
   const int rows_per_wg = (v_hi - v_lo + gx - 1) / gx;
   const dim3 grid((unsigned)gx, (unsigned)mblocks), block(THREADS);
+#define DM_LAUNCH(MODE)                                                                                         \
+  lmhead_mfma_kernel<MT, MODE><<<grid, block, lds_bytes(MT), stream>>>(                                          \
+      static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo, v_hi,    \
+      rows_per_wg, logits, v0, v1, scale, store)
   if (dump)
-    lmhead_mfma_kernel<MT, true><<<grid, block, lds_bytes(MT), stream>>>(
-        static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo, v_hi,
-        rows_per_wg, logits, v0, v1, scale);
+    DM_LAUNCH(1);
+  else if (store.lt != nullptr)
+    DM_LAUNCH(2);
   else
-    lmhead_mfma_kernel<MT, false><<<grid, block, lds_bytes(MT), stream>>>(
-        static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo, v_hi,
-        rows_per_wg, logits, v0, v1, scale);
+    DM_LAUNCH(0);
+#undef DM_LAUNCH
   return hipGetLastError();
 }
 
-template <int MT, bool DUMP>
+template <int MT, int MODE>
 hipError_t raise_lds() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_mfma_kernel<MT, DUMP>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_mfma_kernel<MT, MODE>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(MT));
 }
 
@@ -316,28 +349,30 @@ hipError_t raise_lds() {
 
 hipError_t prepare_lmhead_mfma() {
   hipError_t e;
-  if ((e = raise_lds<1, false>()) != hipSuccess) return e;
-  if ((e = raise_lds<2, false>()) != hipSuccess) return e;
-  if ((e = raise_lds<3, false>()) != hipSuccess) return e;
-  if ((e = raise_lds<4, false>()) != hipSuccess) return e;
-  if ((e = raise_lds<1, true>()) != hipSuccess) return e;
-  if ((e = raise_lds<2, true>()) != hipSuccess) return e;
-  if ((e = raise_lds<3, true>()) != hipSuccess) return e;
-  if ((e = raise_lds<4, true>()) != hipSuccess) return e;
+#define DM_RAISE(MT)                                                                                  \
+  if ((e = raise_lds<MT, 0>()) != hipSuccess || (e = raise_lds<MT, 1>()) != hipSuccess ||             \
+      (e = raise_lds<MT, 2>()) != hipSuccess)                                                         \
+    return e
+  DM_RAISE(1);
+  DM_RAISE(2);
+  DM_RAISE(3);
+  DM_RAISE(4);
+#undef DM_RAISE
   return hipSuccess;
 }
 
 hipError_t launch_lmhead_mfma(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V,
-                              int num_cu, float* logits, int v0, int v1, float scale, hipStream_t stream) {
+                              int num_cu, float* logits, int v0, int v1, float scale, const LogitStore& store,
+                              hipStream_t stream) {
   const int mt_total = (int)(g.M_pad >> 5);
   if (mt_total >= 4) {
     if (mt_total % 4 != 0) return hipErrorInvalidValue;
-    return run<4>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, stream);
+    return run<4>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, stream);
   }
   switch (mt_total) {
-    case 1: return run<1>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, stream);
-    case 2: return run<2>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, stream);
-    case 3: return run<3>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, stream);
+    case 1: return run<1>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, stream);
+    case 2: return run<2>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, stream);
+    case 3: return run<3>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, stream);
     default: return hipErrorInvalidValue;
   }
 }

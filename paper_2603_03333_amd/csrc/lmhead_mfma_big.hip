@@ -114,14 +114,18 @@ __device__ __forceinline__ bool tile_of(const TileWalk& w, const TilePos& p, int
   return p.active && tv < w.NV && tm < w.NMB;
 }
 
-template <int BK, bool DUMP>
+// MODE 0: argmax keys only; MODE 1: debug dump of logits[M, dv1 - dv0]; MODE 2: argmax keys and every
+// scaled logit stored in the layout [position][vocabulary row][path] for the distribution-level rule.
+template <int BK, int MODE>
 __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf16* __restrict__ W,
                                                                      const __bf16* __restrict__ A_sw,
                                                                      unsigned long long* __restrict__ keys, int d,
                                                                      int64_t M, int mt_total, int v_lo, int v_hi,
                                                                      TileWalk walk, float* __restrict__ logits,
-                                                                     int dv0, int dv1, float scale) {
+                                                                     int dv0, int dv1, float scale,
+                                                                     LogitStore store) {
   using C = Cfg<BK>;
+  constexpr bool DUMP = MODE == 1;
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -214,7 +218,7 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
         issue_next(issued);
         ++issued;
       }
-      if (!DUMP && (q % nchunks) == nchunks - 1) DM_BARRIER();  // pairs with the consumers' tile-end barrier
+      if (MODE != 1 && (q % nchunks) == nchunks - 1) DM_BARRIER();  // pairs with the consumers' tile-end barrier
     }
     return;
   }
@@ -278,6 +282,23 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
           }
       }
       continue;
+    }
+
+    if (MODE == 2) {
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+        const int64_t m = (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32;
+        if (m >= M) continue;
+        const int64_t pos = m / store.K;
+        float* row = store.lt + pos * store.V * (int64_t)store.K4 + (m - pos * store.K);
+#pragma unroll
+        for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int v = v0 + 64 * wv + 32 * vt + 8 * (r >> 2) + 4 * hb + (r & 3);
+            if (v < v_hi) row[(int64_t)v * store.K4] = scale * acc[mt][vt][r];
+          }
+      }
     }
 
     unsigned long long* red = reinterpret_cast<unsigned long long*>(lds + C::NS * C::SLAB);  // [4 wv][256 m]
@@ -352,7 +373,7 @@ TileWalk make_walk(int NV, int NMB, int G) {
 
 template <int BK>
 hipError_t run_big(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V, int num_cu,
-                   float* logits, int v0, int v1, float scale, hipStream_t stream) {
+                   float* logits, int v0, int v1, float scale, const LogitStore& store, hipStream_t stream) {
   const bool dump = logits != nullptr;
   const int v_lo = dump ? v0 : 0;
   const int v_hi = dump ? v1 : V;
@@ -365,33 +386,42 @@ hipError_t run_big(const void* W, const void* a_ws, unsigned long long* keys, co
   const TileWalk walk = make_walk(NV, NMB, G);
   const dim3 grid((unsigned)G), block(THREADS);
   const int mt_total = (int)(g.M_pad >> 5);
+#define DM_LAUNCH(MODE)                                                                                            \
+  lmhead_mfma_big_kernel<BK, MODE><<<grid, block, Cfg<BK>::LDS_BYTES, stream>>>(                                    \
+      static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo, v_hi, walk, \
+      logits, v0, v1, scale, store)
   if (dump)
-    lmhead_mfma_big_kernel<BK, true><<<grid, block, Cfg<BK>::LDS_BYTES, stream>>>(
-        static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo, v_hi, walk,
-        logits, v0, v1, scale);
+    DM_LAUNCH(1);
+  else if (store.lt != nullptr)
+    DM_LAUNCH(2);
   else
-    lmhead_mfma_big_kernel<BK, false><<<grid, block, Cfg<BK>::LDS_BYTES, stream>>>(
-        static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo, v_hi, walk,
-        logits, v0, v1, scale);
+    DM_LAUNCH(0);
+#undef DM_LAUNCH
   return hipGetLastError();
 }
 
 constexpr int kBigBK = 64;
 
-}  // namespace
-
-hipError_t prepare_lmhead_mfma_big() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_mfma_big_kernel<kBigBK, false>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, Cfg<kBigBK>::LDS_BYTES);
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_mfma_big_kernel<kBigBK, true>),
+template <int MODE>
+hipError_t raise_lds_big() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_mfma_big_kernel<kBigBK, MODE>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, Cfg<kBigBK>::LDS_BYTES);
 }
 
+}  // namespace
+
+hipError_t prepare_lmhead_mfma_big() {
+  hipError_t e;
+  if ((e = raise_lds_big<0>()) != hipSuccess) return e;
+  if ((e = raise_lds_big<1>()) != hipSuccess) return e;
+  return raise_lds_big<2>();
+}
+
 hipError_t launch_lmhead_mfma_big(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V,
-                                  int num_cu, float* logits, int v0, int v1, float scale, hipStream_t stream) {
+                                  int num_cu, float* logits, int v0, int v1, float scale, const LogitStore& store,
+                                  hipStream_t stream) {
   if (g.M_pad % BM != 0) return hipErrorInvalidValue;
-  return run_big<kBigBK>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, stream);
+  return run_big<kBigBK>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, stream);
 }
 
 }  // namespace dm

@@ -1,6 +1,8 @@
 // Acceptance of draft tokens against the K path tokens of every row: naive token matching
-// (Eq. 4), majority (Eq. 7), then the prefix rule of speculative decoding (chain) or its
-// extension along parent links (tree).  One workgroup per sequence; all integer work.
+// (Eq. 4), majority (Eq. 7), the JS rule (Eq. 6: the partial sums of the JS kernels are added up
+// here, chunks in ascending order) and Algorithm 1 (Eq. 6, else Eq. 7), then the prefix rule of
+// speculative decoding (chain) or its extension along parent links (tree).  One workgroup per
+// sequence.
 #include "kernels.hpp"
 
 namespace dm {
@@ -18,7 +20,8 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long x)
 __global__ __launch_bounds__(256) void vote_accept_kernel(const unsigned long long* __restrict__ keys,
                                                           const int32_t* __restrict__ draft_ids,
                                                           const int32_t* __restrict__ parent, int T, int K,
-                                                          int rule, VoteOut out) {
+                                                          int rule, VoteOut out,
+                                                          const float* __restrict__ part_b, JsGeom jg) {
   extern __shared__ int32_t sm[];
   int32_t* ids = sm;            // [T*K] path tokens of this sequence
   int32_t* vid = ids + T * K;   // [T] mode of each row
@@ -80,7 +83,29 @@ __global__ __launch_bounds__(256) void vote_accept_kernel(const unsigned long lo
       h = forced;
     } else {
       const int32_t g = draft_ids[(int64_t)b * T + t];
-      if (g < 0) {
+      if (rule >= 2) {
+        // Eq. (6): JS(phat || pbar) <= max_i JS(p^(i) || pbar), both sides as float; rule 3 = Alg. 1
+        const float* pb = part_b + ((int64_t)b * T + t) * jg.NC * jg.KS;
+        float js_i = -INFINITY;
+        if (lane < K) {
+          double s = 0.0;
+          for (int c = 0; c < jg.NC; ++c) s += (double)pb[c * jg.KS + lane];
+          js_i = (float)s;
+          if (out.js_heads) out.js_heads[((int64_t)b * T + t) * K + lane] = js_i;
+        }
+        float js_max = js_i;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) js_max = fmaxf(js_max, __shfl_xor(js_max, off, 64));
+        float jd = -1.0f;
+        if (g >= 0) {
+          double s = 0.0;
+          for (int c = 0; c < jg.NC; ++c) s += (double)pb[c * jg.KS + jg.K4];
+          jd = (float)s;
+        }
+        if (lane == 0 && out.js_draft) out.js_draft[(int64_t)b * T + t] = jd;
+        h = (g >= 0 && jd <= js_max) ? 1 : 0;
+        if (rule == 3 && g >= 0 && vid[src] == g) h = 1;
+      } else if (g < 0) {
         h = 0;
       } else if (rule == 1) {
         h = (vid[src] == g) ? 1 : 0;
@@ -139,9 +164,12 @@ hipError_t prepare_vote_accept() {
 }
 
 hipError_t launch_vote_accept(const unsigned long long* keys, const int32_t* draft_ids, const int32_t* parent,
-                              int B, int T, int K, int rule, const VoteOut& out, hipStream_t stream) {
+                              int B, int T, int K, int rule, const VoteOut& out, const float* part_b,
+                              const JsGeom* jg, hipStream_t stream) {
+  if (rule >= 2 && (part_b == nullptr || jg == nullptr || parent != nullptr || K > kJsMaxK)) return hipErrorInvalidValue;
+  const JsGeom geom = jg ? *jg : JsGeom{};
   vote_accept_kernel<<<dim3((unsigned)B), dim3(256), vote_lds_bytes(T, K), stream>>>(keys, draft_ids, parent, T, K,
-                                                                                      rule, out);
+                                                                                      rule, out, part_b, geom);
   return hipGetLastError();
 }
 

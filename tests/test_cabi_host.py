@@ -37,14 +37,19 @@ def test_params_struct_matches_header_field_order():
 def _prm(**kw):
     base = dict(B=1, T=5, K=8, d=256, V=4096, dtype=dmb.DM_F32, p=0.1, seeds=[0])
     base.update(kw)
-    return dmb.make_params(**base)
+    parent_ptr = base.pop("parent_ptr", None)
+    prm, keep = dmb.make_params(**base)
+    if parent_ptr is not None:
+        prm.parent = parent_ptr      # never dereferenced by dm_validate
+    return prm, keep
 
 
 def test_validate_accepts_the_benchmark_shapes():
     for kw in (dict(), dict(d=4096, V=128256, dtype=dmb.DM_BF16, T=8, K=16),
                dict(d=8192, V=128256, dtype=dmb.DM_BF16, B=32, T=8, K=16, seeds=list(range(32))),
                dict(d=4096, V=151936, dtype=dmb.DM_BF16, B=4, T=8, K=32, p=0.2, seeds=[1, 2, 3, 4]),
-               dict(p=0.0), dict(rule=dmb.DM_RULE_MAJORITY, flags=dmb.DM_FLAG_SHARE_MASK_ACROSS_POS)):
+               dict(p=0.0), dict(rule=dmb.DM_RULE_MAJORITY, flags=dmb.DM_FLAG_SHARE_MASK_ACROSS_POS),
+               dict(rule=dmb.DM_RULE_JS, K=5, p=0.3), dict(rule=dmb.DM_RULE_JS_OR_MAJORITY, K=64)):
         prm, keep = _prm(**kw)
         assert dmb.dm_validate(prm) == (dmb.DM_OK, "")
 
@@ -52,7 +57,8 @@ def test_validate_accepts_the_benchmark_shapes():
 @pytest.mark.parametrize("kw,word", [
     (dict(B=0), "B"), (dict(T=0), "T"), (dict(T=5000), "T"), (dict(K=0), "K"), (dict(K=2000), "K"),
     (dict(T=4096, K=8), "T*K"), (dict(d=0), "d"), (dict(V=0), "V"), (dict(dtype=7), "dtype"),
-    (dict(p=1.0), "p"), (dict(p=-0.5), "p"), (dict(p=float("nan")), "p"), (dict(rule=2), "rule"),
+    (dict(p=1.0), "p"), (dict(p=-0.5), "p"), (dict(p=float("nan")), "p"), (dict(rule=4), "rule"), (dict(rule=-1), "rule"),
+    (dict(rule=dmb.DM_RULE_JS, K=65), "K <= 64"), (dict(rule=dmb.DM_RULE_JS_OR_MAJORITY, parent_ptr=1), "chains"),
     (dict(flags=8), "flags"),
 ])
 def test_validate_rejects(kw, word):

@@ -99,3 +99,77 @@ def test_tree_sampled():
 
 def test_batched_sampled():
     _run_config("batched", sample=3)
+
+
+# ------------------------------------------------------------------ distribution-level rule (Eq. 5, 6, Alg. 1)
+def _run_config_js(name, sample):
+    from gpu_harness import JS_ATOL, JS_RTOL
+    wl = wk.CONFIGS[name]
+    print(f"[{name}/js] generating inputs", flush=True)
+    W, h, seeds = wk.make_weight(wl), wk.make_hidden(wl), wk.make_seeds(wl)
+    hd, Wd = to_device(h, wl.dtype), to_device(W, wl.dtype)
+    # undropped head logits for the draft stand-in: a plain library matmul, input preparation only
+    clean = (hd.float().reshape(-1, wl.d) @ Wd.float().T).reshape(wl.B, wl.T, wl.V).cpu().numpy()
+    greedy = clean.argmax(-1).astype(np.int32)
+    draft = wk.make_draft_ids(wl, greedy)
+    probs = wk.make_draft_probs(wl, clean)
+    del clean
+    r = Runner(wl.rows, wl.d, wl.V)
+    try:
+        r.reserve_js(wl.B * wl.T, wl.K)
+        print(f"[{name}/js] running the HIP path", flush=True)
+        res = r.verify_js(wl, hd, Wd, draft, probs, seeds, rule=dmb.DM_RULE_JS_OR_MAJORITY)
+        res2 = r.verify_js(wl, hd, Wd, draft, probs, seeds, rule=dmb.DM_RULE_JS_OR_MAJORITY)
+        for k in res:
+            assert np.array_equal(res[k], res2[k], equal_nan=True), f"{k} not deterministic"
+        del hd, Wd
+    finally:
+        r.close()
+    torch.cuda.empty_cache()
+
+    W64 = W.astype(np.float64)
+    rng = np.random.default_rng(11)
+    rows = [(int(rng.integers(0, wl.B)), int(rng.integers(0, wl.T))) for _ in range(sample)] if sample else \
+           [(b, t) for b in range(wl.B) for t in range(wl.T)]
+    print(f"[{name}/js] oracle on {len(rows)} positions", flush=True)
+    near = 0
+    worst_h = worst_d = 0.0
+    for b, t in rows:
+        Hm = np.stack([orc.masked_state(h[b, t], orc.keep_mask(int(seeds[b]), 0, t, i, wl.d, wl.p), wl.p)
+                       for i in range(wl.K)])
+        L = (W64 @ Hm.T).T
+        js_hit, jd, jh = orc.js_rule(probs[b, t], L)
+        assert np.all(np.abs(res["js_heads"][b, t] - jh) <= JS_ATOL + JS_RTOL * np.abs(jh)), (b, t)
+        worst_h = max(worst_h, float(np.abs(res["js_heads"][b, t] - jh).max()))
+        if draft[b, t] < 0:
+            assert res["js_draft"][b, t] == -1.0 and res["hit"][b, t] == 0
+            continue
+        assert abs(res["js_draft"][b, t] - jd) <= JS_ATOL + JS_RTOL * abs(jd), (b, t)
+        worst_d = max(worst_d, abs(float(res["js_draft"][b, t]) - jd))
+        if abs(jh.max() - jd) <= 2 * (JS_ATOL + JS_RTOL * abs(jd)):
+            near += 1
+        else:
+            gpu_js = res["js_draft"][b, t] <= res["js_heads"][b, t].max()
+            assert bool(gpu_js) == bool(js_hit), (b, t)
+    print(f"[{name}/js] checked positions={len(rows)} near-tie={near} max|d js_heads|={worst_h:.2e} "
+          f"max|d js_draft|={worst_d:.2e}", flush=True)
+    # rule + prefix logic on the GPU's own JS values and path tokens: exact at any size
+    has = draft >= 0
+    gpu_js = has & (res["js_draft"] <= res["js_heads"].max(-1))
+    votes = orc.acceptance_from_path_ids(res["path_ids"], draft, orc.RULE_MAJORITY)
+    want = gpu_js | votes["hit"].astype(bool)
+    assert np.array_equal(res["hit"].astype(bool), want)
+    exp = orc.acceptance_from_hits(want)
+    for k in ("accept_mask", "accept_len", "best_node"):
+        assert np.array_equal(res[k], exp[k]), f"{name}/js: {k} differs"
+    assert np.array_equal(res["vote_ids"], votes["vote_ids"])
+    del W, W64
+    gc.collect()
+
+
+def test_head8b_js_full():
+    _run_config_js("head8b", sample=0)
+
+
+def test_batched_js_sampled():
+    _run_config_js("batched", sample=3)

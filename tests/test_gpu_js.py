@@ -1,0 +1,153 @@
+"""Parity of the distribution-level rules (Eq. 5, Eq. 6, Algorithm 1) on the HIP path with the CPU
+oracle, through the C ABI.  Bars: path tokens / votes as in the token-level tests; JS values within
+JS_ATOL + JS_RTOL * |JS| (derivation in gpu_harness); per-row decisions and accept lengths equal
+to the oracle's, except that at rows whose Eq. (6) margin lies inside the tolerance band the
+GPU's own float32 comparison is taken (counted, printed) and the acceptance is re-derived from
+it with the oracle's rule logic."""
+import numpy as np
+import pytest
+
+from oracle import dropmatch_oracle as orc
+from paper_2603_03333_amd import workloads as wk
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("no GPU", allow_module_level=True)
+
+from paper_2603_03333_amd import binding as dmb  # noqa: E402
+from gpu_harness import Runner, compare_js, compare_path_ids, to_device  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def runner():
+    r = Runner(max_rows=4096, max_d=4096, max_V=8192)
+    r.reserve_js(max_positions=64, max_K=64)
+    yield r
+    r.close()
+
+
+def _problem(d, V, dtype, B, T, K, p, seed, bonus=True, planted=0.0, topk=0, sigma=0.02):
+    wl = wk.Workload("js", d=d, V=V, dtype=dtype, B=B, T=T, K=K, p=p, bonus=bonus, data_seed=seed)
+    W = wk.make_weight(wl, sigma=sigma)
+    h = wk.make_planted_hidden(wl, W, planted)[0] if planted else wk.make_hidden(wl)
+    seeds = wk.make_seeds(wl, base_seed=29)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    clean = np.einsum("vd,btd->btv", W.astype(np.float64), h.astype(np.float64)).astype(np.float32)
+    probs = wk.make_draft_probs(wl, clean, topk=topk)
+    return wl, W, h, seeds, draft, probs
+
+
+def _check(runner, wl, W, h, seeds, draft, probs, rule, label):
+    o_rule = orc.RULE_JS if rule == dmb.DM_RULE_JS else orc.RULE_JS_OR_MAJORITY
+    ref = orc.verify_js(h, W, draft, probs, seeds, wl.K, wl.p, rule=o_rule)
+    hd, Wd = to_device(h, wl.dtype), to_device(W, wl.dtype)
+    res = runner.verify_js(wl, hd, Wd, draft, probs, seeds, rule=rule)
+    nflip, nnear = compare_path_ids(res["path_ids"], ref["path_ids"], ref["gap"])
+    votes = orc.acceptance_from_path_ids(res["path_ids"], draft, orc.RULE_MAJORITY)
+    assert np.array_equal(res["vote_ids"], votes["vote_ids"]) and np.array_equal(res["vote_cnt"], votes["vote_cnt"])
+    n_tie, gpu_js = compare_js(res, ref, draft, rule == dmb.DM_RULE_JS, nflip, label)
+    want_hit = gpu_js.copy()
+    if rule == dmb.DM_RULE_JS_OR_MAJORITY:
+        want_hit |= votes["hit"].astype(bool)
+    assert np.array_equal(res["hit"].astype(bool), want_hit), f"{label}: hit"
+    exp = orc.acceptance_from_hits(want_hit)
+    for k in ("accept_mask", "accept_len", "best_node"):
+        assert np.array_equal(res[k], exp[k]), f"{label}: {k}"
+    if n_tie == 0 and nflip == 0:       # then everything must equal the oracle's own outputs
+        for k in ("hit", "accept_mask", "accept_len", "best_node"):
+            assert np.array_equal(res[k], ref[k]), f"{label}: {k} vs oracle"
+    return ref, res
+
+
+@pytest.mark.parametrize("rule", [dmb.DM_RULE_JS, dmb.DM_RULE_JS_OR_MAJORITY])
+def test_tiny_config_fp32_generic_kernel(runner, rule):
+    wl = wk.CONFIGS["tiny"]
+    W, h, seeds = wk.make_weight(wl), wk.make_hidden(wl), wk.make_seeds(wl)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    clean = np.einsum("vd,btd->btv", W.astype(np.float64), h.astype(np.float64)).astype(np.float32)
+    probs = wk.make_draft_probs(wl, clean)
+    _check(runner, wl, W, h, seeds, draft, probs, rule, f"tiny/f32 rule={rule}")
+
+
+@pytest.mark.parametrize("d,V,B,T,K,p", [
+    (256, 4096, 1, 6, 5, 0.3),      # the paper's operating point K = 5, p = 0.3 (K4 = 8)
+    (512, 5000, 2, 4, 16, 0.1),     # three vocabulary chunks, the last one ragged
+    (256, 1000, 1, 3, 1, 0.2),      # K = 1: the centroid is the single head, radius 0
+    (128, 2048, 1, 2, 33, 0.1),     # K4 = 36 -> widest register tile of the JS kernels
+    (256, 3000, 4, 8, 12, 0.2),     # 384 rows: the 256 x 256 MFMA kernel stores the logits
+    (192, 777, 1, 5, 64, 0.05),     # K = 64, the limit
+])
+def test_bf16_mfma_shapes(runner, d, V, B, T, K, p):
+    wl, W, h, seeds, draft, probs = _problem(d, V, "bf16", B, T, K, p, seed=300 + K)
+    _check(runner, wl, W, h, seeds, draft, probs, dmb.DM_RULE_JS_OR_MAJORITY, f"bf16 d={d} V={V} B={B} T={T} K={K}")
+
+
+def test_peaked_heads_majority_branch(runner):
+    """Planted dominant tokens: heads agree, the cluster is tight, Eq. (6) rejects drafts that are
+    close but not inside, and Algorithm 1's second branch (Eq. 7) accepts matching tokens."""
+    wl, W, h, seeds, draft, probs = _problem(256, 4096, "bf16", 2, 6, 5, 0.3, seed=410, planted=12.0, sigma=0.05)
+    ref, res = _check(runner, wl, W, h, seeds, draft, probs, dmb.DM_RULE_JS_OR_MAJORITY, "planted")
+    js_only = orc.verify_js(h, W, draft, probs, seeds, wl.K, wl.p, rule=orc.RULE_JS)
+    assert ref["hit"].sum() > js_only["hit"].sum(), "the probe should exercise the majority branch"
+
+
+def test_truncated_draft_distribution_has_zeros(runner):
+    wl, W, h, seeds, draft, probs = _problem(256, 4096, "bf16", 1, 4, 8, 0.1, seed=420, topk=50)
+    assert (probs == 0).any()
+    _check(runner, wl, W, h, seeds, draft, probs, dmb.DM_RULE_JS, "topk-50 draft")
+
+
+def test_p_zero_cluster_collapses(runner):
+    wl, W, h, seeds, draft, probs = _problem(256, 2048, "bf16", 1, 4, 8, 0.0, seed=430)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    res = runner.verify_js(wl, hd, Wd, draft, probs, seeds, rule=dmb.DM_RULE_JS_OR_MAJORITY)
+    assert np.all(np.abs(res["js_heads"]) < 1e-6)
+    greedy = orc.greedy_ids(h, W)
+    assert np.array_equal(res["hit"].astype(bool), (draft == greedy) & (draft >= 0))
+
+
+def test_js_is_deterministic_and_optional_outputs(runner):
+    wl, W, h, seeds, draft, probs = _problem(256, 4096, "bf16", 2, 4, 8, 0.1, seed=440)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    a = runner.verify_js(wl, hd, Wd, draft, probs, seeds)
+    b = runner.verify_js(wl, hd, Wd, draft, probs, seeds)
+    for k in a:
+        assert np.array_equal(a[k], b[k], equal_nan=True), k
+    prm, keep = runner.params(wl, seeds, rule=dmb.DM_RULE_JS)
+    acc = torch.zeros(wl.B, dtype=torch.int32, device="cuda")
+    dmb.dropmatch_verify_js(runner.ctx, prm, hd, Wd, torch.from_numpy(draft).cuda(),
+                            torch.from_numpy(probs).cuda(), acc)
+    torch.cuda.synchronize()
+    only = runner.verify_js(wl, hd, Wd, draft, probs, seeds, rule=dmb.DM_RULE_JS)
+    assert np.array_equal(acc.cpu().numpy(), only["accept_len"])
+
+
+def test_js_argument_errors(runner):
+    wl, W, h, seeds, draft, probs = _problem(64, 256, "bf16", 1, 2, 4, 0.1, seed=450)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    dd, pd = torch.from_numpy(draft).cuda(), torch.from_numpy(probs).cuda()
+    acc = torch.zeros(1, dtype=torch.int32, device="cuda")
+    prm, keep = runner.params(wl, seeds, rule=dmb.DM_RULE_ANY)
+    with pytest.raises(dmb.DropMatchError):           # token-level rule through the JS entry point
+        dmb.dropmatch_verify_js(runner.ctx, prm, hd, Wd, dd, pd, acc)
+    prm, keep = runner.params(wl, seeds, rule=dmb.DM_RULE_JS)
+    with pytest.raises(dmb.DropMatchError):           # JS rule through the token-level entry point
+        dmb.dropmatch_verify(runner.ctx, prm, hd, Wd, dd, acc)
+    with pytest.raises(dmb.DropMatchError):           # no draft distribution
+        dmb.dropmatch_verify_js(runner.ctx, prm, hd, Wd, dd, None, acc)
+    par = torch.tensor([[-1, 0]], dtype=torch.int32, device="cuda")
+    prm, keep = runner.params(wl, seeds, rule=dmb.DM_RULE_JS, parent=par)
+    with pytest.raises(dmb.DropMatchError):           # trees are not defined for these rules
+        dmb.dropmatch_verify_js(runner.ctx, prm, hd, Wd, dd, pd, acc)
+    fresh = Runner(max_rows=64, max_d=64, max_V=256)
+    try:
+        prm, keep = fresh.params(wl, seeds, rule=dmb.DM_RULE_JS)
+        with pytest.raises(dmb.DropMatchError):       # dm_reserve_js was never called
+            dmb.dropmatch_verify_js(fresh.ctx, prm, hd, Wd, dd, pd, acc)
+        fresh.reserve_js(1, 4)
+        with pytest.raises(dmb.DropMatchError):       # two positions > the one reserved
+            dmb.dropmatch_verify_js(fresh.ctx, prm, hd, Wd, dd, pd, acc)
+    finally:
+        fresh.close()
