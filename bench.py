@@ -28,6 +28,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=100,
                     help="untimed steps; the first ~50 steps after idle run at ramping clocks")
     ap.add_argument("--workload", default="head8b", help="head8b (the benchmark line), tiny, bigvocab, tree, batched")
+    ap.add_argument("--rule", default="any", choices=["any", "majority", "js", "alg1"],
+                    help="acceptance rule: any (Eq. 4, the benchmark line), majority (Eq. 7), js (Eq. 6), "
+                         "alg1 (Algorithm 1 = Eq. 6 else Eq. 7); js/alg1 go through dropmatch_verify_js")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (for profiler runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain device copy of 1 GiB (reference for HBM counters under rocprofv3 --pmc)")
@@ -46,7 +49,7 @@ def read_traffic(workload):
     return None
 
 
-def cpu_baseline(wl, W, h, draft, seeds, parent):
+def cpu_baseline(wl, W, h, draft, seeds, parent, probs=None, rule=0):
     """The oracle, as it stands, on the first rows of sequence 0 of the same inputs."""
     import numpy as np
     from oracle import dropmatch_oracle as orc
@@ -59,8 +62,12 @@ def cpu_baseline(wl, W, h, draft, seeds, parent):
     reps, total = 0, 0.0
     while reps < 20 and total < 10.0:          # about 10 s of CPU work
         t0 = time.perf_counter()
-        out = orc.verify(h[:1, :n_pos], W, draft[:1, :n_pos], seeds[:1], wl.K, wl.p,
-                         parent=None if parent is None else parent[:1, :n_pos])
+        if probs is not None:
+            out = orc.verify_js(h[:1, :n_pos], W, draft[:1, :n_pos], probs[:1, :n_pos], seeds[:1], wl.K, wl.p,
+                                rule=rule)
+        else:
+            out = orc.verify(h[:1, :n_pos], W, draft[:1, :n_pos], seeds[:1], wl.K, wl.p, rule=rule,
+                             parent=None if parent is None else parent[:1, :n_pos])
         total += time.perf_counter() - t0
         reps += 1
         assert out["path_ids"].shape == (1, n_pos, wl.K)
@@ -100,8 +107,18 @@ def main():
     best_val = torch.full((hf.shape[0],), -float("inf"), device="cuda")
     best_idx = torch.zeros((hf.shape[0],), dtype=torch.int64, device="cuda")
     chunk = 16384
+    js = args.rule in ("js", "alg1")
+    rule = {"any": dmb.DM_RULE_ANY, "majority": dmb.DM_RULE_MAJORITY, "js": dmb.DM_RULE_JS,
+            "alg1": dmb.DM_RULE_JS_OR_MAJORITY}[args.rule]
+    if js and wl.tree:
+        print("bench.py: the distribution-level rules are defined for chains only", file=sys.stderr)
+        sys.exit(2)
+    clean = np.empty((hf.shape[0], wl.V), dtype=np.float32) if js else None   # undropped logits for the draft stand-in
     for c0 in range(0, wl.V, chunk):
-        val, idx = (hf @ W_dev[c0:c0 + chunk].float().T).max(dim=1)
+        blk = hf @ W_dev[c0:c0 + chunk].float().T
+        if js:
+            clean[:, c0:c0 + chunk] = blk.cpu().numpy()
+        val, idx = blk.max(dim=1)
         upd = val > best_val
         best_val = torch.where(upd, val, best_val)
         best_idx = torch.where(upd, idx + c0, best_idx)
@@ -116,9 +133,17 @@ def main():
     draft_dev = torch.from_numpy(draft).cuda()
     parent_dev = None if parent is None else torch.from_numpy(parent).cuda()
 
+    probs = probs_dev = None
+    if js:
+        probs = wk.make_draft_probs(wl, clean.reshape(wl.B, wl.T, wl.V))
+        probs_dev = torch.from_numpy(probs).cuda()
+        del clean
+
     ctx = dmb.dm_create(0, wl.rows, wl.d, wl.V)
+    if js:
+        dmb.dm_reserve_js(ctx, wl.B * wl.T, wl.K)
     prm, keep = dmb.make_params(wl.B, wl.T, wl.K, wl.d, wl.V, dmb.DM_BF16 if bf16 else dmb.DM_F32, wl.p,
-                                [int(s) for s in seeds], parent=parent_dev)
+                                [int(s) for s in seeds], parent=parent_dev, rule=rule)
     kernel = dmb.dm_kernel_choice(prm)
     out = dict(accept_len=torch.zeros(wl.B, dtype=torch.int32, device="cuda"),
                best_node=torch.zeros(wl.B, dtype=torch.int32, device="cuda"),
@@ -129,8 +154,15 @@ def main():
                vote_cnt=torch.zeros((wl.B, wl.T), dtype=torch.int32, device="cuda"))
     stream = torch.cuda.current_stream()
 
+    if js:
+        out["js_draft"] = torch.zeros((wl.B, wl.T), dtype=torch.float32, device="cuda")
+        out["js_heads"] = torch.zeros((wl.B, wl.T, wl.K), dtype=torch.float32, device="cuda")
+
     def step():
-        dmb.dropmatch_verify(ctx, prm, h_dev, W_dev, draft_dev, stream=stream, **out)
+        if js:
+            dmb.dropmatch_verify_js(ctx, prm, h_dev, W_dev, draft_dev, probs_dev, stream=stream, **out)
+        else:
+            dmb.dropmatch_verify(ctx, prm, h_dev, W_dev, draft_dev, stream=stream, **out)
 
     for _ in range(args.warmup):
         step()
@@ -148,7 +180,7 @@ def main():
     dmb.dm_set_profiling(ctx, True)
     for _ in range(nprof):
         step()
-    n_calls, ms_mask, ms_lm, ms_vote = dmb.dm_get_profile(ctx)
+    n_calls, (ms_mask, ms_lm, ms_js1, ms_js2, ms_vote) = dmb.dm_get_profile_stages(ctx)
     dmb.dm_set_profiling(ctx, False)
 
     if args.copy_calibration:
@@ -165,6 +197,8 @@ def main():
     else:
         m_pad = (M + 127) // 128 * 128
     alg_bytes = wl.V * wl.d * esize + m_pad * wl.d * esize + M * 8
+    if js:                                   # the contraction also writes every logit once for Eq. (5)/(6)
+        alg_bytes += M * wl.V * 4
     alg_flops = 2.0 * M * wl.d * wl.V
     sec = ms_lm * 1e-3
     if kernel == 1 and M * 2.0 / esize <= MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
@@ -174,11 +208,18 @@ def main():
     else:
         roof = {"bound": "alu", "achieved": alg_flops / sec / 1e12, "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = read_traffic(wl.name)
+    roof["traffic"] = read_traffic(wl.name) if args.rule in ("any", "majority") else None
     roof["kernel"] = ("lmhead_mfma_kernel" if M <= 128 else "lmhead_mfma_big_kernel") if kernel == 1 \
         else "lmhead_generic_kernel"
     roof["kernel_ms"] = ms_lm
     roof["other_kernels_ms"] = {"mask_rows": ms_mask, "vote_accept": ms_vote}
+    if js:
+        k4 = (wl.K + 3) // 4 * 4
+        pass_bytes = wl.B * wl.T * wl.V * 4 * k4          # stored logits read once per JS pass
+        roof["other_kernels_ms"].update({"js_stats": ms_js1, "js_terms": ms_js2})
+        roof["js_passes"] = {"bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBS,
+                             "js_stats_achieved": pass_bytes / (ms_js1 * 1e-3) / 1e9,
+                             "js_terms_achieved": (pass_bytes + wl.B * wl.T * wl.V * 4) / (ms_js2 * 1e-3) / 1e9}
     roof["events_over_calls"] = n_calls
 
     result = {
@@ -190,11 +231,11 @@ def main():
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: d={wl.d} V={wl.V} {wl.dtype} B={wl.B} T={wl.T} K={wl.K} p={wl.p}"
                                + (" tree" if wl.tree else " chain") + (" +bonus row" if wl.bonus else ""),
-                   "rows": M, "positions_per_step": positions, "rule": "any"},
+                   "rows": M, "positions_per_step": positions, "rule": args.rule},
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, W, h, draft, seeds, parent)
+        result["cpu_baseline"] = cpu_baseline(wl, W, h, draft, seeds, parent, probs, rule)
     dmb.dm_destroy(ctx)
     print(json.dumps(result), flush=True)
 

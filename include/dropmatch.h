@@ -70,6 +70,7 @@ typedef enum {
 #define DM_MAX_ROWS_PER_SEQ 4096 /* T */
 #define DM_MAX_TK 16384          /* T*K per sequence (path tokens of a sequence live in LDS) */
 #define DM_MAX_K_JS 64           /* paths per row with the distribution-level rules */
+#define DM_MAX_TK_JS 8192        /* T*K per sequence with the distribution-level rules */
 
 typedef struct {
   int32_t B;       /* sequences, >= 1 */
@@ -153,7 +154,7 @@ dm_status dropmatch_verify(dm_ctx* ctx, const dm_params* prm,
  * or, under DM_RULE_JS_OR_MAJORITY (Algorithm 1), iff Eq. 6 holds or else Eq. 7 holds.
  * JS(P||Q) = KL(P||M)/2 + KL(Q||M)/2, M = (P+Q)/2, natural logarithm, 0 ln 0 = 0; both sides of
  * Eq. 6 are compared as float.  Chains only (prm->parent must be NULL; the paper pairs tree decoding
- * with naive matching only), K <= DM_MAX_K_JS.  A row with draft id < 0 never hits.
+ * with naive matching only), K <= DM_MAX_K_JS, T*K <= DM_MAX_TK_JS.  A row with draft id < 0 never hits.
  *
  * dm_reserve_js allocates, once, what these rules need beyond dm_create: the logits of every path
  * (max_positions * max_V * roundup(max_K, 4) floats; unlike on the token-level path they are stored,

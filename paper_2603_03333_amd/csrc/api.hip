@@ -76,6 +76,10 @@ const char* check_params(const dm_params* p, char* scratch, size_t n) {
     snprintf(scratch, n, "the distribution-level rules take K <= %d", DM_MAX_K_JS);
     return scratch;
   }
+  if (p->rule >= DM_RULE_JS && (int64_t)p->T * p->K > DM_MAX_TK_JS) {
+    snprintf(scratch, n, "the distribution-level rules take T*K <= %d", DM_MAX_TK_JS);
+    return scratch;
+  }
   if (p->rule >= DM_RULE_JS && p->parent != nullptr)
     return "the distribution-level rules are defined for chains only (parent must be NULL)";
   if (p->flags & ~(DM_FLAG_SHARE_MASK_ACROSS_POS | DM_FLAG_FORCE_GENERIC)) return "unknown bits in flags";
@@ -177,6 +181,9 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
     jg.NC = (prm->V + dm::kJsChunk - 1) / dm::kJsChunk;
     jg.KS = jg.K4 + 4;
     if ((int64_t)prm->B * prm->T > 0x7FFFFFFF) return fail(ctx, DM_EINVAL, "B*T too large");
+    // the contraction kernels address the logit store of one 256-row tile with 32-bit byte offsets
+    if ((int64_t)(256 / prm->K + 2) * prm->V * jg.K4 * 4 >= ((int64_t)1 << 32))
+      return fail(ctx, DM_EUNSUPPORTED, "V = %d is too large for the distribution-level rules with K = %d", prm->V, prm->K);
     if (!ctx->lt) return fail(ctx, DM_EINVAL, "call dm_reserve_js before dropmatch_verify_js");
     if ((size_t)jg.P * (size_t)jg.V * (size_t)jg.K4 > ctx->lt_floats ||
         (size_t)jg.P * (size_t)jg.NC * (size_t)jg.KS > ctx->part_floats)

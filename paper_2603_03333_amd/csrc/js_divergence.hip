@@ -3,8 +3,8 @@
 // Jensen-Shannon divergences JS(p^(i) || pbar), JS(phat || pbar) that Eq. (6) compares.
 //
 // The contraction kernel has stored the scaled logits as lt[(pos * V + v) * K4 + i]; both passes here
-// read that once, coalesced (a thread takes one vocabulary row v = K4 contiguous floats, consecutive
-// threads take consecutive rows).  HBM-bound: 4 * K4 bytes per (position, vocabulary row) per pass.
+// read that once, fully coalesced (see RowMap).  HBM-bound: 4 * K4 bytes per (position, vocabulary
+// row) per pass, plus 4 bytes of the draft distribution in pass 2.
 //
 //   pass 1 (js_stats):  normalisers.  Z_i = max_i + ln sum_v exp(l_i[v] - max_i), with max_i already
 //                       known from the argmax key of the row; for the mean logits lbar[v] the running
@@ -22,12 +22,23 @@ namespace dm {
 namespace {
 
 constexpr int JT = 256;             // threads per workgroup
-constexpr int JV = kJsChunk / JT;   // vocabulary rows per thread
 
 __device__ __forceinline__ float key_logit(unsigned long long key) {
   uint32_t u = (uint32_t)(key >> 32);
   u = (u & 0x80000000u) ? (u & 0x7FFFFFFFu) : ~u;
   return __uint_as_float(u);
+}
+
+// e^x and ln x on the hardware's base-2 units (1 ulp each; the argument scaling adds a relative
+// error of about |x| * 1e-7 to e^x, far inside what Eq. (6) needs).  ln is used on [1, 2] and on
+// probabilities above the smallest normal float.
+__device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896341f); }
+__device__ __forceinline__ float fast_log(float x) { return __builtin_amdgcn_logf(x) * 0.693147180559945309f; }
+
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
 }
 
 __device__ __forceinline__ float wave_sum(float x) {
@@ -38,7 +49,7 @@ __device__ __forceinline__ float wave_sum(float x) {
 
 // ln((1 + e^x) / 2) without overflow
 __device__ __forceinline__ float log_half_1pexp(float x) {
-  return fmaxf(x, 0.f) + log1pf(expf(-fabsf(x))) - 0.693147180559945309f;
+  return fmaxf(x, 0.f) + fast_log(1.0f + fast_exp(-fabsf(x))) - 0.693147180559945309f;
 }
 
 // one JS integrand from ln p, ln q (q = centroid) and the probabilities themselves
@@ -48,84 +59,104 @@ __device__ __forceinline__ float js_term(float lp, float p, float lq, float q) {
   return 0.5f * (q * delta - (p + q) * a);
 }
 
-template <int KP>
-__device__ __forceinline__ void load_row(const float* __restrict__ src, int K4, float (&x)[KP]) {
+// Thread mapping of both passes.  A vocabulary row holds K4 floats; G = KP / 4 consecutive lanes
+// (KP = K4 rounded up to a power of two) take 4 paths each of the same row, so one load instruction
+// of a wavefront covers 64 / G consecutive rows = a contiguous piece of memory, and a lane keeps only
+// 4 running sums.  The mean over the K paths of a row is a butterfly over the G lanes of its group;
+// lane 0 of the group then owns the row's centroid and draft terms.
+template <int G>
+struct RowMap {
+  static constexpr int ROWS_PER_WAVE = 64 / G;
+  static constexpr int ROWS_PER_ITER = (JT / 64) * ROWS_PER_WAVE;
+  static constexpr int ITERS = kJsChunk / ROWS_PER_ITER;
+};
+
+template <int G>
+__device__ __forceinline__ float group_sum(float x) {
 #pragma unroll
-  for (int g = 0; g < KP / 4; ++g) {
-    if (4 * g < K4) {
-      const float4 q = *reinterpret_cast<const float4*>(src + 4 * g);
-      x[4 * g + 0] = q.x;
-      x[4 * g + 1] = q.y;
-      x[4 * g + 2] = q.z;
-      x[4 * g + 3] = q.w;
-    }
-  }
+  for (int off = 1; off < G; off <<= 1) x += __shfl_xor(x, off, 64);
+  return x;
 }
 
-template <int KP>
+// sum over the lanes that hold the same paths (same lane % G), result in every lane
+template <int G>
+__device__ __forceinline__ float column_sum(float x) {
+#pragma unroll
+  for (int off = G; off < 64; off <<= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+
+template <int G>
 __global__ __launch_bounds__(JT) void js_stats_kernel(const float* __restrict__ lt,
                                                       const unsigned long long* __restrict__ keys,
                                                       float* __restrict__ part_a, JsGeom g, float scale) {
+  using RM = RowMap<G>;
+  constexpr int KP = 4 * G;
   __shared__ float red[JT / 64][KP + 2];
   const int pos = blockIdx.x, c = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int K = g.K;
+  const int grp = lane % G, rl = lane / G;
+  const int i0 = 4 * grp;             // first path of this lane
+  const bool active = i0 < g.K4;
 
-  float mx[KP], S[KP];
+  float mx[4], S[4];
 #pragma unroll
-  for (int i = 0; i < KP; ++i) {
-    mx[i] = (i < K) ? scale * key_logit(keys[(int64_t)pos * K + i]) : 0.f;
-    S[i] = 0.f;
+  for (int j = 0; j < 4; ++j) {
+    mx[j] = (i0 + j < K) ? scale * key_logit(keys[(int64_t)pos * K + i0 + j]) : 0.f;
+    S[j] = 0.f;
   }
-  float cb[JV];
-  float cmax = -INFINITY;
-  const float* base = lt + (int64_t)pos * g.V * g.K4;
+  float cmax = -INFINITY, csum = 0.f;  // centroid: running (max, sum of exp relative to it), lane 0 of a group
+  const float* base = lt + (int64_t)pos * g.V * g.K4 + i0;
+  const int v_first = c * kJsChunk + wave * RM::ROWS_PER_WAVE + rl;
+#pragma unroll 4
+  for (int it = 0; it < RM::ITERS; ++it) {
+    const int v = v_first + it * RM::ROWS_PER_ITER;
+    const bool in = v < g.V;
+    float xs = 0.f;
+    if (in && active) {
+      const float4 q = *reinterpret_cast<const float4*>(base + (int64_t)v * g.K4);
+      const float x[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-  for (int j = 0; j < JV; ++j) {
-    const int v = c * kJsChunk + j * JT + tid;
-    cb[j] = -INFINITY;
-    if (v < g.V) {
-      float x[KP];
-      load_row<KP>(base + (int64_t)v * g.K4, g.K4, x);
-      float xs = 0.f;
-#pragma unroll
-      for (int i = 0; i < KP; ++i)
-        if (i < K) {
-          xs += x[i];
-          S[i] += expf(x[i] - mx[i]);
+      for (int j = 0; j < 4; ++j)
+        if (i0 + j < K) {
+          xs += x[j];
+          S[j] += fast_exp(x[j] - mx[j]);
         }
-      cb[j] = xs / (float)K;
-      cmax = fmaxf(cmax, cb[j]);
+    }
+    xs = group_sum<G>(xs);
+    if (in && grp == 0) {
+      const float xbar = xs / (float)K;
+      if (xbar > cmax) {
+        csum *= fast_exp(cmax - xbar);   // cmax = -inf the first time: exp(-inf) = 0
+        cmax = xbar;
+      }
+      csum += fast_exp(xbar - cmax);
     }
   }
-  float csum = 0.f;
-#pragma unroll
-  for (int j = 0; j < JV; ++j)
-    if (cb[j] != -INFINITY) csum += expf(cb[j] - cmax);
 
   // wavefront level
   float wmax = cmax;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) wmax = fmaxf(wmax, __shfl_xor(wmax, off, 64));
-  csum = (cmax == -INFINITY) ? 0.f : csum * expf(cmax - wmax);
+  csum = (cmax == -INFINITY) ? 0.f : csum * fast_exp(cmax - wmax);
   csum = wave_sum(csum);
 #pragma unroll
-  for (int i = 0; i < KP; ++i)
-    if (i < K) {
-      const float t = wave_sum(S[i]);
-      if (lane == 0) red[wave][i] = t;
-    }
+  for (int j = 0; j < 4; ++j) {
+    const float t = column_sum<G>(S[j]);
+    if (lane < G && i0 + j < K) red[wave][i0 + j] = t;
+  }
   if (lane == 0) {
     red[wave][KP] = wmax;
     red[wave][KP + 1] = csum;
   }
   __syncthreads();
-  float* out = part_a + ((int64_t)pos * g.NC + c) * g.KS;
+  float* out = part_a + (int64_t)pos * g.KS * g.NC + c;  // record layout [pos][slot][chunk]
   if (tid < K) {
     float t = red[0][tid];
 #pragma unroll
     for (int w = 1; w < JT / 64; ++w) t += red[w][tid];
-    out[tid] = t;
+    out[(int64_t)tid * g.NC] = t;
   } else if (tid == 64) {
     float m = red[0][KP];
 #pragma unroll
@@ -133,94 +164,115 @@ __global__ __launch_bounds__(JT) void js_stats_kernel(const float* __restrict__ 
     float s = 0.f;
 #pragma unroll
     for (int w = 0; w < JT / 64; ++w)
-      if (red[w][KP] != -INFINITY) s += red[w][KP + 1] * expf(red[w][KP] - m);
-    out[g.K4] = m;
-    out[g.K4 + 1] = s;
+      if (red[w][KP] != -INFINITY) s += red[w][KP + 1] * fast_exp(red[w][KP] - m);
+    out[(int64_t)g.K4 * g.NC] = m;
+    out[(int64_t)(g.K4 + 1) * g.NC] = s;
   }
 }
 
-template <int KP>
+template <int G>
 __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ lt,
                                                       const unsigned long long* __restrict__ keys,
                                                       const float* __restrict__ part_a,
                                                       const float* __restrict__ draft_probs,
                                                       const int32_t* __restrict__ draft_ids,
                                                       float* __restrict__ part_b, JsGeom g, float scale) {
+  using RM = RowMap<G>;
+  constexpr int KP = 4 * G;
   __shared__ float Zs[KP + 1];
   __shared__ float red[JT / 64][KP + 1];
   const int pos = blockIdx.x, c = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int K = g.K;
+  const int grp = lane % G, rl = lane / G;
+  const int i0 = 4 * grp;
+  const bool active = i0 < g.K4;
 
-  // normalisers from the partial sums of pass 1, chunks in ascending order
-  const float* pa = part_a + (int64_t)pos * g.NC * g.KS;
-  if (tid < K) {
-    double s = 0.0;
-    for (int cc = 0; cc < g.NC; ++cc) s += (double)pa[cc * g.KS + tid];
-    Zs[tid] = (float)((double)(scale * key_logit(keys[(int64_t)pos * K + tid])) + log(s));
-  } else if (tid == 64) {
-    float m = -INFINITY;
-    for (int cc = 0; cc < g.NC; ++cc) m = fmaxf(m, pa[cc * g.KS + g.K4]);
-    double s = 0.0;
-    for (int cc = 0; cc < g.NC; ++cc) s += (double)pa[cc * g.KS + g.K4 + 1] * exp((double)pa[cc * g.KS + g.K4] - (double)m);
-    Zs[KP] = (float)((double)m + log(s));
+  // normalisers from the partial sums of pass 1: one wavefront per slot, lanes over chunks, then a
+  // butterfly (a fixed order, the same in every workgroup)
+  const float* pa = part_a + (int64_t)pos * g.KS * g.NC;
+  for (int slot = wave; slot <= K; slot += JT / 64) {
+    if (slot < K) {
+      double s = 0.0;
+      for (int cc = lane; cc < g.NC; cc += 64) s += (double)pa[(int64_t)slot * g.NC + cc];
+      s = wave_sum(s);
+      if (lane == 0) Zs[slot] = (float)((double)(scale * key_logit(keys[(int64_t)pos * K + slot])) + log(s));
+    } else {  // mean logits: chunk records are (max, sum of exp relative to that max)
+      float m = -INFINITY;
+      for (int cc = lane; cc < g.NC; cc += 64) m = fmaxf(m, pa[(int64_t)g.K4 * g.NC + cc]);
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+      double s = 0.0;
+      for (int cc = lane; cc < g.NC; cc += 64)
+        s += (double)pa[(int64_t)(g.K4 + 1) * g.NC + cc] * exp((double)pa[(int64_t)g.K4 * g.NC + cc] - (double)m);
+      s = wave_sum(s);
+      if (lane == 0) Zs[KP] = (float)((double)m + log(s));
+    }
   }
   __syncthreads();
-  float Z[KP], J[KP];
+  float Z[4], J[4];
 #pragma unroll
-  for (int i = 0; i < KP; ++i) {
-    Z[i] = (i < K) ? Zs[i] : 0.f;
-    J[i] = 0.f;
+  for (int j = 0; j < 4; ++j) {
+    Z[j] = (i0 + j < K) ? Zs[i0 + j] : 0.f;
+    J[j] = 0.f;
   }
   const float Zbar = Zs[KP];
   const bool has_draft = draft_ids[pos] >= 0;
   float Jd = 0.f;
-  const float* base = lt + (int64_t)pos * g.V * g.K4;
+  const float* base = lt + (int64_t)pos * g.V * g.K4 + i0;
   const float* dp = draft_probs + (int64_t)pos * g.V;
-#pragma unroll 2
-  for (int j = 0; j < JV; ++j) {
-    const int v = c * kJsChunk + j * JT + tid;
-    if (v < g.V) {
-      float x[KP];
-      load_row<KP>(base + (int64_t)v * g.K4, g.K4, x);
-      float xs = 0.f;
+  const int v_first = c * kJsChunk + wave * RM::ROWS_PER_WAVE + rl;
+#pragma unroll 4
+  for (int it = 0; it < RM::ITERS; ++it) {
+    const int v = v_first + it * RM::ROWS_PER_ITER;
+    const bool in = v < g.V;
+    float x[4] = {0.f, 0.f, 0.f, 0.f};
+    float xs = 0.f;
+    if (in && active) {
+      const float4 q = *reinterpret_cast<const float4*>(base + (int64_t)v * g.K4);
+      x[0] = q.x;
+      x[1] = q.y;
+      x[2] = q.z;
+      x[3] = q.w;
 #pragma unroll
-      for (int i = 0; i < KP; ++i)
-        if (i < K) xs += x[i];
+      for (int j = 0; j < 4; ++j)
+        if (i0 + j < K) xs += x[j];
+    }
+    xs = group_sum<G>(xs);
+    if (in) {
       const float lq = xs / (float)K - Zbar;
-      const float q = expf(lq);
+      const float q = fast_exp(lq);
 #pragma unroll
-      for (int i = 0; i < KP; ++i)
-        if (i < K) {
-          const float lp = x[i] - Z[i];
-          J[i] += js_term(lp, expf(lp), lq, q);
+      for (int j = 0; j < 4; ++j)
+        if (i0 + j < K) {
+          const float lp = x[j] - Z[j];
+          J[j] += js_term(lp, fast_exp(lp), lq, q);
         }
-      if (has_draft) {
+      if (has_draft && grp == 0) {
         const float ph = dp[v];
-        Jd += (ph > 0.f) ? js_term(logf(ph), ph, lq, q) : 0.5f * 0.693147180559945309f * q;
+        Jd += (ph > 1e-37f) ? js_term(fast_log(ph), ph, lq, q) : 0.5f * 0.693147180559945309f * q;
       }
     }
   }
 #pragma unroll
-  for (int i = 0; i < KP; ++i)
-    if (i < K) {
-      const float t = wave_sum(J[i]);
-      if (lane == 0) red[wave][i] = t;
-    }
+  for (int j = 0; j < 4; ++j) {
+    const float t = column_sum<G>(J[j]);
+    if (lane < G && i0 + j < K) red[wave][i0 + j] = t;
+  }
   Jd = wave_sum(Jd);
   if (lane == 0) red[wave][KP] = Jd;
   __syncthreads();
-  float* out = part_b + ((int64_t)pos * g.NC + c) * g.KS;
+  float* out = part_b + (int64_t)pos * g.KS * g.NC + c;
   if (tid < K) {
     float t = red[0][tid];
 #pragma unroll
     for (int w = 1; w < JT / 64; ++w) t += red[w][tid];
-    out[tid] = t;
+    out[(int64_t)tid * g.NC] = t;
   } else if (tid == 64) {
     float t = red[0][KP];
 #pragma unroll
     for (int w = 1; w < JT / 64; ++w) t += red[w][KP];
-    out[g.K4] = t;
+    out[(int64_t)g.K4 * g.NC] = t;
   }
 }
 
@@ -229,11 +281,11 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
 #define DM_JS_DISPATCH(KERNEL, ...)                                                        \
   do {                                                                                     \
     const dim3 grid((unsigned)g.P, (unsigned)g.NC), block(JT);                              \
-    if (g.K4 <= 4) KERNEL<4><<<grid, block, 0, stream>>>(__VA_ARGS__);                      \
-    else if (g.K4 <= 8) KERNEL<8><<<grid, block, 0, stream>>>(__VA_ARGS__);                 \
-    else if (g.K4 <= 16) KERNEL<16><<<grid, block, 0, stream>>>(__VA_ARGS__);               \
-    else if (g.K4 <= 32) KERNEL<32><<<grid, block, 0, stream>>>(__VA_ARGS__);               \
-    else KERNEL<64><<<grid, block, 0, stream>>>(__VA_ARGS__);                               \
+    if (g.K4 <= 4) KERNEL<1><<<grid, block, 0, stream>>>(__VA_ARGS__);                      \
+    else if (g.K4 <= 8) KERNEL<2><<<grid, block, 0, stream>>>(__VA_ARGS__);                 \
+    else if (g.K4 <= 16) KERNEL<4><<<grid, block, 0, stream>>>(__VA_ARGS__);                \
+    else if (g.K4 <= 32) KERNEL<8><<<grid, block, 0, stream>>>(__VA_ARGS__);                \
+    else KERNEL<16><<<grid, block, 0, stream>>>(__VA_ARGS__);                               \
   } while (0)
 
 hipError_t launch_js_stats(const float* lt, const unsigned long long* keys, float* part_a, const JsGeom& g,

@@ -61,20 +61,20 @@ hipError_t prepare_lmhead_mfma_big();
 // Distribution-level rule (Eq. (5), (6)) over the stored logits, in two passes over the vocabulary;
 // each workgroup takes kJsChunk vocabulary rows of one position and leaves partial sums that the
 // next kernel adds up in a fixed order (so results do not depend on scheduling).
-constexpr int kJsChunk = 2048;  // vocabulary rows per workgroup
+constexpr int kJsChunk = 1024;  // vocabulary rows per workgroup
 constexpr int kJsMaxK = 64;     // paths per row the distribution-level rule takes
 struct JsGeom {
   int P;    // positions B*T
   int K, K4;
   int V;
   int NC;   // ceil(V / kJsChunk)
-  int KS;   // floats per (position, chunk) record in part_a / part_b: K4 + 4
+  int KS;   // slots per position in part_a / part_b (layout [pos][slot][chunk]): K4 + 4
 };
-// Pass 1: part_a[pos][c][i] = sum over the chunk of exp(l_i[v] - max_v l_i) for path i < K;
-// [K4] / [K4+1] = running (max, sum of exp) of the mean logits of the chunk.
+// Pass 1: part_a[pos][i][c] = sum over chunk c of exp(l_i[v] - max_v l_i) for path i < K;
+// slots K4 / K4+1 = (max, sum of exp relative to it) of the mean logits over the chunk.
 hipError_t launch_js_stats(const float* lt, const unsigned long long* keys, float* part_a, const JsGeom& g,
                            float scale, hipStream_t stream);
-// Pass 2: part_b[pos][c][i] = chunk's share of JS(p^(i) || pbar) for i < K; [K4] = of JS(phat || pbar).
+// Pass 2: part_b[pos][i][c] = chunk's share of JS(p^(i) || pbar) for i < K; slot K4 = of JS(phat || pbar).
 hipError_t launch_js_terms(const float* lt, const unsigned long long* keys, const float* part_a,
                            const float* draft_probs, const int32_t* draft_ids, float* part_b, const JsGeom& g,
                            float scale, hipStream_t stream);

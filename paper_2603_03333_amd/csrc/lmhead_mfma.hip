@@ -202,14 +202,22 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mt][vt][r] = 0.f;
 
-  // MODE 2: where this lane's masked rows live in the logit store (row m = path m % K of position m / K)
-  float* lt_row[MT];
+  // MODE 2: where this lane's masked rows live in the logit store (row m = path m % K of position
+  // m / K), as a 32-bit byte offset from the first position of the workgroup's row block, so that a
+  // store needs one address register (uniform base + lane offset).  The lane's 4 * hb vocabulary-row
+  // offset is folded in.
+  uint32_t lt_off[MT];
+  bool lt_ok[MT];
+  char* lt_base = nullptr;
   if (MODE == 2) {
+    const int64_t pos0 = ((int64_t)mblk * MT * 32) / store.K;
+    lt_base = reinterpret_cast<char*>(store.lt + pos0 * store.V * (int64_t)store.K4);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int64_t m = (int64_t)(mblk * MT + mt) * 32 + i32;
       const int64_t pos = m / store.K;
-      lt_row[mt] = (m < M) ? store.lt + pos * store.V * (int64_t)store.K4 + (m - pos * store.K) : nullptr;
+      lt_ok[mt] = m < M;
+      lt_off[mt] = (uint32_t)(((pos - pos0) * store.V * store.K4 + (m - pos * store.K) + 4 * hb * store.K4) * 4);
     }
   }
 
@@ -259,16 +267,16 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
 
     if (MODE == 2) {
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        if (lt_row[mt] == nullptr) continue;
+      for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
+        for (int r = 0; r < 16; ++r) {
+          const int vu = v0 + 64 * wave + 32 * vt + 8 * (r >> 2) + (r & 3);  // + 4 * hb per lane
+          char* dst = lt_base + (int64_t)vu * store.K4 * 4;
+          const bool v_ok = vu + 4 * hb < row_end;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int v = v0 + 64 * wave + 32 * vt + 8 * (r >> 2) + 4 * hb + (r & 3);
-            if (v < row_end) lt_row[mt][(int64_t)v * store.K4] = scale * acc[mt][vt][r];
-          }
-      }
+          for (int mt = 0; mt < MT; ++mt)
+            if (lt_ok[mt] && v_ok) *reinterpret_cast<float*>(dst + lt_off[mt]) = scale * acc[mt][vt][r];
+        }
     }
 
     unsigned long long* red = reinterpret_cast<unsigned long long*>(lds + NS * SLAB);  // [4][MT*32]

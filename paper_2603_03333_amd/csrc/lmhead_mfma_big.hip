@@ -285,20 +285,31 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
     }
 
     if (MODE == 2) {
+      // row m = path m % K of position m / K; stores use a uniform base (first position of this
+      // wavefront's 128 rows) plus one 32-bit lane offset
+      const int64_t m_first = (int64_t)tm_c * BM + wm * 128;
+      const int64_t pos0 = m_first / store.K;
+      char* lt_base = reinterpret_cast<char*>(store.lt + pos0 * store.V * (int64_t)store.K4);
+      uint32_t lt_off[4];
+      bool lt_ok[4];
 #pragma unroll
       for (int mt = 0; mt < 4; ++mt) {
-        const int64_t m = (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32;
-        if (m >= M) continue;
+        const int64_t m = m_first + mt * 32 + i32;
         const int64_t pos = m / store.K;
-        float* row = store.lt + pos * store.V * (int64_t)store.K4 + (m - pos * store.K);
-#pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int v = v0 + 64 * wv + 32 * vt + 8 * (r >> 2) + 4 * hb + (r & 3);
-            if (v < v_hi) row[(int64_t)v * store.K4] = scale * acc[mt][vt][r];
-          }
+        lt_ok[mt] = m < M;
+        lt_off[mt] = (uint32_t)(((pos - pos0) * store.V * store.K4 + (m - pos * store.K) + 4 * hb * store.K4) * 4);
       }
+#pragma unroll
+      for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int vu = v0 + 64 * wv + 32 * vt + 8 * (r >> 2) + (r & 3);  // + 4 * hb per lane
+          char* dst = lt_base + (int64_t)vu * store.K4 * 4;
+          const bool v_ok = vu + 4 * hb < v_hi;
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt)
+            if (lt_ok[mt] && v_ok) *reinterpret_cast<float*>(dst + lt_off[mt]) = scale * acc[mt][vt][r];
+        }
     }
 
     unsigned long long* red = reinterpret_cast<unsigned long long*>(lds + C::NS * C::SLAB);  // [4 wv][256 m]

@@ -27,6 +27,7 @@ __global__ __launch_bounds__(256) void vote_accept_kernel(const unsigned long lo
   int32_t* vid = ids + T * K;   // [T] mode of each row
   int32_t* hitv = vid + T;      // [T] per-row rule result
   int32_t* aux = hitv + T;      // [T] tree: depth of accepted nodes, -1 if rejected
+  float* jsv = reinterpret_cast<float*>(aux + T);  // [T][K+1] JS of the K heads, then of the draft (rules 2, 3)
 
   const int b = blockIdx.x;
   const int tid = threadIdx.x;
@@ -41,6 +42,33 @@ __global__ __launch_bounds__(256) void vote_accept_kernel(const unsigned long lo
     if (out.path_ids) out.path_ids[(int64_t)b * TK + x] = id;
   }
   __syncthreads();
+
+  // Eq. (6): total JS of every (row, head) and (row, draft) = its per-chunk partial sums added in
+  // ascending chunk order, one thread per sum (independent loads, so they overlap)
+  if (rule >= 2) {
+    const int K1 = K + 1;
+    for (int x = tid; x < T * K1; x += 256) {
+      const int t = x / K1, i = x - t * K1;
+      const float* src = part_b + (((int64_t)b * T + t) * jg.KS + (i < K ? i : jg.K4)) * jg.NC;
+      double s = 0.0;
+      int c = 0;
+      for (; c + 8 <= jg.NC; c += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[c + u];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += (double)v[u];
+      }
+      for (; c < jg.NC; ++c) s += (double)src[c];
+      const float js = (float)s;
+      jsv[x] = js;
+      if (i < K) {
+        if (out.js_heads) out.js_heads[((int64_t)b * T + t) * K + i] = js;
+      } else if (out.js_draft) {
+        out.js_draft[(int64_t)b * T + t] = draft_ids[(int64_t)b * T + t] >= 0 ? js : -1.0f;
+      }
+    }
+  }
 
   // mode of the K tokens of each row (ties: smallest id), one wavefront per row
   for (int t = wave; t < T; t += 4) {
@@ -85,24 +113,12 @@ __global__ __launch_bounds__(256) void vote_accept_kernel(const unsigned long lo
       const int32_t g = draft_ids[(int64_t)b * T + t];
       if (rule >= 2) {
         // Eq. (6): JS(phat || pbar) <= max_i JS(p^(i) || pbar), both sides as float; rule 3 = Alg. 1
-        const float* pb = part_b + ((int64_t)b * T + t) * jg.NC * jg.KS;
-        float js_i = -INFINITY;
-        if (lane < K) {
-          double s = 0.0;
-          for (int c = 0; c < jg.NC; ++c) s += (double)pb[c * jg.KS + lane];
-          js_i = (float)s;
-          if (out.js_heads) out.js_heads[((int64_t)b * T + t) * K + lane] = js_i;
-        }
-        float js_max = js_i;
+        const float* row = jsv + t * (K + 1);
+        float js_max = -INFINITY;
+        for (int i = lane; i < K; i += 64) js_max = fmaxf(js_max, row[i]);
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) js_max = fmaxf(js_max, __shfl_xor(js_max, off, 64));
-        float jd = -1.0f;
-        if (g >= 0) {
-          double s = 0.0;
-          for (int c = 0; c < jg.NC; ++c) s += (double)pb[c * jg.KS + jg.K4];
-          jd = (float)s;
-        }
-        if (lane == 0 && out.js_draft) out.js_draft[(int64_t)b * T + t] = jd;
+        const float jd = row[K];
         h = (g >= 0 && jd <= js_max) ? 1 : 0;
         if (rule == 3 && g >= 0 && vid[src] == g) h = 1;
       } else if (g < 0) {
@@ -155,20 +171,24 @@ __global__ __launch_bounds__(256) void vote_accept_kernel(const unsigned long lo
 
 }  // namespace
 
-static size_t vote_lds_bytes(int T, int K) { return ((size_t)T * K + 3 * (size_t)T) * sizeof(int32_t); }
+static size_t vote_lds_bytes(int T, int K, int rule) {
+  return ((size_t)T * K + 3 * (size_t)T + (rule >= 2 ? (size_t)T * (K + 1) : 0)) * sizeof(int32_t);
+}
 
 hipError_t prepare_vote_accept() {
   // T*K <= 16384 and T <= 4096: at most 112 KB of LDS
   return hipFuncSetAttribute(reinterpret_cast<const void*>(&vote_accept_kernel),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)vote_lds_bytes(4096, 4));
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)vote_lds_bytes(4096, 4, 0));
 }
 
 hipError_t launch_vote_accept(const unsigned long long* keys, const int32_t* draft_ids, const int32_t* parent,
                               int B, int T, int K, int rule, const VoteOut& out, const float* part_b,
                               const JsGeom* jg, hipStream_t stream) {
-  if (rule >= 2 && (part_b == nullptr || jg == nullptr || parent != nullptr || K > kJsMaxK)) return hipErrorInvalidValue;
+  if (rule >= 2 && (part_b == nullptr || jg == nullptr || parent != nullptr || K > kJsMaxK ||
+                    vote_lds_bytes(T, K, rule) > vote_lds_bytes(4096, 4, 0)))
+    return hipErrorInvalidValue;
   const JsGeom geom = jg ? *jg : JsGeom{};
-  vote_accept_kernel<<<dim3((unsigned)B), dim3(256), vote_lds_bytes(T, K), stream>>>(keys, draft_ids, parent, T, K,
+  vote_accept_kernel<<<dim3((unsigned)B), dim3(256), vote_lds_bytes(T, K, rule), stream>>>(keys, draft_ids, parent, T, K,
                                                                                       rule, out, part_b, geom);
   return hipGetLastError();
 }
