@@ -31,6 +31,8 @@ def parse_args():
     ap.add_argument("--rule", default="any", choices=["any", "majority", "js", "alg1"],
                     help="acceptance rule: any (Eq. 4, the benchmark line), majority (Eq. 7), js (Eq. 6), "
                          "alg1 (Algorithm 1 = Eq. 6 else Eq. 7); js/alg1 go through dropmatch_verify_js")
+    ap.add_argument("--paths", type=int, default=0, help="override K, the dropout paths per row (rows sweep)")
+    ap.add_argument("--batch", type=int, default=0, help="override B, the number of sequences (rows sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (for profiler runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain device copy of 1 GiB (reference for HBM counters under rocprofv3 --pmc)")
@@ -93,6 +95,10 @@ def main():
         sys.exit(3)
     torch.cuda.set_device(0)
     wl = wk.CONFIGS[args.workload]
+    if args.paths:
+        wl = wl.with_(K=args.paths)
+    if args.batch:
+        wl = wl.with_(B=args.batch)
     bf16 = wl.dtype == "bf16"
     tdt = torch.bfloat16 if bf16 else torch.float32
 
