@@ -151,3 +151,18 @@ def test_js_argument_errors(runner):
             dmb.dropmatch_verify_js(fresh.ctx, prm, hd, Wd, dd, pd, acc)
     finally:
         fresh.close()
+
+
+def test_js_size_limits():
+    # DM_MAX_K_JS paths and DM_MAX_TK_JS path tokens per sequence
+    wl, W, h, seeds, draft, probs = _problem(64, 300, "bf16", 1, 128, 64, 0.2, seed=460, sigma=0.3)
+    r = Runner(max_rows=wl.rows, max_d=wl.d, max_V=wl.V)
+    try:
+        r.reserve_js(wl.B * wl.T, wl.K)
+        _check(r, wl, W, h, seeds, draft, probs, dmb.DM_RULE_JS_OR_MAJORITY, "js limits T*K=8192 K=64")
+        for kw in (dict(K=65, T=4), dict(T=129)):
+            prm, keep = r.params(wl.with_(**kw), seeds, rule=dmb.DM_RULE_JS)
+            st, msg = dmb.dm_validate(prm)
+            assert st == dmb.DM_EINVAL and msg
+    finally:
+        r.close()

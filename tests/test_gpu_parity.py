@@ -300,3 +300,26 @@ def test_deep_chain_tree(runner):
     res = runner.verify(wl, to_device(h, "bf16"), to_device(W, "bf16"), draft, seeds, parent=parent)
     _check_against_oracle(res, ref, draft, orc.RULE_ANY, parent=parent, label="deep tree")
     assert res["accept_len"].tolist() == [149, 199]
+
+
+# ------------------------------------------------------------------ the limits the header states
+@pytest.mark.parametrize("d,V,B,T,K", [
+    (64, 40, 1, 4096, 4),     # DM_MAX_ROWS_PER_SEQ rows and DM_MAX_TK path tokens in one sequence
+    (64, 60, 1, 16, 1024),    # DM_MAX_K paths per row
+])
+def test_size_limits(d, V, B, T, K):
+    wl, W, h, seeds, draft = _problem("limit", d, V, "bf16", B, T, K, 0.25, seed=T + K)
+    r = Runner(max_rows=B * T * K, max_d=d, max_V=V)
+    try:
+        hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+        ref = orc.verify(h, W, draft, seeds, K, wl.p, rule=orc.RULE_MAJORITY)
+        res = r.verify(wl, hd, Wd, draft, seeds, rule=orc.RULE_MAJORITY)
+        _check_against_oracle(res, ref, draft, orc.RULE_MAJORITY, label=f"limit T={T} K={K}")
+        # one past each limit is refused before anything is enqueued
+        for kw in (dict(T=T + 1) if T == 4096 else dict(K=K + 1),):
+            big = wl.with_(**kw)
+            prm, keep = r.params(big, seeds)
+            st, msg = dmb.dm_validate(prm)
+            assert st == dmb.DM_EINVAL and msg
+    finally:
+        r.close()
