@@ -33,6 +33,8 @@ def parse_args():
                          "alg1 (Algorithm 1 = Eq. 6 else Eq. 7); js/alg1 go through dropmatch_verify_js")
     ap.add_argument("--paths", type=int, default=0, help="override K, the dropout paths per row (rows sweep)")
     ap.add_argument("--batch", type=int, default=0, help="override B, the number of sequences (rows sweep)")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of a HIP graph that holds one captured step instead of eager calls")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (for profiler runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain device copy of 1 GiB (reference for HBM counters under rocprofv3 --pmc)")
@@ -170,12 +172,26 @@ def main():
         else:
             dmb.dropmatch_verify(ctx, prm, h_dev, W_dev, draft_dev, stream=stream, **out)
 
+    timed = step
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            stream = side
+            step()                                   # warm-up on the capture stream
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            stream = torch.cuda.current_stream()
+            step()
+        stream = torch.cuda.current_stream()
+        timed = graph.replay
     for _ in range(args.warmup):
-        step()
+        timed()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        timed()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
@@ -237,7 +253,8 @@ def main():
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: d={wl.d} V={wl.V} {wl.dtype} B={wl.B} T={wl.T} K={wl.K} p={wl.p}"
                                + (" tree" if wl.tree else " chain") + (" +bonus row" if wl.bonus else ""),
-                   "rows": M, "positions_per_step": positions, "rule": args.rule},
+                   "rows": M, "positions_per_step": positions, "rule": args.rule,
+                   "launch": "hip graph replay" if args.graph else "eager"},
         "roofline": roof,
     }
     if not args.no_cpu_baseline:

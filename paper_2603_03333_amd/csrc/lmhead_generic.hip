@@ -3,7 +3,8 @@
 // GPU implementation the MFMA kernel is compared with in the tests.
 //
 // Workgroup = 256 threads = 64 masked rows x 64 vocabulary rows, 4 x 4 outputs per thread,
-// k in slabs of 16 staged through LDS (stored k-major so the inner loop reads float4).
+// k in slabs of 16 staged through LDS (stored k-major so the inner loop reads float4), the next
+// slab prefetched into registers during the FMAs of the current one.
 #include "kernels.hpp"
 
 namespace dm {
@@ -42,14 +43,25 @@ __global__ __launch_bounds__(256) void lmhead_generic_kernel(const T* __restrict
 #pragma unroll
     for (int b = 0; b < 4; ++b) acc[a][b] = 0.f;
 
-  for (int k0 = 0; k0 < d; k0 += GK) {
+  // slab k0 travels global -> registers while the FMAs of slab k0 - GK run, then registers -> LDS
+  float a_reg[4], w_reg[4];
+  auto fetch = [&](int k0) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int k = k0 + lk + e;
-      As[lk + e][lr] = (k < d_pad) ? to_f32(A[arow * d_pad + k]) : 0.f;
-      Ws[lk + e][lr] = (wrow < V && k < d) ? to_f32(W[(int64_t)wrow * d + k]) : 0.f;
+      a_reg[e] = (k < d_pad) ? to_f32(A[arow * d_pad + k]) : 0.f;
+      w_reg[e] = (wrow < V && k < d) ? to_f32(W[(int64_t)wrow * d + k]) : 0.f;
+    }
+  };
+  fetch(0);
+  for (int k0 = 0; k0 < d; k0 += GK) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      As[lk + e][lr] = a_reg[e];
+      Ws[lk + e][lr] = w_reg[e];
     }
     __syncthreads();
+    if (k0 + GK < d) fetch(k0 + GK);
 #pragma unroll
     for (int k = 0; k < GK; ++k) {
       const float4 a4 = *reinterpret_cast<const float4*>(&As[k][ty * 4]);

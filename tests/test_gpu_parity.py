@@ -323,3 +323,38 @@ def test_size_limits(d, V, B, T, K):
             assert st == dmb.DM_EINVAL and msg
     finally:
         r.close()
+
+
+# ------------------------------------------------------------------ HIP graph capture
+def test_verify_can_be_captured_in_a_hip_graph(runner):
+    """The step only launches kernels on the caller's stream (no allocation, no synchronisation,
+    no memset), so a caller may capture it and replay it.  Every replay is checked against the
+    eager result, with eager work and synchronisations between the replays."""
+    wl, W, h, seeds, draft = _problem("graph", 256, 3000, "bf16", 2, 6, 8, 0.1, seed=321, bonus=True)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    eager = runner.verify(wl, hd, Wd, draft, seeds)
+    prm, keep = runner.params(wl, seeds)
+    draft_dev = torch.from_numpy(draft).cuda()
+    out = dict(accept_len=torch.zeros(wl.B, dtype=torch.int32, device="cuda"),
+               hit=torch.zeros((wl.B, wl.T), dtype=torch.uint8, device="cuda"),
+               path_ids=torch.zeros((wl.B, wl.T, wl.K), dtype=torch.int32, device="cuda"),
+               vote_ids=torch.zeros((wl.B, wl.T), dtype=torch.int32, device="cuda"))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up on the capture stream
+        dmb.dropmatch_verify(runner.ctx, prm, hd, Wd, draft_dev, stream=side, **out)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        dmb.dropmatch_verify(runner.ctx, prm, hd, Wd, draft_dev, stream=torch.cuda.current_stream(), **out)
+    for rep in range(4):
+        for v in out.values():
+            v.fill_(-1 if v.dtype != torch.uint8 else 7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, v in out.items():
+            assert np.array_equal(v.cpu().numpy(), eager[k]), f"replay {rep}: {k}"
+        again = runner.verify(wl, hd, Wd, draft, seeds)      # eager work between replays
+        assert np.array_equal(again["path_ids"], eager["path_ids"])
+    del graph
