@@ -33,6 +33,7 @@ def parse_args():
                          "alg1 (Algorithm 1 = Eq. 6 else Eq. 7); js/alg1 go through dropmatch_verify_js")
     ap.add_argument("--paths", type=int, default=0, help="override K, the dropout paths per row (rows sweep)")
     ap.add_argument("--batch", type=int, default=0, help="override B, the number of sequences (rows sweep)")
+    ap.add_argument("--p-drop", type=float, default=-1.0, help="override the dropout probability p (bigvocab sweep)")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of a HIP graph that holds one captured step instead of eager calls")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (for profiler runs)")
@@ -101,6 +102,8 @@ def main():
         wl = wl.with_(K=args.paths)
     if args.batch:
         wl = wl.with_(B=args.batch)
+    if args.p_drop >= 0.0:
+        wl = wl.with_(p=args.p_drop)
     bf16 = wl.dtype == "bf16"
     tdt = torch.bfloat16 if bf16 else torch.float32
 

@@ -164,7 +164,7 @@ dm_status dropmatch_verify(dm_ctx* ctx, const dm_params* prm,
  *
  * dropmatch_verify_js: same contract and outputs as dropmatch_verify, plus
  *   draft_probs  DEVICE float [B,T,V]: phat of the token that row t verifies (probabilities, >= 0,
- *                summing to 1; exact zeros are allowed; not read at rows with draft id < 0)
+ *                summing to 1; exact zeros are allowed; ignored at rows with draft id < 0)
  *   js_draft     DEVICE float [B,T] or NULL: JS(phat_t || pbar_t); -1 at rows with draft id < 0
  *   js_heads     DEVICE float [B,T,K] or NULL: JS(p_t^(i) || pbar_t)
  * Arithmetic: logits from the same contraction kernels (storage type products, fp32 accumulation,

@@ -14,7 +14,9 @@
 //                       nearly equal logarithms:
 //                         a = ln((1 + e^delta) / 2) = ln(m / p_i),   m = (p_i + pbar) / 2
 //                         p_i ln(p_i/m)/2 + pbar ln(pbar/m)/2 = (pbar * delta - (p_i + pbar) * a) / 2
-//                       (for p_i -> 0 it tends to pbar ln2 / 2, for pbar -> 0 to p_i ln2 / 2).
+//                       (for p_i -> 0 it tends to pbar ln2 / 2, for pbar -> 0 to p_i ln2 / 2).  The
+//                       shorter a = ln(p_i + pbar) - ln 2 - ln p_i was measured too: 3 % faster, ten
+//                       times the error (3e-7), so it is not used.
 // Every reduction (lanes, wavefronts, chunks) runs in a fixed order: results are reproducible.
 #include "kernels.hpp"
 
@@ -71,10 +73,19 @@ struct RowMap {
   static constexpr int ITERS = kJsChunk / ROWS_PER_ITER;
 };
 
+// Sum over the G consecutive lanes of a group (G = 1, 2, 4, 8, 16), result in every lane of the group,
+// with data-parallel-primitive moves inside a row of 16 lanes (no LDS traffic): exchange with lane ^ 1,
+// lane ^ 2, then the mirrored lane of the 8 (whose quad already holds its quad's sum), then of the 16.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
+}
 template <int G>
 __device__ __forceinline__ float group_sum(float x) {
-#pragma unroll
-  for (int off = 1; off < G; off <<= 1) x += __shfl_xor(x, off, 64);
+  if (G >= 2) x += dpp_move<0xB1>(x);    // quad_perm [1,0,3,2]
+  if (G >= 4) x += dpp_move<0x4E>(x);    // quad_perm [2,3,0,1]
+  if (G >= 8) x += dpp_move<0x141>(x);   // row_half_mirror
+  if (G >= 16) x += dpp_move<0x140>(x);  // row_mirror
   return x;
 }
 
@@ -86,7 +97,8 @@ __device__ __forceinline__ float column_sum(float x) {
   return x;
 }
 
-template <int G>
+// FULL: K == 4 G, every lane's four paths exist (no per-path predicates).
+template <int G, bool FULL>
 __global__ __launch_bounds__(JT) void js_stats_kernel(const float* __restrict__ lt,
                                                       const unsigned long long* __restrict__ keys,
                                                       float* __restrict__ part_a, JsGeom g, float scale) {
@@ -101,45 +113,52 @@ __global__ __launch_bounds__(JT) void js_stats_kernel(const float* __restrict__ 
   const bool active = i0 < g.K4;
 
   float mx[4], S[4];
+  bool use[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    mx[j] = (i0 + j < K) ? scale * key_logit(keys[(int64_t)pos * K + i0 + j]) : 0.f;
+    use[j] = FULL || i0 + j < K;
+    mx[j] = use[j] ? scale * key_logit(keys[(int64_t)pos * K + i0 + j]) : 0.f;
     S[j] = 0.f;
   }
-  float cmax = -INFINITY, csum = 0.f;  // centroid: running (max, sum of exp relative to it), lane 0 of a group
-  const float* base = lt + (int64_t)pos * g.V * g.K4 + i0;
+  // centroid: running (max, sum of exp relative to it); kept by every lane of a group, lane 0's is used.
+  // "Nothing yet" is a large negative finite number so that differences never become inf - inf.
+  constexpr float kNone = -3.0e38f;
+  float cmax = kNone, csum = 0.f;
+  const float* base = lt + (int64_t)pos * g.V * g.K4 + (active ? i0 : 0);
   const int v_first = c * kJsChunk + wave * RM::ROWS_PER_WAVE + rl;
+  const float inv_k = 1.0f / (float)K;
+  const bool exact_inv = (K & (K - 1)) == 0;  // then x * (1/K) is the correctly rounded x / K
 #pragma unroll 4
   for (int it = 0; it < RM::ITERS; ++it) {
     const int v = v_first + it * RM::ROWS_PER_ITER;
-    const bool in = v < g.V;
+    const bool in = v < g.V;                       // only the last chunk has rows past the end:
+    const int vc = in ? v : g.V - 1;               // they re-read the last row with weight 0
+    const float4 q = *reinterpret_cast<const float4*>(base + (int64_t)vc * g.K4);
+    const float x[4] = {q.x, q.y, q.z, q.w};
+    const float wgt = (in && active) ? 1.f : 0.f;
     float xs = 0.f;
-    if (in && active) {
-      const float4 q = *reinterpret_cast<const float4*>(base + (int64_t)v * g.K4);
-      const float x[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (i0 + j < K) {
-          xs += x[j];
-          S[j] += fast_exp(x[j] - mx[j]);
-        }
+    for (int j = 0; j < 4; ++j) {
+      const float xj = (use[j] && active) ? x[j] : 0.f;
+      xs += xj;
+      S[j] += (use[j] ? wgt : 0.f) * fast_exp(xj - mx[j]);
     }
     xs = group_sum<G>(xs);
-    if (in && grp == 0) {
-      const float xbar = xs / (float)K;
-      if (xbar > cmax) {
-        csum *= fast_exp(cmax - xbar);   // cmax = -inf the first time: exp(-inf) = 0
-        cmax = xbar;
-      }
-      csum += fast_exp(xbar - cmax);
-    }
+    const float xbar = in ? (exact_inv ? xs * inv_k : xs / (float)K) : kNone;
+    const float m_new = fmaxf(cmax, xbar);
+    csum = csum * fast_exp(cmax - m_new) + (in ? 1.f : 0.f) * fast_exp(xbar - m_new);
+    cmax = m_new;
+  }
+  if (grp != 0) {
+    cmax = kNone;
+    csum = 0.f;
   }
 
   // wavefront level
   float wmax = cmax;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) wmax = fmaxf(wmax, __shfl_xor(wmax, off, 64));
-  csum = (cmax == -INFINITY) ? 0.f : csum * fast_exp(cmax - wmax);
+  csum = csum * fast_exp(cmax - wmax);
   csum = wave_sum(csum);
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -163,14 +182,13 @@ __global__ __launch_bounds__(JT) void js_stats_kernel(const float* __restrict__ 
     for (int w = 1; w < JT / 64; ++w) m = fmaxf(m, red[w][KP]);
     float s = 0.f;
 #pragma unroll
-    for (int w = 0; w < JT / 64; ++w)
-      if (red[w][KP] != -INFINITY) s += red[w][KP + 1] * fast_exp(red[w][KP] - m);
+    for (int w = 0; w < JT / 64; ++w) s += red[w][KP + 1] * fast_exp(red[w][KP] - m);
     out[(int64_t)g.K4 * g.NC] = m;
     out[(int64_t)(g.K4 + 1) * g.NC] = s;
   }
 }
 
-template <int G>
+template <int G, bool FULL>
 __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ lt,
                                                       const unsigned long long* __restrict__ keys,
                                                       const float* __restrict__ part_a,
@@ -211,48 +229,45 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
   }
   __syncthreads();
   float Z[4], J[4];
+  bool use[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    Z[j] = (i0 + j < K) ? Zs[i0 + j] : 0.f;
+    use[j] = FULL || i0 + j < K;
+    Z[j] = use[j] ? Zs[i0 + j] : 0.f;
     J[j] = 0.f;
   }
   const float Zbar = Zs[KP];
-  const bool has_draft = draft_ids[pos] >= 0;
+  const bool draft_on = draft_ids[pos] >= 0 && grp == 0;
   float Jd = 0.f;
-  const float* base = lt + (int64_t)pos * g.V * g.K4 + i0;
+  const float* base = lt + (int64_t)pos * g.V * g.K4 + (active ? i0 : 0);
   const float* dp = draft_probs + (int64_t)pos * g.V;
   const int v_first = c * kJsChunk + wave * RM::ROWS_PER_WAVE + rl;
+  const float inv_k = 1.0f / (float)K;
+  const bool exact_inv = (K & (K - 1)) == 0;
 #pragma unroll 4
   for (int it = 0; it < RM::ITERS; ++it) {
     const int v = v_first + it * RM::ROWS_PER_ITER;
-    const bool in = v < g.V;
-    float x[4] = {0.f, 0.f, 0.f, 0.f};
+    const bool in = v < g.V;                       // rows past the end re-read the last row with weight 0
+    const int vc = in ? v : g.V - 1;
+    const float4 qv = *reinterpret_cast<const float4*>(base + (int64_t)vc * g.K4);
+    const float ph = dp[vc];
+    const float x[4] = {qv.x, qv.y, qv.z, qv.w};
+    const float wgt = (in && active) ? 1.f : 0.f;
     float xs = 0.f;
-    if (in && active) {
-      const float4 q = *reinterpret_cast<const float4*>(base + (int64_t)v * g.K4);
-      x[0] = q.x;
-      x[1] = q.y;
-      x[2] = q.z;
-      x[3] = q.w;
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (i0 + j < K) xs += x[j];
-    }
+    for (int j = 0; j < 4; ++j) xs += (use[j] && active) ? x[j] : 0.f;
     xs = group_sum<G>(xs);
-    if (in) {
-      const float lq = xs / (float)K - Zbar;
-      const float q = fast_exp(lq);
+    const float lq = (exact_inv ? xs * inv_k : xs / (float)K) - Zbar;
+    const float q = fast_exp(lq);
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (i0 + j < K) {
-          const float lp = x[j] - Z[j];
-          J[j] += js_term(lp, fast_exp(lp), lq, q);
-        }
-      if (has_draft && grp == 0) {
-        const float ph = dp[v];
-        Jd += (ph > 1e-37f) ? js_term(fast_log(ph), ph, lq, q) : 0.5f * 0.693147180559945309f * q;
-      }
+    for (int j = 0; j < 4; ++j) {
+      const float lp = ((use[j] && active) ? x[j] : 0.f) - Z[j];
+      J[j] += (use[j] ? wgt : 0.f) * js_term(lp, fast_exp(lp), lq, q);
     }
+    // draft: ln phat needs phat > 0; at phat = 0 the integrand is pbar ln2 / 2
+    const bool pos_ph = ph > 1e-37f;
+    const float td = js_term(fast_log(pos_ph ? ph : 1.f), pos_ph ? ph : 0.f, lq, q);
+    Jd += (in && draft_on) ? (pos_ph ? td : 0.5f * 0.693147180559945309f * q) : 0.f;
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -278,14 +293,23 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
 
 }  // namespace
 
-#define DM_JS_DISPATCH(KERNEL, ...)                                                        \
-  do {                                                                                     \
-    const dim3 grid((unsigned)g.P, (unsigned)g.NC), block(JT);                              \
-    if (g.K4 <= 4) KERNEL<1><<<grid, block, 0, stream>>>(__VA_ARGS__);                      \
-    else if (g.K4 <= 8) KERNEL<2><<<grid, block, 0, stream>>>(__VA_ARGS__);                 \
-    else if (g.K4 <= 16) KERNEL<4><<<grid, block, 0, stream>>>(__VA_ARGS__);                \
-    else if (g.K4 <= 32) KERNEL<8><<<grid, block, 0, stream>>>(__VA_ARGS__);                \
-    else KERNEL<16><<<grid, block, 0, stream>>>(__VA_ARGS__);                               \
+#define DM_JS_DISPATCH(KERNEL, ...)                                                          \
+  do {                                                                                       \
+    const dim3 grid((unsigned)g.P, (unsigned)g.NC), block(JT);                                \
+    const int G = g.K4 <= 4 ? 1 : g.K4 <= 8 ? 2 : g.K4 <= 16 ? 4 : g.K4 <= 32 ? 8 : 16;       \
+    const bool full = g.K == 4 * G;                                                           \
+    switch (G * 2 + (full ? 1 : 0)) {                                                         \
+      case 2: KERNEL<1, false><<<grid, block, 0, stream>>>(__VA_ARGS__); break;               \
+      case 3: KERNEL<1, true><<<grid, block, 0, stream>>>(__VA_ARGS__); break;                \
+      case 4: KERNEL<2, false><<<grid, block, 0, stream>>>(__VA_ARGS__); break;               \
+      case 5: KERNEL<2, true><<<grid, block, 0, stream>>>(__VA_ARGS__); break;                \
+      case 8: KERNEL<4, false><<<grid, block, 0, stream>>>(__VA_ARGS__); break;               \
+      case 9: KERNEL<4, true><<<grid, block, 0, stream>>>(__VA_ARGS__); break;                \
+      case 16: KERNEL<8, false><<<grid, block, 0, stream>>>(__VA_ARGS__); break;              \
+      case 17: KERNEL<8, true><<<grid, block, 0, stream>>>(__VA_ARGS__); break;               \
+      case 32: KERNEL<16, false><<<grid, block, 0, stream>>>(__VA_ARGS__); break;             \
+      default: KERNEL<16, true><<<grid, block, 0, stream>>>(__VA_ARGS__); break;              \
+    }                                                                                         \
   } while (0)
 
 hipError_t launch_js_stats(const float* lt, const unsigned long long* keys, float* part_a, const JsGeom& g,
