@@ -36,6 +36,10 @@ listed with its reason in the design notes of the repository):
     tokens (the paper's agreement table lists majority sizes 1..5 for K = 5),
     ties between modes -> smallest token id;
   * draft id < 0 means "no draft token at this row" and never matches;
+  * `clean_last_path` (the paper does not say which token is emitted after a rejection
+    or as the bonus token): path K-1 of every row is the plain LM head, h_t itself
+    with no mask and no scale; its token is reported in path_ids[..., K-1] and the
+    rules (Eq. (4), (6), (7), Alg. 1) use paths 0..K-2 only;
   * Jensen-Shannon divergence (the paper names it without a formula): the standard
     JS(P||Q) = KL(P||M)/2 + KL(Q||M)/2 with M = (P+Q)/2, natural logarithm,
     0 log 0 = 0; the two sides of Eq. (6) are compared after rounding each to
@@ -170,6 +174,17 @@ def path_token(logits: np.ndarray):
     return y, float(top2[1] - top2[0])
 
 
+def row_states(h_t, seed, step, tt, K, d, p, clean_last_path=False):
+    """The K inputs of the LM head for one row, [K, d]: Eq. (1)-(2) for every path, except that
+    with `clean_last_path` the last one is h_t itself (no mask, no scale)."""
+    rows = [masked_state(h_t, keep_mask(seed, step, tt, i, d, p), p) for i in range(K)]
+    if clean_last_path:
+        if K < 2:
+            raise ValueError("clean_last_path needs K >= 2")
+        rows[K - 1] = np.asarray(h_t, dtype=np.float64).copy()
+    return np.stack(rows, axis=0)
+
+
 # --------------------------------------------------------------------------- #
 # Eq. (4), Eq. (7), prefix / tree acceptance
 # --------------------------------------------------------------------------- #
@@ -281,7 +296,8 @@ def algorithm1_hit(draft: int, p_hat: np.ndarray, L: np.ndarray, ids) -> bool:
 
 
 def verify_js(h, W, draft_ids, draft_probs, seeds, K: int, p, step: int = 0,
-              rule: int = RULE_JS_OR_MAJORITY, share_mask_across_pos: bool = False):
+              rule: int = RULE_JS_OR_MAJORITY, share_mask_across_pos: bool = False,
+              clean_last_path: bool = False):
     """One verification step with the distribution-level rule (chains only).
 
     draft_probs [B, T, V]: the draft model's distribution for the token row t verifies
@@ -289,7 +305,8 @@ def verify_js(h, W, draft_ids, draft_probs, seeds, K: int, p, step: int = 0,
     RULE_JS_OR_MAJORITY (Algorithm 1).
 
     Returns what verify() returns plus js_draft[B,T] (-1 at rows without a draft
-    token), js_heads[B,T,K], and js_margin[B,T] = max_i js_heads - js_draft (the
+    token), js_heads[B,T,K] (0 in the slot of a clean last path), and js_margin[B,T] =
+    max_i js_heads - js_draft (the
     distance of the Eq. (6) decision from a tie; +inf at rows without a draft token).
     """
     if rule not in (RULE_JS, RULE_JS_OR_MAJORITY):
@@ -303,6 +320,7 @@ def verify_js(h, W, draft_ids, draft_probs, seeds, K: int, p, step: int = 0,
     if W64.shape[1] != d or draft_ids.shape != (B, T) or draft_probs.shape != (B, T, V) or len(seeds) != B:
         raise ValueError("shape mismatch")
 
+    KU = K - 1 if clean_last_path else K      # paths the rules use
     path_ids = np.zeros((B, T, K), dtype=np.int32)
     gap = np.zeros((B, T, K), dtype=np.float64)
     js_draft = np.full((B, T), -1.0)
@@ -312,14 +330,13 @@ def verify_js(h, W, draft_ids, draft_probs, seeds, K: int, p, step: int = 0,
     for b in range(B):
         for t in range(T):
             tt = 0 if share_mask_across_pos else t
-            Hm = np.stack([masked_state(h[b, t], keep_mask(seeds[b], step, tt, i, d, p), p)
-                           for i in range(K)], axis=0)          # Eq. (1)-(2), [K, d]
+            Hm = row_states(h[b, t], seeds[b], step, tt, K, d, p, clean_last_path)   # Eq. (1)-(2), [K, d]
             L = (W64 @ Hm.T).T                                   # Eq. (3), [K, V]
             for i in range(K):
                 path_ids[b, t, i], gap[b, t, i] = path_token(L[i])
             g = int(draft_ids[b, t])
-            js_hit, jd, jh = js_rule(draft_probs[b, t], L)
-            js_heads[b, t] = jh
+            js_hit, jd, jh = js_rule(draft_probs[b, t], L[:KU])
+            js_heads[b, t, :KU] = jh
             if g < 0:
                 continue
             js_draft[b, t] = jd
@@ -327,10 +344,10 @@ def verify_js(h, W, draft_ids, draft_probs, seeds, K: int, p, step: int = 0,
             if rule == RULE_JS:
                 hit[b, t] = js_hit
             else:
-                hit[b, t] = js_hit or rule_hit(g, path_ids[b, t], RULE_MAJORITY)
+                hit[b, t] = js_hit or rule_hit(g, path_ids[b, t, :KU], RULE_MAJORITY)
 
     out = acceptance_from_hits(hit)
-    votes = acceptance_from_path_ids(path_ids, draft_ids, RULE_MAJORITY)
+    votes = acceptance_from_path_ids(path_ids[:, :, :KU], draft_ids, RULE_MAJORITY)
     out.update(vote_ids=votes["vote_ids"], vote_cnt=votes["vote_cnt"], path_ids=path_ids, gap=gap,
                js_draft=js_draft, js_heads=js_heads, js_margin=js_margin)
     return out
@@ -352,7 +369,8 @@ def acceptance_from_hits(hit):
 # The whole step
 # --------------------------------------------------------------------------- #
 def verify(h, W, draft_ids, seeds, K: int, p, step: int = 0, rule: int = RULE_ANY,
-           share_mask_across_pos: bool = False, parent=None, want_logits=None):
+           share_mask_across_pos: bool = False, parent=None, want_logits=None,
+           clean_last_path: bool = False):
     """One DropMatch verification step for B sequences.
 
     h          [B, T, d]  final hidden states (any float dtype; used as float64)
@@ -385,15 +403,15 @@ def verify(h, W, draft_ids, seeds, K: int, p, step: int = 0, rule: int = RULE_AN
         for t in range(T):
             tt = 0 if share_mask_across_pos else t
             # K masked states of this row, Eq. (1)-(2)
-            Hm = np.stack([masked_state(h[b, t], keep_mask(seeds[b], step, tt, i, d, p), p)
-                           for i in range(K)], axis=0)          # [K, d]
+            Hm = row_states(h[b, t], seeds[b], step, tt, K, d, p, clean_last_path)   # [K, d]
             L = W64 @ Hm.T                                       # Eq. (3), [V, K]
             for i in range(K):
                 path_ids[b, t, i], gap[b, t, i] = path_token(L[:, i])
                 if logits_out is not None:
                     logits_out[(b * T + t) * K + i] = L[v0:v1, i]
 
-    out = acceptance_from_path_ids(path_ids, draft_ids, rule, parent)
+    KU = K - 1 if clean_last_path else K      # paths the rules use
+    out = acceptance_from_path_ids(path_ids[:, :, :KU], draft_ids, rule, parent)
     out["path_ids"] = path_ids
     out["gap"] = gap
     if logits_out is not None:

@@ -268,3 +268,14 @@ def test_draft_probs_generator_shapes_and_topk():
     assert ((tk > 0).sum(-1) == 7).all() and np.allclose(tk.sum(-1), 1.0, atol=1e-5)
     out = orc.verify_js(h, W, draft, tk, seeds, wl.K, wl.p)          # zeros in the draft are fine
     assert np.isfinite(out["js_draft"]).all()
+
+
+def test_clean_last_path_under_the_js_rules():
+    wl, W, h, seeds, draft, probs = _small_problem(81, B=2, T=4, K=6)
+    for rule in (orc.RULE_JS, orc.RULE_JS_OR_MAJORITY):
+        a = orc.verify_js(h, W, draft, probs, seeds, wl.K, wl.p, rule=rule, clean_last_path=True)
+        b = orc.verify_js(h, W, draft, probs, seeds, wl.K - 1, wl.p, rule=rule)
+        assert np.array_equal(a["path_ids"][:, :, -1], orc.greedy_ids(h, W))
+        assert np.array_equal(a["js_heads"][:, :, :-1], b["js_heads"]) and np.all(a["js_heads"][:, :, -1] == 0)
+        for k in ("js_draft", "js_margin", "vote_ids", "vote_cnt", "hit", "accept_mask", "accept_len"):
+            assert np.array_equal(a[k], b[k]), k

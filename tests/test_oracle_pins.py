@@ -418,3 +418,28 @@ def test_tiny_config_end_to_end():
     keep = orc.keep_mask(int(seeds[0]), 0, 2, 3, wl.d, wl.p)
     np.testing.assert_allclose(out["logits"][2 * 8 + 3], orc.path_logits(W, h[0, 2], keep, wl.p)[10:20],
                                rtol=0, atol=1e-12)
+
+
+# ---- clean last path ------------------------------------------------------------ #
+def test_clean_last_path_is_the_plain_head_and_is_ignored_by_the_rules():
+    """With clean_last_path, path K-1 is the undropped LM head (its token is the greedy token,
+    its logits are W h exactly, with no 1/(1-p)), and every acceptance output equals the one of
+    a run with K-1 paths (the masks of paths 0..K-2 do not depend on K)."""
+    wl = wk.Workload("clean", d=48, V=60, dtype="f32", B=2, T=5, K=6, p=0.3, bonus=True, data_seed=71)
+    W, h, seeds = wk.make_weight(wl, sigma=0.3), wk.make_hidden(wl), wk.make_seeds(wl, base_seed=5)
+    greedy = orc.greedy_ids(h, W)
+    draft = wk.make_draft_ids(wl, greedy)
+    for rule in (orc.RULE_ANY, orc.RULE_MAJORITY):
+        a = orc.verify(h, W, draft, seeds, wl.K, wl.p, rule=rule, clean_last_path=True, want_logits=(0, wl.V))
+        b = orc.verify(h, W, draft, seeds, wl.K - 1, wl.p, rule=rule)
+        assert np.array_equal(a["path_ids"][:, :, -1], greedy)
+        assert np.array_equal(a["path_ids"][:, :, :-1], b["path_ids"])
+        for k in ("vote_ids", "vote_cnt", "hit", "accept_mask", "accept_len", "best_node"):
+            assert np.array_equal(a[k], b[k]), k
+        L = a["logits"].reshape(wl.B, wl.T, wl.K, wl.V)
+        want = np.einsum("vd,btd->btv", W.astype(np.float64), h.astype(np.float64))
+        assert np.allclose(L[:, :, -1], want, rtol=1e-13, atol=1e-13)
+        # the other paths keep their scale: mean over kept dims would otherwise shrink by (1-p)
+        assert not np.allclose(L[:, :, 0], want, atol=1e-3)
+    with pytest.raises(ValueError):
+        orc.verify(h, W, draft, seeds, 1, wl.p, clean_last_path=True)
