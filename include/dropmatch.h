@@ -65,6 +65,14 @@ typedef enum {
  * kernel applies (lets the two kernels be compared on the same inputs). */
 #define DM_FLAG_FORCE_GENERIC 2u
 
+/* Path K-1 of every row is computed without dropout (all dimensions kept, no 1/(1-p)): the plain
+ * LM head.  Its token, the greedy target token of the row, is returned in path_ids[b,t,K-1] (the
+ * token to emit after a rejection or as the bonus token; the paper leaves that choice open), and
+ * the rules (Eq. 4, 6, 7, Algorithm 1), vote_ids/vote_cnt and js_heads use paths 0..K-2 only
+ * (js_heads[b,t,K-1] = 0).  The masks of the other paths are those of a call without the flag.
+ * Needs K >= 2. */
+#define DM_FLAG_CLEAN_LAST_PATH 4u
+
 /* Limits of this build. */
 #define DM_MAX_K 1024            /* paths per row */
 #define DM_MAX_ROWS_PER_SEQ 4096 /* T */

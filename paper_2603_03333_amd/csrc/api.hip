@@ -82,7 +82,8 @@ const char* check_params(const dm_params* p, char* scratch, size_t n) {
   }
   if (p->rule >= DM_RULE_JS && p->parent != nullptr)
     return "the distribution-level rules are defined for chains only (parent must be NULL)";
-  if (p->flags & ~(DM_FLAG_SHARE_MASK_ACROSS_POS | DM_FLAG_FORCE_GENERIC)) return "unknown bits in flags";
+  if (p->flags & ~(DM_FLAG_SHARE_MASK_ACROSS_POS | DM_FLAG_FORCE_GENERIC | DM_FLAG_CLEAN_LAST_PATH)) return "unknown bits in flags";
+  if ((p->flags & DM_FLAG_CLEAN_LAST_PATH) && p->K < 2) return "DM_FLAG_CLEAN_LAST_PATH needs K >= 2";
   if (!p->seeds) return "seeds is NULL";
   return nullptr;
 }
@@ -112,6 +113,7 @@ dm_status make_geom(dm_ctx* ctx, const dm_params* p, bool mfma, dm::RowGeom* g) 
   g->thr = (uint32_t)std::floor((double)p->p * 4294967296.0);
   g->step = p->step;
   g->share_pos = (p->flags & DM_FLAG_SHARE_MASK_ACROSS_POS) ? 1 : 0;
+  g->clean_last = (p->flags & DM_FLAG_CLEAN_LAST_PATH) ? 1 : 0;
   return DM_OK;
 }
 
@@ -132,7 +134,9 @@ struct DeviceGuard {
 // `ev` (optional): 3 events recorded before the mask kernel, between the two kernels, after.
 dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g, bool mfma, const void* h,
                           const void* W, float* logits, int v0, int v1, hipStream_t s, hipEvent_t* ev = nullptr,
-                          const dm::LogitStore& store = dm::LogitStore{nullptr, 0, 0, 0}) {
+                          dm::LogitStore store = dm::LogitStore{nullptr, 0, 0, 0, 0}) {
+  store.K = p->K;  // the debug dump needs K and the clean-path flag even when nothing is stored
+  store.clean_last = g.clean_last;
   const bool bf16 = p->dtype == DM_BF16;
   if (ev) (void)hipEventRecord(ev[0], s);
   hipError_t e = dm::launch_mask_rows(h, ctx->a_ws, ctx->keys, p->seeds, g, bf16, mfma, s);
@@ -172,11 +176,12 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
   if (dm_status st = make_geom(ctx, prm, mfma, &g)) return st;
   const bool js = draft_probs != nullptr;
   dm::JsGeom jg{};
-  dm::LogitStore store{nullptr, 0, 0, 0};
+  dm::LogitStore store{nullptr, 0, 0, 0, 0};
   if (js) {
     jg.P = prm->B * prm->T;
     jg.K = prm->K;
     jg.K4 = (int)round_up(prm->K, 4);
+    jg.KU = g.clean_last ? prm->K - 1 : prm->K;
     jg.V = prm->V;
     jg.NC = (prm->V + dm::kJsChunk - 1) / dm::kJsChunk;
     jg.KS = jg.K4 + 4;
@@ -188,7 +193,7 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
     if ((size_t)jg.P * (size_t)jg.V * (size_t)jg.K4 > ctx->lt_floats ||
         (size_t)jg.P * (size_t)jg.NC * (size_t)jg.KS > ctx->part_floats)
       return fail(ctx, DM_EINVAL, "B*T = %d positions with K = %d exceed what dm_reserve_js reserved", jg.P, jg.K);
-    store = dm::LogitStore{ctx->lt, jg.K, jg.K4, jg.V};
+    store = dm::LogitStore{ctx->lt, jg.K, jg.K4, jg.V, g.clean_last};
   }
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return fail(ctx, DM_EHIP, "cannot select device %d", ctx->device);
@@ -211,7 +216,8 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
     (void)hipEventRecord(ev[4], s);
   }
   dm::VoteOut out{accept_len, best_node, accept_mask, hit, path_ids, vote_ids, vote_cnt, js_draft, js_heads};
-  e = dm::launch_vote_accept(ctx->keys, draft_ids, prm->parent, prm->B, prm->T, prm->K, prm->rule, out,
+  e = dm::launch_vote_accept(ctx->keys, draft_ids, prm->parent, prm->B, prm->T, prm->K,
+                             g.clean_last ? prm->K - 1 : prm->K, prm->rule, out,
                              js ? ctx->part_b : nullptr, js ? &jg : nullptr, s);
   if (e != hipSuccess) return fail_hip(ctx, "vote_accept launch", e);
   if (ev) {

@@ -97,7 +97,7 @@ __device__ __forceinline__ float column_sum(float x) {
   return x;
 }
 
-// FULL: K == 4 G, every lane's four paths exist (no per-path predicates).
+// FULL: the number of heads in use is 4 G, every lane's four paths exist (no per-path predicates).
 template <int G, bool FULL>
 __global__ __launch_bounds__(JT) void js_stats_kernel(const float* __restrict__ lt,
                                                       const unsigned long long* __restrict__ keys,
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(JT) void js_stats_kernel(const float* __restrict__ 
   __shared__ float red[JT / 64][KP + 2];
   const int pos = blockIdx.x, c = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int K = g.K;
+  const int K = g.K, KU = g.KU;  // rows per position in the store / heads in use
   const int grp = lane % G, rl = lane / G;
   const int i0 = 4 * grp;             // first path of this lane
   const bool active = i0 < g.K4;
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(JT) void js_stats_kernel(const float* __restrict__ 
   bool use[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    use[j] = FULL || i0 + j < K;
+    use[j] = FULL || i0 + j < KU;
     mx[j] = use[j] ? scale * key_logit(keys[(int64_t)pos * K + i0 + j]) : 0.f;
     S[j] = 0.f;
   }
@@ -126,8 +126,8 @@ __global__ __launch_bounds__(JT) void js_stats_kernel(const float* __restrict__ 
   float cmax = kNone, csum = 0.f;
   const float* base = lt + (int64_t)pos * g.V * g.K4 + (active ? i0 : 0);
   const int v_first = c * kJsChunk + wave * RM::ROWS_PER_WAVE + rl;
-  const float inv_k = 1.0f / (float)K;
-  const bool exact_inv = (K & (K - 1)) == 0;  // then x * (1/K) is the correctly rounded x / K
+  const float inv_k = 1.0f / (float)KU;
+  const bool exact_inv = (KU & (KU - 1)) == 0;  // then x * (1/K) is the correctly rounded x / K
 #pragma unroll 4
   for (int it = 0; it < RM::ITERS; ++it) {
     const int v = v_first + it * RM::ROWS_PER_ITER;
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(JT) void js_stats_kernel(const float* __restrict__ 
       S[j] += (use[j] ? wgt : 0.f) * fast_exp(xj - mx[j]);
     }
     xs = group_sum<G>(xs);
-    const float xbar = in ? (exact_inv ? xs * inv_k : xs / (float)K) : kNone;
+    const float xbar = in ? (exact_inv ? xs * inv_k : xs / (float)KU) : kNone;
     const float m_new = fmaxf(cmax, xbar);
     csum = csum * fast_exp(cmax - m_new) + (in ? 1.f : 0.f) * fast_exp(xbar - m_new);
     cmax = m_new;
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(JT) void js_stats_kernel(const float* __restrict__ 
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const float t = column_sum<G>(S[j]);
-    if (lane < G && i0 + j < K) red[wave][i0 + j] = t;
+    if (lane < G && i0 + j < KU) red[wave][i0 + j] = t;
   }
   if (lane == 0) {
     red[wave][KP] = wmax;
@@ -171,7 +171,7 @@ __global__ __launch_bounds__(JT) void js_stats_kernel(const float* __restrict__ 
   }
   __syncthreads();
   float* out = part_a + (int64_t)pos * g.KS * g.NC + c;  // record layout [pos][slot][chunk]
-  if (tid < K) {
+  if (tid < KU) {
     float t = red[0][tid];
 #pragma unroll
     for (int w = 1; w < JT / 64; ++w) t += red[w][tid];
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
   __shared__ float red[JT / 64][KP + 1];
   const int pos = blockIdx.x, c = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int K = g.K;
+  const int K = g.K, KU = g.KU;  // rows per position in the store / heads in use
   const int grp = lane % G, rl = lane / G;
   const int i0 = 4 * grp;
   const bool active = i0 < g.K4;
@@ -209,8 +209,8 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
   // normalisers from the partial sums of pass 1: one wavefront per slot, lanes over chunks, then a
   // butterfly (a fixed order, the same in every workgroup)
   const float* pa = part_a + (int64_t)pos * g.KS * g.NC;
-  for (int slot = wave; slot <= K; slot += JT / 64) {
-    if (slot < K) {
+  for (int slot = wave; slot <= KU; slot += JT / 64) {
+    if (slot < KU) {
       double s = 0.0;
       for (int cc = lane; cc < g.NC; cc += 64) s += (double)pa[(int64_t)slot * g.NC + cc];
       s = wave_sum(s);
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
   bool use[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    use[j] = FULL || i0 + j < K;
+    use[j] = FULL || i0 + j < KU;
     Z[j] = use[j] ? Zs[i0 + j] : 0.f;
     J[j] = 0.f;
   }
@@ -242,8 +242,8 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
   const float* base = lt + (int64_t)pos * g.V * g.K4 + (active ? i0 : 0);
   const float* dp = draft_probs + (int64_t)pos * g.V;
   const int v_first = c * kJsChunk + wave * RM::ROWS_PER_WAVE + rl;
-  const float inv_k = 1.0f / (float)K;
-  const bool exact_inv = (K & (K - 1)) == 0;
+  const float inv_k = 1.0f / (float)KU;
+  const bool exact_inv = (KU & (KU - 1)) == 0;
 #pragma unroll 4
   for (int it = 0; it < RM::ITERS; ++it) {
     const int v = v_first + it * RM::ROWS_PER_ITER;
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
 #pragma unroll
     for (int j = 0; j < 4; ++j) xs += (use[j] && active) ? x[j] : 0.f;
     xs = group_sum<G>(xs);
-    const float lq = (exact_inv ? xs * inv_k : xs / (float)K) - Zbar;
+    const float lq = (exact_inv ? xs * inv_k : xs / (float)KU) - Zbar;
     const float q = fast_exp(lq);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -272,13 +272,13 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const float t = column_sum<G>(J[j]);
-    if (lane < G && i0 + j < K) red[wave][i0 + j] = t;
+    if (lane < G && i0 + j < KU) red[wave][i0 + j] = t;
   }
   Jd = wave_sum(Jd);
   if (lane == 0) red[wave][KP] = Jd;
   __syncthreads();
   float* out = part_b + (int64_t)pos * g.KS * g.NC + c;
-  if (tid < K) {
+  if (tid < KU) {
     float t = red[0][tid];
 #pragma unroll
     for (int w = 1; w < JT / 64; ++w) t += red[w][tid];
@@ -297,7 +297,7 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
   do {                                                                                       \
     const dim3 grid((unsigned)g.P, (unsigned)g.NC), block(JT);                                \
     const int G = g.K4 <= 4 ? 1 : g.K4 <= 8 ? 2 : g.K4 <= 16 ? 4 : g.K4 <= 32 ? 8 : 16;       \
-    const bool full = g.K == 4 * G;                                                           \
+    const bool full = g.KU == 4 * G;                                                           \
     switch (G * 2 + (full ? 1 : 0)) {                                                         \
       case 2: KERNEL<1, false><<<grid, block, 0, stream>>>(__VA_ARGS__); break;               \
       case 3: KERNEL<1, true><<<grid, block, 0, stream>>>(__VA_ARGS__); break;                \
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
 
 hipError_t launch_js_stats(const float* lt, const unsigned long long* keys, float* part_a, const JsGeom& g,
                            float scale, hipStream_t stream) {
-  if (g.K < 1 || g.K > kJsMaxK || g.P < 1 || g.NC < 1 || g.NC > 65535) return hipErrorInvalidValue;
+  if (g.K < 1 || g.K > kJsMaxK || g.KU < 1 || g.KU > g.K || g.P < 1 || g.NC < 1 || g.NC > 65535) return hipErrorInvalidValue;
   DM_JS_DISPATCH(js_stats_kernel, lt, keys, part_a, g, scale);
   return hipGetLastError();
 }
@@ -322,7 +322,7 @@ hipError_t launch_js_stats(const float* lt, const unsigned long long* keys, floa
 hipError_t launch_js_terms(const float* lt, const unsigned long long* keys, const float* part_a,
                            const float* draft_probs, const int32_t* draft_ids, float* part_b, const JsGeom& g,
                            float scale, hipStream_t stream) {
-  if (g.K < 1 || g.K > kJsMaxK || g.P < 1 || g.NC < 1 || g.NC > 65535) return hipErrorInvalidValue;
+  if (g.K < 1 || g.K > kJsMaxK || g.KU < 1 || g.KU > g.K || g.P < 1 || g.NC < 1 || g.NC > 65535) return hipErrorInvalidValue;
   DM_JS_DISPATCH(js_terms_kernel, lt, keys, part_a, draft_probs, draft_ids, part_b, g, scale);
   return hipGetLastError();
 }

@@ -20,6 +20,7 @@ struct RowGeom {
   uint32_t thr;    // drop threshold floor(p * 2^32)
   uint32_t step;
   int share_pos;   // row word of the counter forced to 0
+  int clean_last;  // path K-1 of every row keeps every dimension (the plain LM head)
 };
 
 // Eq. (1)+(2) without the scale: masked rows a = keep ? h : 0 into the workspace, and the
@@ -38,6 +39,7 @@ hipError_t launch_mask_bits(uint32_t* bits, const uint64_t* seeds_host, const Ro
 struct LogitStore {
   float* lt;
   int K, K4, V;
+  int clean_last;  // debug dump only: rows of path K-1 are reported without the factor 1/(1-p)
 };
 
 // Eq. (3) + per-row argmax, generic fp32-FMA tiles.  a_ws plain layout.  If logits != null the
@@ -65,7 +67,8 @@ constexpr int kJsChunk = 1024;  // vocabulary rows per workgroup
 constexpr int kJsMaxK = 64;     // paths per row the distribution-level rule takes
 struct JsGeom {
   int P;    // positions B*T
-  int K, K4;
+  int K, K4;  // rows per position in the logit store (K4 = K rounded up to a multiple of 4)
+  int KU;     // heads the rule uses: K, or K - 1 when the last path is the clean one
   int V;
   int NC;   // ceil(V / kJsChunk)
   int KS;   // slots per position in part_a / part_b (layout [pos][slot][chunk]): K4 + 4
@@ -92,8 +95,9 @@ struct VoteOut {
   float* js_heads;  // [B,T,K]
 };
 // part_b / jg: partial JS sums of launch_js_terms (rules 2 and 3), else nullptr.
+// Kv: paths the rules and the vote use (K, or K - 1 with a clean last path).
 hipError_t launch_vote_accept(const unsigned long long* keys, const int32_t* draft_ids, const int32_t* parent,
-                              int B, int T, int K, int rule, const VoteOut& out, const float* part_b,
+                              int B, int T, int K, int Kv, int rule, const VoteOut& out, const float* part_b,
                               const JsGeom* jg, hipStream_t stream);
 hipError_t prepare_vote_accept();
 

@@ -82,10 +82,11 @@ __global__ __launch_bounds__(256) void lmhead_generic_kernel(const T* __restrict
     for (int x = 0; x < 4; ++x) {
       const int64_t m = m0 + ty * 4 + x;
       if (m >= M) continue;
+      const float sc = (store.clean_last && m % store.K == store.K - 1) ? 1.0f : scale;  // clean path: no 1/(1-p)
 #pragma unroll
       for (int y = 0; y < 4; ++y) {
         const int v = v0 + tx * 4 + y;
-        if (v >= dv0 && v < dv1 && v < V) logits[m * nv + (v - dv0)] = scale * acc[x][y];
+        if (v >= dv0 && v < dv1 && v < V) logits[m * nv + (v - dv0)] = sc * acc[x][y];
       }
     }
     return;

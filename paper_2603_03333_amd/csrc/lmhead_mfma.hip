@@ -253,12 +253,13 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const int64_t m = (int64_t)(mblk * MT + mt) * 32 + i32;
+        const float sc = (store.clean_last && m % store.K == store.K - 1) ? 1.0f : scale;  // clean path: no 1/(1-p)
 #pragma unroll
         for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int v = v0 + 64 * wave + 32 * vt + 8 * (r >> 2) + 4 * hb + (r & 3);
-            if (m < M && v >= dv0 && v < dv1 && v < row_end) logits[m * nv + (v - dv0)] = scale * acc[mt][vt][r];
+            if (m < M && v >= dv0 && v < dv1 && v < row_end) logits[m * nv + (v - dv0)] = sc * acc[mt][vt][r];
             acc[mt][vt][r] = 0.f;
           }
       }

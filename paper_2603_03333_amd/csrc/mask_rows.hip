@@ -45,8 +45,10 @@ __global__ __launch_bounds__(256) void mask_rows_kernel(const T* __restrict__ h,
     const int t = rem / g.K;
     const int i = rem - t * g.K;
     const uint64_t seed = seeds.s[b - b0];
-    const uint32_t bits = keep_bits8(o, g.share_pos ? 0u : (uint32_t)t, (uint32_t)i, g.step,
-                                     (uint32_t)seed, (uint32_t)(seed >> 32), g.thr);
+    const uint32_t bits = (g.clean_last && i == g.K - 1)
+                              ? 0xFFu
+                              : keep_bits8(o, g.share_pos ? 0u : (uint32_t)t, (uint32_t)i, g.step,
+                                           (uint32_t)seed, (uint32_t)(seed >> 32), g.thr);
     const T* src = h + ((int64_t)b * g.T + t) * g.d + 8 * (int64_t)o;
     if ((g.d & 7) == 0) {
       const Vec8<T> in = *reinterpret_cast<const Vec8<T>*>(src);
@@ -86,11 +88,15 @@ __global__ __launch_bounds__(256) void mask_bits_kernel(uint32_t* __restrict__ b
   const int i = rem - t * g.K;
   const uint64_t seed = seeds.s[b - b0];
   uint32_t word = 0;
+  if (g.clean_last && i == g.K - 1) {
+    word = 0xFFFFFFFFu;
+  } else {
 #pragma unroll
-  for (uint32_t q = 0; q < 4; ++q)
-    word |= keep_bits8(4u * w + q, g.share_pos ? 0u : (uint32_t)t, (uint32_t)i, g.step, (uint32_t)seed,
-                       (uint32_t)(seed >> 32), g.thr)
-            << (8u * q);
+    for (uint32_t q = 0; q < 4; ++q)
+      word |= keep_bits8(4u * w + q, g.share_pos ? 0u : (uint32_t)t, (uint32_t)i, g.step, (uint32_t)seed,
+                         (uint32_t)(seed >> 32), g.thr)
+              << (8u * q);
+  }
   const int valid = g.d - 32 * (int)w;  // dimensions of this word that exist
   if (valid < 32) word &= (1u << valid) - 1u;
   bits[r * nwords + w] = word;

@@ -20,7 +20,7 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long x)
 __global__ __launch_bounds__(256) void vote_accept_kernel(const unsigned long long* __restrict__ keys,
                                                           const int32_t* __restrict__ draft_ids,
                                                           const int32_t* __restrict__ parent, int T, int K,
-                                                          int rule, VoteOut out,
+                                                          int Kv, int rule, VoteOut out,
                                                           const float* __restrict__ part_b, JsGeom jg) {
   extern __shared__ int32_t sm[];
   int32_t* ids = sm;            // [T*K] path tokens of this sequence
@@ -49,6 +49,11 @@ __global__ __launch_bounds__(256) void vote_accept_kernel(const unsigned long lo
     const int K1 = K + 1;
     for (int x = tid; x < T * K1; x += 256) {
       const int t = x / K1, i = x - t * K1;
+      if (i >= Kv && i < K) {  // slot of the clean path: not a head of the cluster
+        jsv[x] = 0.f;
+        if (out.js_heads) out.js_heads[((int64_t)b * T + t) * K + i] = 0.f;
+        continue;
+      }
       const float* src = part_b + (((int64_t)b * T + t) * jg.KS + (i < K ? i : jg.K4)) * jg.NC;
       double s = 0.0;
       int c = 0;
@@ -74,12 +79,12 @@ __global__ __launch_bounds__(256) void vote_accept_kernel(const unsigned long lo
   for (int t = wave; t < T; t += 4) {
     const int32_t* row = ids + t * K;
     unsigned long long best = 0;
-    for (int i0 = 0; i0 < K; i0 += 64) {
+    for (int i0 = 0; i0 < Kv; i0 += 64) {
       const int i = i0 + lane;
-      if (i < K) {
+      if (i < Kv) {
         const int32_t mine = row[i];
         uint32_t cnt = 0;
-        for (int j = 0; j < K; ++j) cnt += (row[j] == mine) ? 1u : 0u;
+        for (int j = 0; j < Kv; ++j) cnt += (row[j] == mine) ? 1u : 0u;
         const unsigned long long k = ((unsigned long long)cnt << 32) | (0x7FFFFFFFu - (uint32_t)mine);
         best = k > best ? k : best;
       }
@@ -115,7 +120,7 @@ __global__ __launch_bounds__(256) void vote_accept_kernel(const unsigned long lo
         // Eq. (6): JS(phat || pbar) <= max_i JS(p^(i) || pbar), both sides as float; rule 3 = Alg. 1
         const float* row = jsv + t * (K + 1);
         float js_max = -INFINITY;
-        for (int i = lane; i < K; i += 64) js_max = fmaxf(js_max, row[i]);
+        for (int i = lane; i < Kv; i += 64) js_max = fmaxf(js_max, row[i]);
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) js_max = fmaxf(js_max, __shfl_xor(js_max, off, 64));
         const float jd = row[K];
@@ -127,7 +132,7 @@ __global__ __launch_bounds__(256) void vote_accept_kernel(const unsigned long lo
         h = (vid[src] == g) ? 1 : 0;
       } else {
         int any = 0;
-        for (int i = lane; i < K; i += 64) any |= (ids[src * K + i] == g) ? 1 : 0;
+        for (int i = lane; i < Kv; i += 64) any |= (ids[src * K + i] == g) ? 1 : 0;
         h = __any(any) ? 1 : 0;
       }
     }
@@ -182,14 +187,15 @@ hipError_t prepare_vote_accept() {
 }
 
 hipError_t launch_vote_accept(const unsigned long long* keys, const int32_t* draft_ids, const int32_t* parent,
-                              int B, int T, int K, int rule, const VoteOut& out, const float* part_b,
+                              int B, int T, int K, int Kv, int rule, const VoteOut& out, const float* part_b,
                               const JsGeom* jg, hipStream_t stream) {
+  if (Kv < 1 || Kv > K) return hipErrorInvalidValue;
   if (rule >= 2 && (part_b == nullptr || jg == nullptr || parent != nullptr || K > kJsMaxK ||
                     vote_lds_bytes(T, K, rule) > vote_lds_bytes(4096, 4, 0)))
     return hipErrorInvalidValue;
   const JsGeom geom = jg ? *jg : JsGeom{};
   vote_accept_kernel<<<dim3((unsigned)B), dim3(256), vote_lds_bytes(T, K, rule), stream>>>(keys, draft_ids, parent, T, K,
-                                                                                      rule, out, part_b, geom);
+                                                                                      Kv, rule, out, part_b, geom);
   return hipGetLastError();
 }
 

@@ -166,3 +166,28 @@ def test_js_size_limits():
             assert st == dmb.DM_EINVAL and msg
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("K", [5, 16, 17])
+def test_js_with_clean_last_path(runner, K):
+    """K-1 dropout heads form the cluster, path K-1 is the plain head (K = 17: 16 heads, the fully
+    populated lane layout of the JS kernels, next to a clean 17th row)."""
+    wl, W, h, seeds, draft, probs = _problem(256, 3000, "bf16", 2, 4, K, 0.2, seed=470 + K)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    flag = dmb.DM_FLAG_CLEAN_LAST_PATH
+    ref = orc.verify_js(h, W, draft, probs, seeds, K, wl.p, rule=orc.RULE_JS_OR_MAJORITY, clean_last_path=True)
+    res = runner.verify_js(wl, hd, Wd, draft, probs, seeds, rule=dmb.DM_RULE_JS_OR_MAJORITY, flags=flag)
+    nflip, _ = compare_path_ids(res["path_ids"], ref["path_ids"], ref["gap"])
+    assert np.array_equal(res["path_ids"][:, :, -1], orc.greedy_ids(h, W))
+    assert np.all(res["js_heads"][:, :, -1] == 0)
+    n_tie, gpu_js = compare_js(res, ref, draft, False, nflip, f"js clean K={K}")
+    fewer = runner.verify_js(wl.with_(K=K - 1), hd, Wd, draft, probs, seeds, rule=dmb.DM_RULE_JS_OR_MAJORITY, K=K - 1)
+    # the (K-1)-path run groups lanes differently, so its sums round differently: equal within the JS bar
+    from gpu_harness import JS_ATOL, JS_RTOL
+    assert np.allclose(res["js_heads"][:, :, :-1], fewer["js_heads"], atol=JS_ATOL, rtol=JS_RTOL)
+    assert np.allclose(res["js_draft"], fewer["js_draft"], atol=JS_ATOL, rtol=JS_RTOL)
+    for k in ("vote_ids", "vote_cnt") + (("hit", "accept_len") if n_tie == 0 else ()):
+        assert np.array_equal(res[k], fewer[k]), k
+    if n_tie == 0 and nflip == 0:
+        for k in ("hit", "accept_mask", "accept_len", "vote_ids", "vote_cnt"):
+            assert np.array_equal(res[k], ref[k]), k

@@ -358,3 +358,36 @@ def test_verify_can_be_captured_in_a_hip_graph(runner):
         again = runner.verify(wl, hd, Wd, draft, seeds)      # eager work between replays
         assert np.array_equal(again["path_ids"], eager["path_ids"])
     del graph
+
+
+# ------------------------------------------------------------------ clean last path
+@pytest.mark.parametrize("d,V,B,T,K,dtype", [
+    (256, 3000, 2, 6, 16, "bf16"),    # MFMA kernel, 192 rows -> 256-row tiles
+    (256, 3000, 1, 8, 16, "bf16"),    # 128 rows: the W-streaming kernel
+    (100, 130, 2, 3, 5, "f32"),       # generic kernel
+])
+def test_clean_last_path(runner, d, V, B, T, K, dtype):
+    """Path K-1 without dropout: its token is the greedy token, its mask is all ones, its debug logits
+    carry no 1/(1-p), and the rules see paths 0..K-2 only (oracle with the same option)."""
+    wl, W, h, seeds, draft = _problem("clean", d, V, dtype, B, T, K, 0.3, seed=d + K, bonus=True)
+    hd, Wd = to_device(h, dtype), to_device(W, dtype)
+    flag = dmb.DM_FLAG_CLEAN_LAST_PATH
+    for rule in (orc.RULE_ANY, orc.RULE_MAJORITY):
+        ref = orc.verify(h, W, draft, seeds, K, wl.p, rule=rule, clean_last_path=True)
+        res = runner.verify(wl, hd, Wd, draft, seeds, rule=rule, flags=flag)
+        _check_against_oracle(res, ref, draft, rule, label=f"clean {dtype} M={B*T*K} rule={rule}")
+        assert np.array_equal(res["path_ids"][:, :, -1], orc.greedy_ids(h, W))
+        fewer = runner.verify(wl.with_(K=K - 1), hd, Wd, draft, seeds, rule=rule, K=K - 1)
+        for k in ("vote_ids", "vote_cnt", "hit", "accept_len"):
+            assert np.array_equal(res[k], fewer[k]), k
+    bits = runner.masks(wl, seeds, flags=flag)
+    plain = runner.masks(wl, seeds)
+    nw = (d + 31) // 32
+    full = np.full(nw, 0xFFFFFFFF, dtype=np.uint32)
+    if d % 32:
+        full[-1] = (1 << (d % 32)) - 1
+    assert np.array_equal(bits[:, :, -1], np.broadcast_to(full, bits[:, :, -1].shape))
+    assert np.array_equal(bits[:, :, :-1], plain[:, :, :-1])
+    ref = orc.verify(h, W, draft, seeds, K, wl.p, clean_last_path=True, want_logits=(0, min(V, 200)))
+    lg = runner.logits(wl, hd, Wd, seeds, 0, min(V, 200), flags=flag)
+    assert np.abs(lg - ref["logits"]).max() < (2e-2 if dtype == "bf16" else 1e-3)
