@@ -38,12 +38,10 @@
 // (walked in tiles of 256, the last one partial), so every CU streams the same number of
 // bytes; the slab pipeline runs across tile borders.
 #include "kernels.hpp"
+#include "mfma_common.hpp"
 
 namespace dm {
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int BN = 256;                 // vocabulary rows per tile
 constexpr int BK = 64;                  // k per slab
@@ -54,49 +52,12 @@ constexpr int THREADS = 512;
 __host__ __device__ constexpr int slab_bytes(int MT) { return W_SLAB_BYTES + MT * 4 * 1024; }
 __host__ __device__ constexpr int lds_bytes(int MT) { return NS * slab_bytes(MT) + 4 * MT * 32 * 8; }
 
-#define DM_GLOBAL_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
-#define DM_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
+// The W stream is copied with the non-temporal form (dma_copy16_stream): every byte of W is used once
+// per call, so its lines should be the first to leave L2, where the masked rows (re-read by every
+// workgroup for every vocabulary tile) have to stay.  Without the hint a fifth of the masked-row reads
+// missed L2 and the kernel fetched 13 % more than W from memory (measured: 184 us -> 162 us at
+// d=4096, V=128256).
 
-// s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14])
-#define DM_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
-#define DM_BARRIER()              \
-  do {                            \
-    asm volatile("" ::: "memory"); \
-    __builtin_amdgcn_s_barrier();  \
-    asm volatile("" ::: "memory"); \
-  } while (0)
-
-// One LDS-DMA copy instruction: every lane moves 16 bytes from (uniform base + its 32-bit offset)
-// to LDS address (uniform dst + 16 * lane).  Written out so that the address needs no vector ALU
-// instruction: producers share their SIMD with wavefronts that keep the vector ALU busy with MFMAs
-// (measured on the 256 x 256 kernel: one v_mov per copy cost 6 % of MFMA peak).
-__device__ __forceinline__ void dma_copy16(const char* base, uint32_t lane_off, unsigned char* lds_dst) {
-  const uint32_t dst = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_dst;
-  asm volatile(
-      "s_mov_b32 m0, %2\n\t"
-      "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %0, %1"
-      :
-      : "v"(lane_off), "s"(base), "s"(dst)
-      : "memory", "m0");
-}
-
-// Same copy for the W stream, marked non-temporal: every byte of W is used once per call, so its
-// lines should be the first to leave L2, where the masked rows (re-read by every workgroup for every
-// vocabulary tile) have to stay.  Without the hint a fifth of the masked-row reads missed L2 and the
-// kernel fetched 13 % more than W from memory (measured: 184 us -> 162 us at d=4096, V=128256).
-__device__ __forceinline__ void dma_copy16_stream(const char* base, uint32_t lane_off, unsigned char* lds_dst) {
-  const uint32_t dst = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_dst;
-  asm volatile(
-      "s_mov_b32 m0, %2\n\t"
-      "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %0, %1 nt"
-      :
-      : "v"(lane_off), "s"(base), "s"(dst)
-      : "memory", "m0");
-}
-
-// Rows [v_lo, v_hi) of W are covered by the grid; workgroup g owns rows_per_wg of them.
 // MODE 0: per-row argmax keys only (the verify path of the token-level rules).
 // MODE 1: debug dump of scaled logits for vocabulary rows [dv0, dv1) into logits[M, dv1 - dv0].
 // MODE 2: argmax keys AND every scaled logit stored for the distribution-level rule, in the

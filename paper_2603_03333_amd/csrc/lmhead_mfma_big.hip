@@ -24,12 +24,10 @@
 // workgroups and a slab of W once per sm workgroups.  Rounds sweep the vocabulary first, so
 // across the chip W streams from HBM once per sweep of up to 16 row tiles.
 #include "kernels.hpp"
+#include "mfma_common.hpp"
 
 namespace dm {
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int BN = 256;  // vocabulary rows per tile
 constexpr int BM = 256;  // masked rows per tile
@@ -51,30 +49,6 @@ struct Cfg {
   static constexpr int LDS_BYTES = NS * SLAB + RED_BYTES;
   static constexpr int SWZ_SHIFT = (BK == 64) ? 1 : 2;     // rows per 256-byte bank period: 2 or 4
 };
-
-#define DM_GLOBAL_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
-#define DM_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
-#define DM_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
-#define DM_BARRIER()               \
-  do {                             \
-    asm volatile("" ::: "memory"); \
-    __builtin_amdgcn_s_barrier();  \
-    asm volatile("" ::: "memory"); \
-  } while (0)
-
-// One LDS-DMA copy instruction: every lane moves 16 bytes from (uniform base + its 32-bit offset)
-// to LDS address (uniform dst + 16 * lane).  Written out so that the address needs no vector ALU
-// instruction: producers share their SIMD with wavefronts that keep the vector ALU busy with MFMAs.
-__device__ __forceinline__ void dma_copy16(const char* base, uint32_t lane_off, unsigned char* lds_dst) {
-  const uint32_t dst = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_dst;
-  asm volatile(
-      "s_mov_b32 m0, %2\n\t"
-      "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %0, %1"
-      :
-      : "v"(lane_off), "s"(base), "s"(dst)
-      : "memory", "m0");
-}
 
 // How the persistent grid walks the NV x NMB tiles (filled on the host).
 struct TileWalk {
