@@ -73,6 +73,11 @@ typedef enum {
  * Needs K >= 2. */
 #define DM_FLAG_CLEAN_LAST_PATH 4u
 
+/* Testing aid: always run the acceptance step as its own kernel.  (Without it, calls that go to the
+ * W-streaming kernel - bf16, at most 128 masked rows, token-level rule - run that step inside the
+ * contraction launch, in the workgroup that finishes last.) */
+#define DM_FLAG_SEPARATE_VOTE 8u
+
 /* Limits of this build. */
 #define DM_MAX_K 1024            /* paths per row */
 #define DM_MAX_ROWS_PER_SEQ 4096 /* T */

@@ -14,7 +14,7 @@ from typing import Optional, Sequence
 DM_OK, DM_EINVAL, DM_ENOMEM, DM_EHIP, DM_EUNSUPPORTED = 0, -1, -2, -3, -4
 DM_F32, DM_BF16 = 0, 1
 DM_RULE_ANY, DM_RULE_MAJORITY, DM_RULE_JS, DM_RULE_JS_OR_MAJORITY = 0, 1, 2, 3
-DM_FLAG_SHARE_MASK_ACROSS_POS, DM_FLAG_FORCE_GENERIC, DM_FLAG_CLEAN_LAST_PATH = 1, 2, 4
+DM_FLAG_SHARE_MASK_ACROSS_POS, DM_FLAG_FORCE_GENERIC, DM_FLAG_CLEAN_LAST_PATH, DM_FLAG_SEPARATE_VOTE = 1, 2, 4, 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdropmatch.so")

@@ -18,6 +18,7 @@ struct dm_ctx {
   int32_t d_pad = 0;     // max_d rounded up to 64
   void* a_ws = nullptr;               // masked rows
   unsigned long long* keys = nullptr; // packed (logit, index) argmax per row
+  unsigned int* done = nullptr;       // workgroups done, for the acceptance step fused into the contraction
   // distribution-level rule (dm_reserve_js): stored logits and per-chunk partial sums
   float* lt = nullptr;
   size_t lt_floats = 0;
@@ -82,7 +83,8 @@ const char* check_params(const dm_params* p, char* scratch, size_t n) {
   }
   if (p->rule >= DM_RULE_JS && p->parent != nullptr)
     return "the distribution-level rules are defined for chains only (parent must be NULL)";
-  if (p->flags & ~(DM_FLAG_SHARE_MASK_ACROSS_POS | DM_FLAG_FORCE_GENERIC | DM_FLAG_CLEAN_LAST_PATH)) return "unknown bits in flags";
+  if (p->flags & ~(DM_FLAG_SHARE_MASK_ACROSS_POS | DM_FLAG_FORCE_GENERIC | DM_FLAG_CLEAN_LAST_PATH | DM_FLAG_SEPARATE_VOTE))
+    return "unknown bits in flags";
   if ((p->flags & DM_FLAG_CLEAN_LAST_PATH) && p->K < 2) return "DM_FLAG_CLEAN_LAST_PATH needs K >= 2";
   if (!p->seeds) return "seeds is NULL";
   return nullptr;
@@ -134,7 +136,9 @@ struct DeviceGuard {
 // `ev` (optional): 3 events recorded before the mask kernel, between the two kernels, after.
 dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g, bool mfma, const void* h,
                           const void* W, float* logits, int v0, int v1, hipStream_t s, hipEvent_t* ev = nullptr,
-                          dm::LogitStore store = dm::LogitStore{nullptr, 0, 0, 0, 0}) {
+                          dm::LogitStore store = dm::LogitStore{nullptr, 0, 0, 0, 0},
+                          const dm::VoteFuse* fuse = nullptr, bool* fused = nullptr) {
+  if (fused) *fused = false;
   store.K = p->K;  // the debug dump needs K and the clean-path flag even when nothing is stored
   store.clean_last = g.clean_last;
   const bool bf16 = p->dtype == DM_BF16;
@@ -144,7 +148,7 @@ dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g,
   if (ev) (void)hipEventRecord(ev[1], s);
   const float scale = (float)(1.0 / (1.0 - (double)p->p));
   if (mfma && g.M <= 128)
-    e = dm::launch_lmhead_mfma(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, store, s);
+    e = dm::launch_lmhead_mfma(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, store, fuse, fused, s);
   else if (mfma)
     e = dm::launch_lmhead_mfma_big(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, store, s);
   else
@@ -201,7 +205,15 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
 
   hipEvent_t* ev = nullptr;
   if (ctx->prof_enabled && ctx->ev && ctx->prof_calls < DM_PROFILE_MAX_CALLS) ev = ctx->ev + kEv * ctx->prof_calls;
-  if (dm_status st = run_contraction(ctx, prm, g, mfma, h, W, nullptr, 0, 0, s, ev, store)) return st;
+  const int Kv = g.clean_last ? prm->K - 1 : prm->K;
+  dm::VoteOut out{accept_len, best_node, accept_mask, hit, path_ids, vote_ids, vote_cnt, js_draft, js_heads};
+  // token-level rules on the W-streaming kernel: the acceptance step runs as the tail of that launch
+  dm::VoteFuse fuse{ctx->done, draft_ids, prm->parent, prm->B, prm->T, prm->K, Kv, prm->rule, out};
+  const bool want_fuse = !js && !(prm->flags & DM_FLAG_SEPARATE_VOTE);
+  bool fused = false;
+  if (dm_status st = run_contraction(ctx, prm, g, mfma, h, W, nullptr, 0, 0, s, ev, store, want_fuse ? &fuse : nullptr,
+                                     &fused))
+    return st;
   hipError_t e;
   if (js) {
     const float scale = (float)(1.0 / (1.0 - (double)prm->p));
@@ -215,11 +227,11 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
     (void)hipEventRecord(ev[3], s);
     (void)hipEventRecord(ev[4], s);
   }
-  dm::VoteOut out{accept_len, best_node, accept_mask, hit, path_ids, vote_ids, vote_cnt, js_draft, js_heads};
-  e = dm::launch_vote_accept(ctx->keys, draft_ids, prm->parent, prm->B, prm->T, prm->K,
-                             g.clean_last ? prm->K - 1 : prm->K, prm->rule, out,
-                             js ? ctx->part_b : nullptr, js ? &jg : nullptr, s);
-  if (e != hipSuccess) return fail_hip(ctx, "vote_accept launch", e);
+  if (!fused) {
+    e = dm::launch_vote_accept(ctx->keys, draft_ids, prm->parent, prm->B, prm->T, prm->K, Kv, prm->rule, out,
+                               js ? ctx->part_b : nullptr, js ? &jg : nullptr, s);
+    if (e != hipSuccess) return fail_hip(ctx, "vote_accept launch", e);
+  }
   if (ev) {
     (void)hipEventRecord(ev[5], s);
     ++ctx->prof_calls;
@@ -273,9 +285,12 @@ dm_status dm_create(dm_ctx** out, int device, int64_t max_rows, int32_t max_d, i
   ctx->d_pad = (int32_t)round_up(max_d, 64);
   const size_t a_bytes = (size_t)ctx->rows_pad * (size_t)ctx->d_pad * 4;
   if ((e = hipMalloc(&ctx->a_ws, a_bytes)) != hipSuccess ||
-      (e = hipMalloc((void**)&ctx->keys, (size_t)ctx->rows_pad * 8)) != hipSuccess) {
+      (e = hipMalloc((void**)&ctx->keys, (size_t)ctx->rows_pad * 8)) != hipSuccess ||
+      (e = hipMalloc((void**)&ctx->done, 256)) != hipSuccess || (e = hipMemset(ctx->done, 0, 256)) != hipSuccess) {
     (void)hipGetLastError();
     if (ctx->a_ws) (void)hipFree(ctx->a_ws);
+    if (ctx->keys) (void)hipFree(ctx->keys);
+    if (ctx->done) (void)hipFree(ctx->done);
     delete ctx;
     return fail(nullptr, DM_ENOMEM, "workspace allocation of %zu bytes failed: %s", a_bytes, hipGetErrorString(e));
   }
@@ -283,6 +298,7 @@ dm_status dm_create(dm_ctx** out, int device, int64_t max_rows, int32_t max_d, i
       (e = dm::prepare_vote_accept()) != hipSuccess) {
     (void)hipFree(ctx->a_ws);
     (void)hipFree(ctx->keys);
+    (void)hipFree(ctx->done);
     delete ctx;
     return fail_hip(nullptr, "raising the dynamic LDS limit", e);
   }
@@ -298,6 +314,7 @@ dm_status dm_destroy(dm_ctx* ctx) {
   drop_events(ctx);
   if (ctx->a_ws) (void)hipFree(ctx->a_ws);
   if (ctx->keys) (void)hipFree(ctx->keys);
+  if (ctx->done) (void)hipFree(ctx->done);
   if (ctx->lt) (void)hipFree(ctx->lt);
   if (ctx->part_a) (void)hipFree(ctx->part_a);
   if (ctx->part_b) (void)hipFree(ctx->part_b);

@@ -49,9 +49,12 @@ hipError_t launch_lmhead_generic(const void* W, const void* a_ws, unsigned long 
                                  const LogitStore& store, hipStream_t stream);
 
 // Eq. (3) + per-row argmax on bf16 MFMA; a_ws swizzled layout; d % 64 == 0.
+struct VoteFuse;
+// fuse (optional): also run the acceptance step in the same launch (token-level rules, no dump, no store).
+// *fused is set when that was done.
 hipError_t launch_lmhead_mfma(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g,
                               int V, int num_cu, float* logits, int v0, int v1, float scale,
-                              const LogitStore& store, hipStream_t stream);
+                              const LogitStore& store, const VoteFuse* fuse, bool* fused, hipStream_t stream);
 hipError_t prepare_lmhead_mfma();  // raises the dynamic-LDS limit of the kernels once per process
 
 // Same contract for more than 128 masked rows (256 x 256 tiles); needs M_pad % 256 == 0.
@@ -95,6 +98,17 @@ struct VoteOut {
   float* js_heads;  // [B,T,K]
 };
 // part_b / jg: partial JS sums of launch_js_terms (rules 2 and 3), else nullptr.
+// Acceptance step run as the tail of the contraction kernel: every workgroup bumps `counter` when
+// its argmax keys are merged, and the workgroup that finds it at (workgroups - 1) runs the step for
+// all B sequences and puts the counter back to 0.  counter == nullptr: not fused.
+struct VoteFuse {
+  unsigned int* counter;
+  const int32_t* draft_ids;
+  const int32_t* parent;
+  int B, T, K, Kv, rule;
+  VoteOut out;
+};
+
 // Kv: paths the rules and the vote use (K, or K - 1 with a clean last path).
 hipError_t launch_vote_accept(const unsigned long long* keys, const int32_t* draft_ids, const int32_t* parent,
                               int B, int T, int K, int Kv, int rule, const VoteOut& out, const float* part_b,

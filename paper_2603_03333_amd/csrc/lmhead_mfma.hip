@@ -39,6 +39,7 @@
 // bytes; the slab pipeline runs across tile borders.
 #include "kernels.hpp"
 #include "mfma_common.hpp"
+#include "vote_body.hpp"
 
 namespace dm {
 namespace {
@@ -68,7 +69,8 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
                                                                  unsigned long long* __restrict__ keys, int d,
                                                                  int64_t M, int mt_total, int v_lo, int v_hi,
                                                                  int rows_per_wg, float* __restrict__ logits,
-                                                                 int dv0, int dv1, float scale, LogitStore store) {
+                                                                 int dv0, int dv1, float scale, LogitStore store,
+                                                                 VoteFuse fuse) {
   constexpr bool DUMP = MODE == 1;
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   constexpr int SLAB = slab_bytes(MT);
@@ -147,141 +149,172 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
       const int n = q / nchunks;
       if (MODE != 1 && q - n * nchunks == nchunks - 1) DM_BARRIER();  // pairs with the consumers' tile-end barrier
     }
-    return;
-  }
+  } else {
+    // -------------------------------------------------------------------- consumer
+    const int i32 = lane & 31;  // row inside a 32-row MFMA tile
+    const int hb = lane >> 5;   // which 8 of the 16 k of an MFMA step
+    const int swz = (i32 >> 1) & 7;
 
-  // -------------------------------------------------------------------- consumer
-  const int i32 = lane & 31;  // row inside a 32-row MFMA tile
-  const int hb = lane >> 5;   // which 8 of the 16 k of an MFMA step
-  const int swz = (i32 >> 1) & 7;
-
-  f32x16 acc[MT][2];
+    f32x16 acc[MT][2];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int vt = 0; vt < 2; ++vt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[mt][vt][r] = 0.f;
-
-  // MODE 2: where this lane's masked rows live in the logit store (row m = path m % K of position
-  // m / K), as a 32-bit byte offset from the first position of the workgroup's row block, so that a
-  // store needs one address register (uniform base + lane offset).  The lane's 4 * hb vocabulary-row
-  // offset is folded in.
-  uint32_t lt_off[MT];
-  bool lt_ok[MT];
-  char* lt_base = nullptr;
-  if (MODE == 2) {
-    const int64_t pos0 = ((int64_t)mblk * MT * 32) / store.K;
-    lt_base = reinterpret_cast<char*>(store.lt + pos0 * store.V * (int64_t)store.K4);
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int64_t m = (int64_t)(mblk * MT + mt) * 32 + i32;
-      const int64_t pos = m / store.K;
-      lt_ok[mt] = m < M;
-      lt_off[mt] = (uint32_t)(((pos - pos0) * store.V * store.K4 + (m - pos * store.K) + 4 * hb * store.K4) * 4);
-    }
-  }
-
-  for (int q = 0; q < total; ++q) {
-    DM_BARRIER();
-    const unsigned char* stage = lds + (q % NS) * SLAB;
-    const unsigned char* wbase = stage + wave * 8192 + i32 * 128;
-    const unsigned char* abase = stage + W_SLAB_BYTES + lane * 16;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      bf16x8 wf[2], af[MT];
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int vt = 0; vt < 2; ++vt)
-        wf[vt] = *reinterpret_cast<const bf16x8*>(wbase + vt * 4096 + 16 * ((2 * s + hb) ^ swz));
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) af[mt] = *reinterpret_cast<const bf16x8*>(abase + (s * MT + mt) * 1024);
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
-          acc[mt][vt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[vt], af[mt], acc[mt][vt], 0, 0, 0);
-    }
-    asm volatile("" ::: "memory");
+        for (int r = 0; r < 16; ++r) acc[mt][vt][r] = 0.f;
 
-    const int n = q / nchunks;
-    if (q - n * nchunks != nchunks - 1) continue;
-
-    // ---- tile finished: accumulator (vt, r) of lane holds row v, column m ----
-    //   v = v0 + 64*wave + 32*vt + 8*(r/4) + 4*hb + (r%4),  m = 32*(MT*mblk + mt) + lane%32
-    const int v0 = row_begin + n * BN;
-    if (DUMP) {
-      const int nv = dv1 - dv0;
+    // MODE 2: where this lane's masked rows live in the logit store (row m = path m % K of position
+    // m / K), as a 32-bit byte offset from the first position of the workgroup's row block, so that a
+    // store needs one address register (uniform base + lane offset).  The lane's 4 * hb vocabulary-row
+    // offset is folded in.
+    uint32_t lt_off[MT];
+    bool lt_ok[MT];
+    char* lt_base = nullptr;
+    if (MODE == 2) {
+      const int64_t pos0 = ((int64_t)mblk * MT * 32) / store.K;
+      lt_base = reinterpret_cast<char*>(store.lt + pos0 * store.V * (int64_t)store.K4);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const int64_t m = (int64_t)(mblk * MT + mt) * 32 + i32;
-        const float sc = (store.clean_last && m % store.K == store.K - 1) ? 1.0f : scale;  // clean path: no 1/(1-p)
+        const int64_t pos = m / store.K;
+        lt_ok[mt] = m < M;
+        lt_off[mt] = (uint32_t)(((pos - pos0) * store.V * store.K4 + (m - pos * store.K) + 4 * hb * store.K4) * 4);
+      }
+    }
+
+    for (int q = 0; q < total; ++q) {
+      DM_BARRIER();
+      const unsigned char* stage = lds + (q % NS) * SLAB;
+      const unsigned char* wbase = stage + wave * 8192 + i32 * 128;
+      const unsigned char* abase = stage + W_SLAB_BYTES + lane * 16;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        bf16x8 wf[2], af[MT];
+#pragma unroll
+        for (int vt = 0; vt < 2; ++vt)
+          wf[vt] = *reinterpret_cast<const bf16x8*>(wbase + vt * 4096 + 16 * ((2 * s + hb) ^ swz));
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) af[mt] = *reinterpret_cast<const bf16x8*>(abase + (s * MT + mt) * 1024);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int vt = 0; vt < 2; ++vt)
+            acc[mt][vt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[vt], af[mt], acc[mt][vt], 0, 0, 0);
+      }
+      asm volatile("" ::: "memory");
+
+      const int n = q / nchunks;
+      if (q - n * nchunks != nchunks - 1) continue;
+
+      // ---- tile finished: accumulator (vt, r) of lane holds row v, column m ----
+      //   v = v0 + 64*wave + 32*vt + 8*(r/4) + 4*hb + (r%4),  m = 32*(MT*mblk + mt) + lane%32
+      const int v0 = row_begin + n * BN;
+      if (DUMP) {
+        const int nv = dv1 - dv0;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const int64_t m = (int64_t)(mblk * MT + mt) * 32 + i32;
+          const float sc = (store.clean_last && m % store.K == store.K - 1) ? 1.0f : scale;  // clean path: no 1/(1-p)
+#pragma unroll
+          for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int v = v0 + 64 * wave + 32 * vt + 8 * (r >> 2) + 4 * hb + (r & 3);
+              if (m < M && v >= dv0 && v < dv1 && v < row_end) logits[m * nv + (v - dv0)] = sc * acc[mt][vt][r];
+              acc[mt][vt][r] = 0.f;
+            }
+        }
+        continue;
+      }
+
+      if (MODE == 2) {
 #pragma unroll
         for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
+            const int vu = v0 + 64 * wave + 32 * vt + 8 * (r >> 2) + (r & 3);  // + 4 * hb per lane
+            char* dst = lt_base + (int64_t)vu * store.K4 * 4;
+            const bool v_ok = vu + 4 * hb < row_end;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+              if (lt_ok[mt] && v_ok) *reinterpret_cast<float*>(dst + lt_off[mt]) = scale * acc[mt][vt][r];
+          }
+      }
+
+      unsigned long long* red = reinterpret_cast<unsigned long long*>(lds + NS * SLAB);  // [4][MT*32]
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        float best = -INFINITY;
+        uint32_t bv = 0xFFFFFFFFu;
+#pragma unroll
+        for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {  // ascending v for this lane: strict > keeps the smallest index
             const int v = v0 + 64 * wave + 32 * vt + 8 * (r >> 2) + 4 * hb + (r & 3);
-            if (m < M && v >= dv0 && v < dv1 && v < row_end) logits[m * nv + (v - dv0)] = sc * acc[mt][vt][r];
+            const float val = acc[mt][vt][r] + 0.0f;
+            if (v < row_end && (bv == 0xFFFFFFFFu || val > best)) {
+              best = val;
+              bv = (uint32_t)v;
+            }
             acc[mt][vt][r] = 0.f;
           }
-      }
-      continue;
-    }
-
-    if (MODE == 2) {
-#pragma unroll
-      for (int vt = 0; vt < 2; ++vt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int vu = v0 + 64 * wave + 32 * vt + 8 * (r >> 2) + (r & 3);  // + 4 * hb per lane
-          char* dst = lt_base + (int64_t)vu * store.K4 * 4;
-          const bool v_ok = vu + 4 * hb < row_end;
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
-            if (lt_ok[mt] && v_ok) *reinterpret_cast<float*>(dst + lt_off[mt]) = scale * acc[mt][vt][r];
-        }
-    }
-
-    unsigned long long* red = reinterpret_cast<unsigned long long*>(lds + NS * SLAB);  // [4][MT*32]
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      float best = -INFINITY;
-      uint32_t bv = 0xFFFFFFFFu;
-#pragma unroll
-      for (int vt = 0; vt < 2; ++vt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {  // ascending v for this lane: strict > keeps the smallest index
-          const int v = v0 + 64 * wave + 32 * vt + 8 * (r >> 2) + 4 * hb + (r & 3);
-          const float val = acc[mt][vt][r] + 0.0f;
-          if (v < row_end && (bv == 0xFFFFFFFFu || val > best)) {
-            best = val;
-            bv = (uint32_t)v;
-          }
-          acc[mt][vt][r] = 0.f;
-        }
-      unsigned long long key = (bv == 0xFFFFFFFFu) ? 0ull : pack_key(best, bv);
-      const unsigned long long other = __shfl_xor(key, 32, 64);
-      key = other > key ? other : key;
-      if (hb == 0) red[wave * (MT * 32) + mt * 32 + i32] = key;
-    }
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): LDS writes above are done
-    DM_BARRIER();
-    if (tid < MT * 32) {
-      unsigned long long key = red[tid];
-#pragma unroll
-      for (int w = 1; w < 4; ++w) {
-        const unsigned long long other = red[w * (MT * 32) + tid];
+        unsigned long long key = (bv == 0xFFFFFFFFu) ? 0ull : pack_key(best, bv);
+        const unsigned long long other = __shfl_xor(key, 32, 64);
         key = other > key ? other : key;
+        if (hb == 0) red[wave * (MT * 32) + mt * 32 + i32] = key;
       }
-      const int64_t m = (int64_t)mblk * (MT * 32) + tid;
-      if (m < M && key != 0ull) atomicMax(&keys[m], key);
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): LDS writes above are done
+      DM_BARRIER();
+      if (tid < MT * 32) {
+        unsigned long long key = red[tid];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+          const unsigned long long other = red[w * (MT * 32) + tid];
+          key = other > key ? other : key;
+        }
+        const int64_t m = (int64_t)mblk * (MT * 32) + tid;
+        if (m < M && key != 0ull) atomicMax(&keys[m], key);
+      }
+    }
+  }  // consumer
+
+  // -------------------------------------------------------------------- fused acceptance step
+  // Every thread waits until its own argmax merges are done, the workgroup meets, one thread bumps
+  // the counter; the workgroup that sees all others done reads the final keys and runs the vote /
+  // rule / prefix step, then clears the counter for the next call.  The merges, the counter and the
+  // reads of the keys are all device-scope atomic operations, which are carried out at the memory
+  // side, past the per-XCD L2s; that is what makes the keys of other XCDs visible here.  A device
+  // scope fence is deliberately not used: it writes back and invalidates the XCD's whole L2, which the
+  // workgroups still streaming W depend on for the masked rows (measured: 160 us -> 218 us).
+  // The LDS slabs are free by now.
+  if (MODE == 0 && fuse.counter != nullptr) {
+    asm volatile("" ::: "memory");
+    DM_WAIT_VMCNT(0);
+    __syncthreads();
+    int* flag = reinterpret_cast<int*>(lds);
+    if (tid == 0) {
+      const unsigned int done = atomicAdd(fuse.counter, 1u);
+      *flag = (done == gridDim.x * gridDim.y - 1u) ? 1 : 0;
+    }
+    __syncthreads();
+    const bool last = *flag != 0;
+    __syncthreads();  // everyone has read the flag before the scratch below overwrites it
+    if (last) {
+      for (int b = 0; b < fuse.B; ++b) {
+        vote_accept_body<true>(b, tid, THREADS, reinterpret_cast<int32_t*>(lds), keys, fuse.draft_ids, fuse.parent,
+                               fuse.T, fuse.K, fuse.Kv, fuse.rule, fuse.out, nullptr, JsGeom{});
+        __syncthreads();
+      }
+      if (tid == 0) atomicExch(fuse.counter, 0u);
     }
   }
 }
 
 template <int MT>
 hipError_t run(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V, int num_cu,
-               float* logits, int v0, int v1, float scale, const LogitStore& store, hipStream_t stream) {
+               float* logits, int v0, int v1, float scale, const LogitStore& store, const VoteFuse& fuse,
+               hipStream_t stream) {
   const bool dump = logits != nullptr;
   const int v_lo = dump ? v0 : 0;
   const int v_hi = dump ? v1 : V;
@@ -298,7 +331,7 @@ hipError_t run(const void* W, const void* a_ws, unsigned long long* keys, const 
 #define DM_LAUNCH(MODE)                                                                                         \
   lmhead_mfma_kernel<MT, MODE><<<grid, block, lds_bytes(MT), stream>>>(                                          \
       static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo, v_hi,    \
-      rows_per_wg, logits, v0, v1, scale, store)
+      rows_per_wg, logits, v0, v1, scale, store, fuse)
   if (dump)
     DM_LAUNCH(1);
   else if (store.lt != nullptr)
@@ -333,16 +366,24 @@ hipError_t prepare_lmhead_mfma() {
 
 hipError_t launch_lmhead_mfma(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V,
                               int num_cu, float* logits, int v0, int v1, float scale, const LogitStore& store,
-                              hipStream_t stream) {
+                              const VoteFuse* fuse_in, bool* fused, hipStream_t stream) {
+  // the acceptance step rides along when this is the plain verify path and its scratch fits the slabs
+  VoteFuse fuse{};
+  const bool can_fuse = fuse_in != nullptr && fuse_in->counter != nullptr && logits == nullptr &&
+                        store.lt == nullptr && fuse_in->rule < 2 && fuse_in->B <= 8 &&  // one workgroup does all sequences
+                       
+                        vote_lds_ints(fuse_in->T, fuse_in->K, fuse_in->rule) * sizeof(int32_t) <= (size_t)lds_bytes(1);
+  if (can_fuse) fuse = *fuse_in;
+  if (fused) *fused = can_fuse;
   const int mt_total = (int)(g.M_pad >> 5);
   if (mt_total >= 4) {
     if (mt_total % 4 != 0) return hipErrorInvalidValue;
-    return run<4>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, stream);
+    return run<4>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, stream);
   }
   switch (mt_total) {
-    case 1: return run<1>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, stream);
-    case 2: return run<2>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, stream);
-    case 3: return run<3>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, stream);
+    case 1: return run<1>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, stream);
+    case 2: return run<2>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, stream);
+    case 3: return run<3>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, stream);
     default: return hipErrorInvalidValue;
   }
 }

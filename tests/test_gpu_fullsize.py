@@ -52,9 +52,12 @@ def _run_config(name, sample):
         hd, Wd = to_device(h, wl.dtype), to_device(W, wl.dtype)
         print(f"[{name}] running the HIP path", flush=True)
         res = r.verify(wl, hd, Wd, draft, seeds, parent=parent)
-        res2 = r.verify(wl, hd, Wd, draft, seeds, parent=parent)
-        for k in res:
-            assert np.array_equal(res[k], res2[k]), f"{k} not deterministic"
+        # repeated calls (for at most 128 rows the acceptance step runs inside the contraction launch,
+        # elected by a counter that every call has to leave at zero): identical outputs every time
+        for rep in range(40 if wl.rows <= 128 else 1):
+            res2 = r.verify(wl, hd, Wd, draft, seeds, parent=parent)
+            for k in res:
+                assert np.array_equal(res[k], res2[k]), f"{k} not deterministic (repetition {rep})"
         # masks of sampled rows, bit-exact
         bits = r.masks(wl, seeds)
         for b, t in rows[:4]:

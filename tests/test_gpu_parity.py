@@ -391,3 +391,26 @@ def test_clean_last_path(runner, d, V, B, T, K, dtype):
     ref = orc.verify(h, W, draft, seeds, K, wl.p, clean_last_path=True, want_logits=(0, min(V, 200)))
     lg = runner.logits(wl, hd, Wd, seeds, 0, min(V, 200), flags=flag)
     assert np.abs(lg - ref["logits"]).max() < (2e-2 if dtype == "bf16" else 1e-3)
+
+
+# ------------------------------------------------------------------ acceptance step inside the contraction launch
+@pytest.mark.parametrize("B,T,K,tree", [(1, 8, 16, False), (2, 4, 16, False), (8, 2, 8, False), (1, 5, 5, False),
+                                        (2, 16, 4, True)])
+def test_fused_and_separate_acceptance_step_agree(runner, B, T, K, tree):
+    """At most 128 masked rows, bf16: the vote / rule / prefix step runs in the workgroup of the
+    contraction kernel that finishes last.  Same outputs as with the step as its own kernel, and as
+    the oracle; repeated calls reuse the counter that elects that workgroup."""
+    wl, W, h, seeds, draft = _problem("fuse", 256, 3000, "bf16", B, T, K, 0.2, seed=40 + B * T + K, bonus=not tree)
+    parent = None
+    if tree:
+        parent = wk.make_tree_parents(wl.with_(tree=True), max_depth=5, max_branch=3)
+        draft = wk.make_tree_draft_ids(wl, parent, orc.greedy_ids(h, W))
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    for rule in (orc.RULE_ANY, orc.RULE_MAJORITY):
+        ref = orc.verify(h, W, draft, seeds, K, wl.p, rule=rule, parent=parent)
+        for rep in range(3):
+            fused = runner.verify(wl, hd, Wd, draft, seeds, rule=rule, parent=parent)
+            _check_against_oracle(fused, ref, draft, rule, parent=parent, label=f"fused B={B} T={T} K={K} rule={rule}")
+        apart = runner.verify(wl, hd, Wd, draft, seeds, rule=rule, parent=parent, flags=dmb.DM_FLAG_SEPARATE_VOTE)
+        for k in fused:
+            assert np.array_equal(fused[k], apart[k]), k
