@@ -36,6 +36,13 @@ listed with its reason in the design notes of the repository):
     tokens (the paper's agreement table lists majority sizes 1..5 for K = 5),
     ties between modes -> smallest token id;
   * draft id < 0 means "no draft token at this row" and never matches;
+  * sampled path tokens (the paper says a path's token may be "selected by nucleus sampling"
+    instead of the arg max, without parameters): with a temperature tau the token of path i
+    is drawn from Softmax(l^(i) / tau) by the Gumbel-max construction,
+    y = argmax_v (l[v] / tau + g[v]), g[v] = -ln(-ln u[v]), with u[v] = ((w >> 9) + 1/2) 2^-23
+    and w the Philox4x32-10 word (v & 3) of counter (v >> 2, t, i, step) under the key
+    seed + 0x9E3779B97F4A7C15 (mod 2^64) - a stream separate from the masks'.  Truncation
+    to a nucleus (top-p < 1) is not implemented;
   * `clean_last_path` (the paper does not say which token is emitted after a rejection
     or as the bonus token): path K-1 of every row is the plain LM head, h_t itself
     with no mask and no scale; its token is reported in path_ids[..., K-1] and the
@@ -183,6 +190,31 @@ def row_states(h_t, seed, step, tt, K, d, p, clean_last_path=False):
             raise ValueError("clean_last_path needs K >= 2")
         rows[K - 1] = np.asarray(h_t, dtype=np.float64).copy()
     return np.stack(rows, axis=0)
+
+
+SAMPLE_KEY_OFFSET = 0x9E3779B97F4A7C15    # added to the sequence seed for the sampling stream
+
+
+def sampling_uniforms(seed: int, step: int, t: int, i: int, V: int) -> np.ndarray:
+    """u[v] in (0, 1) for the sampled token of path i at row t: 23 random bits per vocabulary
+    entry, centred in their cell so that u is exact in float32 and never 0 or 1."""
+    key = (int(seed) + SAMPLE_KEY_OFFSET) & 0xFFFFFFFFFFFFFFFF
+    nctr = (V + 3) // 4
+    words = philox4x32_10(np.arange(nctr, dtype=np.uint64), t, i, step, key & 0xFFFFFFFF, key >> 32)
+    w = np.stack(words, axis=1).reshape(-1)[:V].astype(np.uint64)
+    return ((w >> np.uint64(9)).astype(np.float64) + 0.5) * 2.0 ** -23
+
+
+def gumbel_noise(u: np.ndarray) -> np.ndarray:
+    """Standard Gumbel variates g = -ln(-ln u) (quantile function of the Gumbel distribution)."""
+    u = np.asarray(u, dtype=np.float64)
+    return -np.log(-np.log1p(-(1.0 - u)))      # ln u through log1p: exact near u = 1, where g is largest
+
+
+def sampled_token(logits: np.ndarray, tau: float, g: np.ndarray):
+    """Gumbel-max draw from Softmax(logits / tau): argmax_v (logits[v] / tau + g[v]), ties ->
+    smallest v.  Also returns the top-1 minus top-2 gap of the perturbed values."""
+    return path_token(np.asarray(logits, dtype=np.float64) / float(tau) + g)
 
 
 # --------------------------------------------------------------------------- #
@@ -370,7 +402,7 @@ def acceptance_from_hits(hit):
 # --------------------------------------------------------------------------- #
 def verify(h, W, draft_ids, seeds, K: int, p, step: int = 0, rule: int = RULE_ANY,
            share_mask_across_pos: bool = False, parent=None, want_logits=None,
-           clean_last_path: bool = False):
+           clean_last_path: bool = False, temperature=None):
     """One DropMatch verification step for B sequences.
 
     h          [B, T, d]  final hidden states (any float dtype; used as float64)
@@ -379,6 +411,9 @@ def verify(h, W, draft_ids, seeds, K: int, p, step: int = 0, rule: int = RULE_AN
     seeds      [B]        64-bit mask seed per sequence
     parent     None (chain) or [B, T] (tree)
     want_logits optional (v0, v1): also return logits[B*T*K, v1-v0] for parity of values
+    temperature None: path token = arg max.  A positive number: path token sampled from
+               Softmax(l / temperature) (see sampled_token; a clean last path stays arg max);
+               `gap` then refers to the perturbed values
 
     Returns a dict of numpy arrays: path_ids[B,T,K], gap[B,T,K] (top-1 minus top-2
     logit of each path), vote_ids[B,T], vote_cnt[B,T], hit[B,T], accept_mask[B,T],
@@ -406,7 +441,11 @@ def verify(h, W, draft_ids, seeds, K: int, p, step: int = 0, rule: int = RULE_AN
             Hm = row_states(h[b, t], seeds[b], step, tt, K, d, p, clean_last_path)   # [K, d]
             L = W64 @ Hm.T                                       # Eq. (3), [V, K]
             for i in range(K):
-                path_ids[b, t, i], gap[b, t, i] = path_token(L[:, i])
+                if temperature is None or (clean_last_path and i == K - 1):
+                    path_ids[b, t, i], gap[b, t, i] = path_token(L[:, i])
+                else:
+                    g = gumbel_noise(sampling_uniforms(seeds[b], step, t, i, V))
+                    path_ids[b, t, i], gap[b, t, i] = sampled_token(L[:, i], temperature, g)
                 if logits_out is not None:
                     logits_out[(b * T + t) * K + i] = L[v0:v1, i]
 

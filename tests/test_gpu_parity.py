@@ -414,3 +414,24 @@ def test_fused_and_separate_acceptance_step_agree(runner, B, T, K, tree):
         apart = runner.verify(wl, hd, Wd, draft, seeds, rule=rule, parent=parent, flags=dmb.DM_FLAG_SEPARATE_VOTE)
         for k in fused:
             assert np.array_equal(fused[k], apart[k]), k
+
+
+# ------------------------------------------------------------------ peaked heads (the regime of a real LM)
+def test_planted_dominant_tokens(runner):
+    """Hidden states with a planted dominant token (stand-in for the paper's agreement table, where all
+    K = 5 paths agree at 98 % of positions): most rows are unanimous, drafts equal to the planted
+    token are accepted under both rules, and everything matches the oracle."""
+    wl = wk.Workload("planted", d=256, V=4096, dtype="bf16", B=4, T=8, K=5, p=0.3, bonus=True, data_seed=88)
+    W = wk.make_weight(wl, sigma=0.05)
+    h, planted = wk.make_planted_hidden(wl, W, alpha=14.0)
+    seeds = wk.make_seeds(wl, base_seed=3)
+    draft = planted.copy()
+    draft[:, -1] = -1
+    draft[1, 3] = (planted[1, 3] + 1) % wl.V          # one wrong draft token: the prefix stops there
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    for rule in (orc.RULE_ANY, orc.RULE_MAJORITY):
+        ref = orc.verify(h, W, draft, seeds, wl.K, wl.p, rule=rule)
+        res = runner.verify(wl, hd, Wd, draft, seeds, rule=rule)
+        _check_against_oracle(res, ref, draft, rule, label=f"planted rule={rule}")
+        assert (res["vote_cnt"] == wl.K).mean() > 0.9
+        assert res["accept_len"].tolist() == [7, 3, 7, 7]
