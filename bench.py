@@ -34,6 +34,8 @@ def parse_args():
     ap.add_argument("--paths", type=int, default=0, help="override K, the dropout paths per row (rows sweep)")
     ap.add_argument("--batch", type=int, default=0, help="override B, the number of sequences (rows sweep)")
     ap.add_argument("--p-drop", type=float, default=-1.0, help="override the dropout probability p (bigvocab sweep)")
+    ap.add_argument("--temperature", type=float, default=0.0,
+                    help="> 0: path tokens sampled from Softmax(l / temperature) instead of the arg max")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of a HIP graph that holds one captured step instead of eager calls")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (for profiler runs)")
@@ -154,7 +156,9 @@ def main():
     if js:
         dmb.dm_reserve_js(ctx, wl.B * wl.T, wl.K)
     prm, keep = dmb.make_params(wl.B, wl.T, wl.K, wl.d, wl.V, dmb.DM_BF16 if bf16 else dmb.DM_F32, wl.p,
-                                [int(s) for s in seeds], parent=parent_dev, rule=rule)
+                                [int(s) for s in seeds], parent=parent_dev, rule=rule,
+                                flags=dmb.DM_FLAG_SAMPLE_PATHS if args.temperature > 0 else 0,
+                                temperature=args.temperature)
     kernel = dmb.dm_kernel_choice(prm)
     out = dict(accept_len=torch.zeros(wl.B, dtype=torch.int32, device="cuda"),
                best_node=torch.zeros(wl.B, dtype=torch.int32, device="cuda"),
@@ -257,7 +261,8 @@ def main():
         "config": {"workload": f"{wl.name}: d={wl.d} V={wl.V} {wl.dtype} B={wl.B} T={wl.T} K={wl.K} p={wl.p}"
                                + (" tree" if wl.tree else " chain") + (" +bonus row" if wl.bonus else ""),
                    "rows": M, "positions_per_step": positions, "rule": args.rule,
-                   "launch": "hip graph replay" if args.graph else "eager"},
+                   "launch": "hip graph replay" if args.graph else "eager",
+                   "path_tokens": f"sampled, temperature {args.temperature}" if args.temperature > 0 else "arg max"},
         "roofline": roof,
     }
     if not args.no_cpu_baseline:

@@ -73,6 +73,16 @@ typedef enum {
  * Needs K >= 2. */
 #define DM_FLAG_CLEAN_LAST_PATH 4u
 
+/* Sampled path tokens.  The paper remarks that the token of a path may be "selected by nucleus
+ * sampling" instead of being the arg max, without giving parameters.  With this flag the token of path
+ * i at row t is a draw from Softmax(l_t^(i) / temperature), made by the Gumbel-max construction so that
+ * it is a pure function of (seed, step, i, t): y = argmax_v (l[v] / temperature + g[v]),
+ * g[v] = -ln(-ln u[v]), u[v] = ((w >> 9) + 1/2) 2^-23, w = word (v & 3) of Philox4x32-10 with counter
+ * (v >> 2, t, i, step) and key = seed + 0x9E3779B97F4A7C15 (mod 2^64; a stream apart from the masks').
+ * Ties -> smallest v.  Truncation to a nucleus (top-p < 1) is not implemented.  Needs
+ * prm->temperature > 0; token-level rules only (dropmatch_verify); a clean last path stays arg max. */
+#define DM_FLAG_SAMPLE_PATHS 16u
+
 /* Testing aid: always run the acceptance step as its own kernel.  (Without it, calls that go to the
  * W-streaming kernel - bf16, at most 128 masked rows, token-level rule - run that step inside the
  * contraction launch, in the workgroup that finishes last.) */
@@ -100,11 +110,12 @@ typedef struct {
   const int32_t* parent; /* DEVICE [B,T] or NULL.  NULL: chain.  Else tree: parent[b,0] = -1,
                             0 <= parent[b,n] < n.  A node whose parent index breaks this is
                             treated as rejected (never read out of bounds). */
+  float temperature;     /* DM_FLAG_SAMPLE_PATHS only: > 0, finite.  Ignored otherwise. */
 } dm_params;
 
 /* Create a context on HIP device `device` able to serve calls with B*T*K <= max_rows,
  * d <= max_d, V <= max_V.  Allocates the workspace (masked rows: max_rows rounded up to
- * 256 times max_d rounded up to 64 elements of 4 bytes, plus 8 bytes per row).  The context
+ * 256 times max_d rounded up to 64 elements of 4 bytes, plus 16 bytes per row).  The context
  * may be used from one host thread at a time; calls on one context must be enqueued on
  * one stream (or be ordered by the caller), since they share the workspace. */
 dm_status dm_create(dm_ctx** out, int device, int64_t max_rows, int32_t max_d, int32_t max_V);

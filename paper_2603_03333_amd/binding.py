@@ -15,6 +15,7 @@ DM_OK, DM_EINVAL, DM_ENOMEM, DM_EHIP, DM_EUNSUPPORTED = 0, -1, -2, -3, -4
 DM_F32, DM_BF16 = 0, 1
 DM_RULE_ANY, DM_RULE_MAJORITY, DM_RULE_JS, DM_RULE_JS_OR_MAJORITY = 0, 1, 2, 3
 DM_FLAG_SHARE_MASK_ACROSS_POS, DM_FLAG_FORCE_GENERIC, DM_FLAG_CLEAN_LAST_PATH, DM_FLAG_SEPARATE_VOTE = 1, 2, 4, 8
+DM_FLAG_SAMPLE_PATHS = 16
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdropmatch.so")
@@ -27,7 +28,8 @@ EXPORTS = ("dm_create", "dm_destroy", "dm_last_error", "dm_validate", "dropmatch
 class dm_params(C.Structure):
     _fields_ = [("B", C.c_int32), ("T", C.c_int32), ("K", C.c_int32), ("d", C.c_int32), ("V", C.c_int32),
                 ("dtype", C.c_int32), ("p", C.c_float), ("step", C.c_uint32), ("rule", C.c_int32),
-                ("flags", C.c_uint32), ("seeds", C.POINTER(C.c_uint64)), ("parent", C.c_void_p)]
+                ("flags", C.c_uint32), ("seeds", C.POINTER(C.c_uint64)), ("parent", C.c_void_p),
+                ("temperature", C.c_float)]
 
 
 class DropMatchError(RuntimeError):
@@ -88,10 +90,11 @@ def _ptr(t) -> Optional[int]:
 
 
 def make_params(B: int, T: int, K: int, d: int, V: int, dtype: int, p: float, seeds: Sequence[int],
-                step: int = 0, rule: int = DM_RULE_ANY, flags: int = 0, parent=None):
+                step: int = 0, rule: int = DM_RULE_ANY, flags: int = 0, parent=None, temperature: float = 0.0):
     """Fill a dm_params.  Returns (params, keepalive): hold `keepalive` while params is in use."""
     arr = (C.c_uint64 * len(seeds))(*[int(s) & 0xFFFFFFFFFFFFFFFF for s in seeds])
-    prm = dm_params(B, T, K, d, V, dtype, p, step, rule, flags, C.cast(arr, C.POINTER(C.c_uint64)), _ptr(parent))
+    prm = dm_params(B, T, K, d, V, dtype, p, step, rule, flags, C.cast(arr, C.POINTER(C.c_uint64)), _ptr(parent),
+                    temperature)
     return prm, (arr, parent)
 
 

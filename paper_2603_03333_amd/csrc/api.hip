@@ -19,6 +19,7 @@ struct dm_ctx {
   void* a_ws = nullptr;               // masked rows
   unsigned long long* keys = nullptr; // packed (logit, index) argmax per row
   unsigned int* done = nullptr;       // workgroups done, for the acceptance step fused into the contraction
+  uint64_t* seeds_dev = nullptr;      // seeds of the current call, for the sampling epilogues
   // distribution-level rule (dm_reserve_js): stored logits and per-chunk partial sums
   float* lt = nullptr;
   size_t lt_floats = 0;
@@ -83,9 +84,15 @@ const char* check_params(const dm_params* p, char* scratch, size_t n) {
   }
   if (p->rule >= DM_RULE_JS && p->parent != nullptr)
     return "the distribution-level rules are defined for chains only (parent must be NULL)";
-  if (p->flags & ~(DM_FLAG_SHARE_MASK_ACROSS_POS | DM_FLAG_FORCE_GENERIC | DM_FLAG_CLEAN_LAST_PATH | DM_FLAG_SEPARATE_VOTE))
+  if (p->flags & ~(DM_FLAG_SHARE_MASK_ACROSS_POS | DM_FLAG_FORCE_GENERIC | DM_FLAG_CLEAN_LAST_PATH | DM_FLAG_SEPARATE_VOTE |
+                   DM_FLAG_SAMPLE_PATHS))
     return "unknown bits in flags";
   if ((p->flags & DM_FLAG_CLEAN_LAST_PATH) && p->K < 2) return "DM_FLAG_CLEAN_LAST_PATH needs K >= 2";
+  if (p->flags & DM_FLAG_SAMPLE_PATHS) {
+    if (!(p->temperature > 0.0f) || !std::isfinite(p->temperature))
+      return "DM_FLAG_SAMPLE_PATHS needs a finite temperature > 0";
+    if (p->rule >= DM_RULE_JS) return "sampled path tokens go with the token-level rules only";
+  }
   if (!p->seeds) return "seeds is NULL";
   return nullptr;
 }
@@ -143,16 +150,23 @@ dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g,
   store.clean_last = g.clean_last;
   const bool bf16 = p->dtype == DM_BF16;
   if (ev) (void)hipEventRecord(ev[0], s);
-  hipError_t e = dm::launch_mask_rows(h, ctx->a_ws, ctx->keys, p->seeds, g, bf16, mfma, s);
+  const bool sample = (p->flags & DM_FLAG_SAMPLE_PATHS) && logits == nullptr;
+  hipError_t e = dm::launch_mask_rows(h, ctx->a_ws, ctx->keys, p->seeds, g, bf16, mfma,
+                                      sample ? ctx->seeds_dev : nullptr, s);
   if (e != hipSuccess) return fail_hip(ctx, "mask_rows launch", e);
   if (ev) (void)hipEventRecord(ev[1], s);
   const float scale = (float)(1.0 / (1.0 - (double)p->p));
+  dm::SampleCfg samp{nullptr, 0.f, p->T, p->K, p->step, g.clean_last};
+  if (sample) {
+    samp.seeds = ctx->seeds_dev;
+    samp.zscale = (float)(1.0 / (1.0 - (double)p->p) / (double)p->temperature);
+  }
   if (mfma && g.M <= 128)
-    e = dm::launch_lmhead_mfma(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, store, fuse, fused, s);
+    e = dm::launch_lmhead_mfma(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, store, samp, fuse, fused, s);
   else if (mfma)
-    e = dm::launch_lmhead_mfma_big(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, store, s);
+    e = dm::launch_lmhead_mfma_big(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, store, samp, s);
   else
-    e = dm::launch_lmhead_generic(W, ctx->a_ws, ctx->keys, g, p->V, bf16, logits, v0, v1, scale, store, s);
+    e = dm::launch_lmhead_generic(W, ctx->a_ws, ctx->keys, g, p->V, bf16, logits, v0, v1, scale, store, samp, s);
   if (e != hipSuccess) return fail_hip(ctx, "lmhead launch", e);
   if (ev) (void)hipEventRecord(ev[2], s);
   return DM_OK;
@@ -286,11 +300,13 @@ dm_status dm_create(dm_ctx** out, int device, int64_t max_rows, int32_t max_d, i
   const size_t a_bytes = (size_t)ctx->rows_pad * (size_t)ctx->d_pad * 4;
   if ((e = hipMalloc(&ctx->a_ws, a_bytes)) != hipSuccess ||
       (e = hipMalloc((void**)&ctx->keys, (size_t)ctx->rows_pad * 8)) != hipSuccess ||
-      (e = hipMalloc((void**)&ctx->done, 256)) != hipSuccess || (e = hipMemset(ctx->done, 0, 256)) != hipSuccess) {
+      (e = hipMalloc((void**)&ctx->done, 256)) != hipSuccess || (e = hipMemset(ctx->done, 0, 256)) != hipSuccess ||
+      (e = hipMalloc((void**)&ctx->seeds_dev, (size_t)ctx->rows_pad * 8)) != hipSuccess) {
     (void)hipGetLastError();
     if (ctx->a_ws) (void)hipFree(ctx->a_ws);
     if (ctx->keys) (void)hipFree(ctx->keys);
     if (ctx->done) (void)hipFree(ctx->done);
+    if (ctx->seeds_dev) (void)hipFree(ctx->seeds_dev);
     delete ctx;
     return fail(nullptr, DM_ENOMEM, "workspace allocation of %zu bytes failed: %s", a_bytes, hipGetErrorString(e));
   }
@@ -299,6 +315,7 @@ dm_status dm_create(dm_ctx** out, int device, int64_t max_rows, int32_t max_d, i
     (void)hipFree(ctx->a_ws);
     (void)hipFree(ctx->keys);
     (void)hipFree(ctx->done);
+    (void)hipFree(ctx->seeds_dev);
     delete ctx;
     return fail_hip(nullptr, "raising the dynamic LDS limit", e);
   }
@@ -315,6 +332,7 @@ dm_status dm_destroy(dm_ctx* ctx) {
   if (ctx->a_ws) (void)hipFree(ctx->a_ws);
   if (ctx->keys) (void)hipFree(ctx->keys);
   if (ctx->done) (void)hipFree(ctx->done);
+  if (ctx->seeds_dev) (void)hipFree(ctx->seeds_dev);
   if (ctx->lt) (void)hipFree(ctx->lt);
   if (ctx->part_a) (void)hipFree(ctx->part_a);
   if (ctx->part_b) (void)hipFree(ctx->part_b);

@@ -26,8 +26,10 @@ struct RowGeom {
 // Eq. (1)+(2) without the scale: masked rows a = keep ? h : 0 into the workspace, and the
 // per-row argmax keys reset to 0.  swizzled = layout of the MFMA kernel's B-fragments;
 // otherwise plain [M_pad, d_pad].  is_bf16 selects the element type of h and the workspace.
+// seeds_dev (optional): DEVICE [B], receives the seeds (for the sampling epilogues of the same call).
 hipError_t launch_mask_rows(const void* h, void* a_ws, unsigned long long* keys, const uint64_t* seeds_host,
-                            const RowGeom& g, bool is_bf16, bool swizzled, hipStream_t stream);
+                            const RowGeom& g, bool is_bf16, bool swizzled, uint64_t* seeds_dev,
+                            hipStream_t stream);
 
 // Eq. (1) only, bit-packed [M, ceil(d/32)].
 hipError_t launch_mask_bits(uint32_t* bits, const uint64_t* seeds_host, const RowGeom& g, hipStream_t stream);
@@ -42,11 +44,21 @@ struct LogitStore {
   int clean_last;  // debug dump only: rows of path K-1 are reported without the factor 1/(1-p)
 };
 
+// Sampled path tokens (seeds == nullptr: plain arg max).  The contraction epilogues then compare
+// zscale * accumulator + Gumbel noise instead of the accumulator (zscale = 1 / ((1-p) tau)).
+struct SampleCfg {
+  const uint64_t* seeds;  // DEVICE [B], written by the mask kernel of the same call
+  float zscale;
+  int T, K;
+  uint32_t step;
+  int clean_last;
+};
+
 // Eq. (3) + per-row argmax, generic fp32-FMA tiles.  a_ws plain layout.  If logits != null the
 // kernel instead stores scale * accumulator for v in [v0, v1) and touches no keys.
 hipError_t launch_lmhead_generic(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g,
                                  int V, bool is_bf16, float* logits, int v0, int v1, float scale,
-                                 const LogitStore& store, hipStream_t stream);
+                                 const LogitStore& store, const SampleCfg& samp, hipStream_t stream);
 
 // Eq. (3) + per-row argmax on bf16 MFMA; a_ws swizzled layout; d % 64 == 0.
 struct VoteFuse;
@@ -54,13 +66,14 @@ struct VoteFuse;
 // *fused is set when that was done.
 hipError_t launch_lmhead_mfma(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g,
                               int V, int num_cu, float* logits, int v0, int v1, float scale,
-                              const LogitStore& store, const VoteFuse* fuse, bool* fused, hipStream_t stream);
+                              const LogitStore& store, const SampleCfg& samp, const VoteFuse* fuse, bool* fused,
+                              hipStream_t stream);
 hipError_t prepare_lmhead_mfma();  // raises the dynamic-LDS limit of the kernels once per process
 
 // Same contract for more than 128 masked rows (256 x 256 tiles); needs M_pad % 256 == 0.
 hipError_t launch_lmhead_mfma_big(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g,
                                   int V, int num_cu, float* logits, int v0, int v1, float scale,
-                                  const LogitStore& store, hipStream_t stream);
+                                  const LogitStore& store, const SampleCfg& samp, hipStream_t stream);
 hipError_t prepare_lmhead_mfma_big();
 
 // Distribution-level rule (Eq. (5), (6)) over the stored logits, in two passes over the vocabulary;

@@ -6,6 +6,7 @@
 // k in slabs of 16 staged through LDS (stored k-major so the inner loop reads float4), the next
 // slab prefetched into registers during the FMAs of the current one.
 #include "kernels.hpp"
+#include "sampling.hpp"
 
 namespace dm {
 namespace {
@@ -18,12 +19,13 @@ constexpr int GK = 16;  // k slab
 
 // MODE 0: argmax keys; MODE 1: debug dump of logits[M, dv1 - dv0]; MODE 2: argmax keys and every scaled
 // logit stored as [position][vocabulary row][path] for the distribution-level rule.
-template <typename T, int MODE>
+// SAMPLE (MODE 0 only): arg max over zscale * logit + Gumbel noise = a draw from Softmax(logit / temperature).
+template <typename T, int MODE, bool SAMPLE>
 __global__ __launch_bounds__(256) void lmhead_generic_kernel(const T* __restrict__ W, const T* __restrict__ A,
                                                              unsigned long long* __restrict__ keys, int64_t M,
                                                              int d, int d_pad, int V, int vtile0,
                                                              float* __restrict__ logits, int dv0, int dv1,
-                                                             float scale, LogitStore store) {
+                                                             float scale, LogitStore store, SampleCfg samp) {
   constexpr bool DUMP = MODE == 1;
   __shared__ __attribute__((aligned(16))) float As[GK][GT + 4];
   __shared__ __attribute__((aligned(16))) float Ws[GK][GT + 4];
@@ -111,10 +113,15 @@ __global__ __launch_bounds__(256) void lmhead_generic_kernel(const T* __restrict
   for (int x = 0; x < 4; ++x) {
     float best = -INFINITY;
     uint32_t bv = 0xFFFFFFFFu;
+    RowRng rng{0u, 0u, 0u, 0u, false};
+    if (SAMPLE) rng = make_row_rng(samp, m0 + ty * 4 + x, M);
+    const bool noisy = SAMPLE && rng.on;
+    float g[4] = {0.f, 0.f, 0.f, 0.f};
+    if (noisy) gumbel4(rng, (uint32_t)(v0 + tx * 4), samp.step, g);
 #pragma unroll
     for (int y = 0; y < 4; ++y) {
       const int v = v0 + tx * 4 + y;
-      const float val = acc[x][y] + 0.0f;  // -0 -> +0
+      const float val = noisy ? fmaf(acc[x][y], samp.zscale, g[y]) : acc[x][y] + 0.0f;  // -0 -> +0
       if (v < V && (bv == 0xFFFFFFFFu || val > best)) {
         best = val;
         bv = (uint32_t)v;
@@ -136,7 +143,7 @@ __global__ __launch_bounds__(256) void lmhead_generic_kernel(const T* __restrict
 
 hipError_t launch_lmhead_generic(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g,
                                  int V, bool is_bf16, float* logits, int v0, int v1, float scale,
-                                 const LogitStore& store, hipStream_t stream) {
+                                 const LogitStore& store, const SampleCfg& samp, hipStream_t stream) {
   const bool dump = logits != nullptr;
   const int tile0 = dump ? v0 / GT : 0;
   const int tile1 = dump ? (v1 + GT - 1) / GT : (V + GT - 1) / GT;
@@ -145,14 +152,18 @@ hipError_t launch_lmhead_generic(const void* W, const void* a_ws, unsigned long 
   if (mtiles > 65535) return hipErrorInvalidValue;
   const dim3 grid((unsigned)(tile1 - tile0), (unsigned)mtiles), block(256);
   const int mode = dump ? 1 : (store.lt != nullptr ? 2 : 0);
-#define DM_GEN(T, MODE)                                                                                  \
-  lmhead_generic_kernel<T, MODE><<<grid, block, 0, stream>>>(static_cast<const T*>(W),                   \
-                                                             static_cast<const T*>(a_ws), keys, g.M, g.d, \
-                                                             g.d_pad, V, tile0, logits, v0, v1, scale, store)
+#define DM_GEN(T, MODE, SAMPLE)                                                                                   \
+  lmhead_generic_kernel<T, MODE, SAMPLE><<<grid, block, 0, stream>>>(static_cast<const T*>(W),                     \
+                                                                     static_cast<const T*>(a_ws), keys, g.M, g.d,  \
+                                                                     g.d_pad, V, tile0, logits, v0, v1, scale,     \
+                                                                     store, samp)
+  const bool sample = mode == 0 && samp.seeds != nullptr;
   if (is_bf16) {
-    if (mode == 1) DM_GEN(uint16_t, 1); else if (mode == 2) DM_GEN(uint16_t, 2); else DM_GEN(uint16_t, 0);
+    if (mode == 1) DM_GEN(uint16_t, 1, false); else if (mode == 2) DM_GEN(uint16_t, 2, false);
+    else if (sample) DM_GEN(uint16_t, 0, true); else DM_GEN(uint16_t, 0, false);
   } else {
-    if (mode == 1) DM_GEN(float, 1); else if (mode == 2) DM_GEN(float, 2); else DM_GEN(float, 0);
+    if (mode == 1) DM_GEN(float, 1, false); else if (mode == 2) DM_GEN(float, 2, false);
+    else if (sample) DM_GEN(float, 0, true); else DM_GEN(float, 0, false);
   }
 #undef DM_GEN
   return hipGetLastError();

@@ -39,6 +39,7 @@
 // bytes; the slab pipeline runs across tile borders.
 #include "kernels.hpp"
 #include "mfma_common.hpp"
+#include "sampling.hpp"
 #include "vote_body.hpp"
 
 namespace dm {
@@ -63,14 +64,16 @@ __host__ __device__ constexpr int lds_bytes(int MT) { return NS * slab_bytes(MT)
 // MODE 1: debug dump of scaled logits for vocabulary rows [dv0, dv1) into logits[M, dv1 - dv0].
 // MODE 2: argmax keys AND every scaled logit stored for the distribution-level rule, in the
 //         layout [position][vocabulary row][path] (store.lt, see LogitStore).
-template <int MT, int MODE>
+// SAMPLE (MODE 0 only): the per-row arg max runs over zscale * logit + Gumbel noise, i.e. the path token
+//         is drawn from Softmax(logit / temperature) instead of being the arg max.
+template <int MT, int MODE, bool SAMPLE>
 __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* __restrict__ W,
                                                                  const __bf16* __restrict__ A_sw,
                                                                  unsigned long long* __restrict__ keys, int d,
                                                                  int64_t M, int mt_total, int v_lo, int v_hi,
                                                                  int rows_per_wg, float* __restrict__ logits,
                                                                  int dv0, int dv1, float scale, LogitStore store,
-                                                                 VoteFuse fuse) {
+                                                                 VoteFuse fuse, SampleCfg samp) {
   constexpr bool DUMP = MODE == 1;
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   constexpr int SLAB = slab_bytes(MT);
@@ -182,6 +185,12 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
       }
     }
 
+    RowRng rng[MT];
+    if (SAMPLE) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) rng[mt] = make_row_rng(samp, (int64_t)(mblk * MT + mt) * 32 + i32, M);
+    }
+
     for (int q = 0; q < total; ++q) {
       DM_BARRIER();
       const unsigned char* stage = lds + (q % NS) * SLAB;
@@ -249,14 +258,21 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
 #pragma unroll
         for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {  // ascending v for this lane: strict > keeps the smallest index
-            const int v = v0 + 64 * wave + 32 * vt + 8 * (r >> 2) + 4 * hb + (r & 3);
-            const float val = acc[mt][vt][r] + 0.0f;
-            if (v < row_end && (bv == 0xFFFFFFFFu || val > best)) {
-              best = val;
-              bv = (uint32_t)v;
+          for (int rq = 0; rq < 4; ++rq) {
+            float g[4] = {0.f, 0.f, 0.f, 0.f};
+            const bool noisy = SAMPLE && rng[mt].on;
+            if (noisy) gumbel4(rng[mt], (uint32_t)(v0 + 64 * wave + 32 * vt + 8 * rq + 4 * hb), samp.step, g);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {  // ascending v for this lane: strict > keeps the smallest index
+              const int r = 4 * rq + e;
+              const int v = v0 + 64 * wave + 32 * vt + 8 * rq + 4 * hb + e;
+              const float val = noisy ? fmaf(acc[mt][vt][r], samp.zscale, g[e]) : acc[mt][vt][r] + 0.0f;
+              if (v < row_end && (bv == 0xFFFFFFFFu || val > best)) {
+                best = val;
+                bv = (uint32_t)v;
+              }
+              acc[mt][vt][r] = 0.f;
             }
-            acc[mt][vt][r] = 0.f;
           }
         unsigned long long key = (bv == 0xFFFFFFFFu) ? 0ull : pack_key(best, bv);
         const unsigned long long other = __shfl_xor(key, 32, 64);
@@ -314,7 +330,7 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
 template <int MT>
 hipError_t run(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V, int num_cu,
                float* logits, int v0, int v1, float scale, const LogitStore& store, const VoteFuse& fuse,
-               hipStream_t stream) {
+               const SampleCfg& samp, hipStream_t stream) {
   const bool dump = logits != nullptr;
   const int v_lo = dump ? v0 : 0;
   const int v_hi = dump ? v1 : V;
@@ -326,25 +342,28 @@ hipError_t run(const void* W, const void* a_ws, unsigned long long* keys, const 
   if (cap < 1) cap = 1;
   int gx = (v_hi - v_lo + BN / 2 - 1) / (BN / 2);
   if (gx > cap) gx = cap;
-  const int rows_per_wg = (v_hi - v_lo + gx - 1) / gx;
+  int rows_per_wg = (v_hi - v_lo + gx - 1) / gx;
+  rows_per_wg = (rows_per_wg + 3) & ~3;  // ranges start at multiples of 4: one Philox call serves 4 rows when sampling
   const dim3 grid((unsigned)gx, (unsigned)mblocks), block(THREADS);
-#define DM_LAUNCH(MODE)                                                                                         \
-  lmhead_mfma_kernel<MT, MODE><<<grid, block, lds_bytes(MT), stream>>>(                                          \
+#define DM_LAUNCH(MODE, SAMPLE)                                                                                 \
+  lmhead_mfma_kernel<MT, MODE, SAMPLE><<<grid, block, lds_bytes(MT), stream>>>(                                  \
       static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo, v_hi,    \
-      rows_per_wg, logits, v0, v1, scale, store, fuse)
+      rows_per_wg, logits, v0, v1, scale, store, fuse, samp)
   if (dump)
-    DM_LAUNCH(1);
+    DM_LAUNCH(1, false);
   else if (store.lt != nullptr)
-    DM_LAUNCH(2);
+    DM_LAUNCH(2, false);
+  else if (samp.seeds != nullptr)
+    DM_LAUNCH(0, true);
   else
-    DM_LAUNCH(0);
+    DM_LAUNCH(0, false);
 #undef DM_LAUNCH
   return hipGetLastError();
 }
 
-template <int MT, int MODE>
+template <int MT, int MODE, bool SAMPLE>
 hipError_t raise_lds() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_mfma_kernel<MT, MODE>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_mfma_kernel<MT, MODE, SAMPLE>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(MT));
 }
 
@@ -353,8 +372,8 @@ hipError_t raise_lds() {
 hipError_t prepare_lmhead_mfma() {
   hipError_t e;
 #define DM_RAISE(MT)                                                                                  \
-  if ((e = raise_lds<MT, 0>()) != hipSuccess || (e = raise_lds<MT, 1>()) != hipSuccess ||             \
-      (e = raise_lds<MT, 2>()) != hipSuccess)                                                         \
+  if ((e = raise_lds<MT, 0, false>()) != hipSuccess || (e = raise_lds<MT, 0, true>()) != hipSuccess || \
+      (e = raise_lds<MT, 1, false>()) != hipSuccess || (e = raise_lds<MT, 2, false>()) != hipSuccess)  \
     return e
   DM_RAISE(1);
   DM_RAISE(2);
@@ -366,7 +385,7 @@ hipError_t prepare_lmhead_mfma() {
 
 hipError_t launch_lmhead_mfma(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V,
                               int num_cu, float* logits, int v0, int v1, float scale, const LogitStore& store,
-                              const VoteFuse* fuse_in, bool* fused, hipStream_t stream) {
+                              const SampleCfg& samp, const VoteFuse* fuse_in, bool* fused, hipStream_t stream) {
   // the acceptance step rides along when this is the plain verify path and its scratch fits the slabs
   VoteFuse fuse{};
   const bool can_fuse = fuse_in != nullptr && fuse_in->counter != nullptr && logits == nullptr &&
@@ -378,12 +397,12 @@ hipError_t launch_lmhead_mfma(const void* W, const void* a_ws, unsigned long lon
   const int mt_total = (int)(g.M_pad >> 5);
   if (mt_total >= 4) {
     if (mt_total % 4 != 0) return hipErrorInvalidValue;
-    return run<4>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, stream);
+    return run<4>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, samp, stream);
   }
   switch (mt_total) {
-    case 1: return run<1>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, stream);
-    case 2: return run<2>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, stream);
-    case 3: return run<3>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, stream);
+    case 1: return run<1>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, samp, stream);
+    case 2: return run<2>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, samp, stream);
+    case 3: return run<3>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, samp, stream);
     default: return hipErrorInvalidValue;
   }
 }

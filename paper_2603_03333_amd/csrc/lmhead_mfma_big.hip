@@ -25,6 +25,7 @@
 // across the chip W streams from HBM once per sweep of up to 16 row tiles.
 #include "kernels.hpp"
 #include "mfma_common.hpp"
+#include "sampling.hpp"
 
 namespace dm {
 namespace {
@@ -90,14 +91,15 @@ __device__ __forceinline__ bool tile_of(const TileWalk& w, const TilePos& p, int
 
 // MODE 0: argmax keys only; MODE 1: debug dump of logits[M, dv1 - dv0]; MODE 2: argmax keys and every
 // scaled logit stored in the layout [position][vocabulary row][path] for the distribution-level rule.
-template <int BK, int MODE>
+// SAMPLE (MODE 0 only): arg max over zscale * logit + Gumbel noise = a draw from Softmax(logit / temperature).
+template <int BK, int MODE, bool SAMPLE>
 __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf16* __restrict__ W,
                                                                      const __bf16* __restrict__ A_sw,
                                                                      unsigned long long* __restrict__ keys, int d,
                                                                      int64_t M, int mt_total, int v_lo, int v_hi,
                                                                      TileWalk walk, float* __restrict__ logits,
                                                                      int dv0, int dv1, float scale,
-                                                                     LogitStore store) {
+                                                                     LogitStore store, SampleCfg samp) {
   using C = Cfg<BK>;
   constexpr bool DUMP = MODE == 1;
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
@@ -292,17 +294,26 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
     for (int mt = 0; mt < 4; ++mt) {
       float best = -INFINITY;
       uint32_t bv = 0xFFFFFFFFu;
+      RowRng rng{0u, 0u, 0u, 0u, false};
+      if (SAMPLE) rng = make_row_rng(samp, (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32, M);
+      const bool noisy = SAMPLE && rng.on;
 #pragma unroll
       for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {  // ascending v for this lane: strict > keeps the smallest index
-          const int v = v0 + 64 * wv + 32 * vt + 8 * (r >> 2) + 4 * hb + (r & 3);
-          const float val = acc[mt][vt][r] + 0.0f;
-          if (v < v_hi && (bv == 0xFFFFFFFFu || val > best)) {
-            best = val;
-            bv = (uint32_t)v;
+        for (int rq = 0; rq < 4; ++rq) {
+          float g[4] = {0.f, 0.f, 0.f, 0.f};
+          if (noisy) gumbel4(rng, (uint32_t)(v0 + 64 * wv + 32 * vt + 8 * rq + 4 * hb), samp.step, g);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {  // ascending v for this lane: strict > keeps the smallest index
+            const int r = 4 * rq + e;
+            const int v = v0 + 64 * wv + 32 * vt + 8 * rq + 4 * hb + e;
+            const float val = noisy ? fmaf(acc[mt][vt][r], samp.zscale, g[e]) : acc[mt][vt][r] + 0.0f;
+            if (v < v_hi && (bv == 0xFFFFFFFFu || val > best)) {
+              best = val;
+              bv = (uint32_t)v;
+            }
+            acc[mt][vt][r] = 0.f;
           }
-          acc[mt][vt][r] = 0.f;
         }
       unsigned long long key = (bv == 0xFFFFFFFFu) ? 0ull : pack_key(best, bv);
       const unsigned long long other = __shfl_xor(key, 32, 64);
@@ -359,7 +370,8 @@ TileWalk make_walk(int NV, int NMB, int G) {
 
 template <int BK>
 hipError_t run_big(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V, int num_cu,
-                   float* logits, int v0, int v1, float scale, const LogitStore& store, hipStream_t stream) {
+                   float* logits, int v0, int v1, float scale, const LogitStore& store, const SampleCfg& samp,
+                   hipStream_t stream) {
   const bool dump = logits != nullptr;
   const int v_lo = dump ? v0 : 0;
   const int v_hi = dump ? v1 : V;
@@ -372,25 +384,27 @@ hipError_t run_big(const void* W, const void* a_ws, unsigned long long* keys, co
   const TileWalk walk = make_walk(NV, NMB, G);
   const dim3 grid((unsigned)G), block(THREADS);
   const int mt_total = (int)(g.M_pad >> 5);
-#define DM_LAUNCH(MODE)                                                                                            \
-  lmhead_mfma_big_kernel<BK, MODE><<<grid, block, Cfg<BK>::LDS_BYTES, stream>>>(                                    \
+#define DM_LAUNCH(MODE, SAMPLE)                                                                                    \
+  lmhead_mfma_big_kernel<BK, MODE, SAMPLE><<<grid, block, Cfg<BK>::LDS_BYTES, stream>>>(                            \
       static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo, v_hi, walk, \
-      logits, v0, v1, scale, store)
+      logits, v0, v1, scale, store, samp)
   if (dump)
-    DM_LAUNCH(1);
+    DM_LAUNCH(1, false);
   else if (store.lt != nullptr)
-    DM_LAUNCH(2);
+    DM_LAUNCH(2, false);
+  else if (samp.seeds != nullptr)
+    DM_LAUNCH(0, true);
   else
-    DM_LAUNCH(0);
+    DM_LAUNCH(0, false);
 #undef DM_LAUNCH
   return hipGetLastError();
 }
 
 constexpr int kBigBK = 64;
 
-template <int MODE>
+template <int MODE, bool SAMPLE>
 hipError_t raise_lds_big() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_mfma_big_kernel<kBigBK, MODE>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_mfma_big_kernel<kBigBK, MODE, SAMPLE>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, Cfg<kBigBK>::LDS_BYTES);
 }
 
@@ -398,16 +412,17 @@ hipError_t raise_lds_big() {
 
 hipError_t prepare_lmhead_mfma_big() {
   hipError_t e;
-  if ((e = raise_lds_big<0>()) != hipSuccess) return e;
-  if ((e = raise_lds_big<1>()) != hipSuccess) return e;
-  return raise_lds_big<2>();
+  if ((e = raise_lds_big<0, false>()) != hipSuccess) return e;
+  if ((e = raise_lds_big<0, true>()) != hipSuccess) return e;
+  if ((e = raise_lds_big<1, false>()) != hipSuccess) return e;
+  return raise_lds_big<2, false>();
 }
 
 hipError_t launch_lmhead_mfma_big(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V,
                                   int num_cu, float* logits, int v0, int v1, float scale, const LogitStore& store,
-                                  hipStream_t stream) {
+                                  const SampleCfg& samp, hipStream_t stream) {
   if (g.M_pad % BM != 0) return hipErrorInvalidValue;
-  return run_big<kBigBK>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, stream);
+  return run_big<kBigBK>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, samp, stream);
 }
 
 }  // namespace dm

@@ -49,4 +49,30 @@ __device__ __forceinline__ uint32_t keep_bits8(uint32_t o, uint32_t t, uint32_t 
   return bits;
 }
 
+// ---- sampled path tokens: Gumbel-max draw from Softmax(l / tau) ------------------------------
+// The paper remarks that a path's token may be selected by sampling instead of the arg max.
+// y = argmax_v (l[v] / tau + g[v]) with g = -ln(-ln u) is a draw from Softmax(l / tau); u[v] comes
+// from a Philox stream of its own: counter (v >> 2, row, path, step), key = sequence seed +
+// 0x9E3779B97F4A7C15 (mod 2^64), word v & 3, u = ((w >> 9) + 1/2) 2^-23 (exact in float, never 0 or 1).
+constexpr uint64_t kSampleKeyOffset = 0x9E3779B97F4A7C15ull;
+
+// g = -ln(-ln u).  The largest g come from u next to 1, where -ln u has to be accurate relative to
+// its own size: there it is the series of -ln(1 - c) in c = 1 - u (exact in float); elsewhere the
+// hardware logarithm (base 2, 1 ulp) is enough.
+__device__ __forceinline__ float gumbel_from_word(uint32_t w) {
+  const float k = (float)(w >> 9);
+  const float u = (k + 0.5f) * 1.1920928955078125e-07f;             // 2^-23
+  const float c = (8388607.5f - k) * 1.1920928955078125e-07f;       // 1 - u, exact
+  const float series = c * (1.0f + c * (0.5f + c * (0.333333343f + c * 0.25f)));
+  const float direct = -0.693147180559945309f * __builtin_amdgcn_logf(u);
+  const float e = (c <= 0.015625f) ? series : direct;               // -ln u
+  return -0.693147180559945309f * __builtin_amdgcn_logf(e);
+}
+
+// Which stream a masked row draws from.
+struct RowRng {
+  uint32_t k0, k1, t, i;
+  bool on;   // false: padding row, or the clean last path (plain arg max)
+};
+
 }  // namespace dm

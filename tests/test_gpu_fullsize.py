@@ -176,3 +176,38 @@ def test_head8b_js_full():
 
 def test_batched_js_sampled():
     _run_config_js("batched", sample=3)
+
+
+# ------------------------------------------------------------------ sampled path tokens at full size
+def test_head8b_sampled_tokens_on_sampled_rows():
+    wl = wk.CONFIGS["head8b"]
+    tau = 0.8
+    W, h, seeds = wk.make_weight(wl), wk.make_hidden(wl), wk.make_seeds(wl)
+    draft = wk.make_draft_ids(wl, None)
+    r = Runner(wl.rows, wl.d, wl.V)
+    try:
+        hd, Wd = to_device(h, wl.dtype), to_device(W, wl.dtype)
+        res = r.verify(wl, hd, Wd, draft, seeds, flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=tau)
+        res2 = r.verify(wl, hd, Wd, draft, seeds, flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=tau)
+        assert np.array_equal(res["path_ids"], res2["path_ids"])
+        del hd, Wd
+    finally:
+        r.close()
+    torch.cuda.empty_cache()
+    W64 = W.astype(np.float64)
+    near = flips = 0
+    for t in (0, 5):                                    # two positions, all 16 paths each, full vocabulary
+        Hm = np.stack([orc.masked_state(h[0, t], orc.keep_mask(int(seeds[0]), 0, t, i, wl.d, wl.p), wl.p)
+                       for i in range(wl.K)])
+        L = W64 @ Hm.T
+        for i in range(wl.K):
+            g = orc.gumbel_noise(orc.sampling_uniforms(int(seeds[0]), 0, t, i, wl.V))
+            y, gap = orc.sampled_token(L[:, i], tau, g)
+            near += gap < 1.25e-3
+            if res["path_ids"][0, t, i] != y:
+                flips += 1
+                assert gap < 1.25e-3, (t, i, gap)
+    print(f"[head8b/sampled] rows=32 near-tie={near} flips={flips}", flush=True)
+    exp = orc.acceptance_from_path_ids(res["path_ids"], draft, orc.RULE_ANY)
+    for k in ("vote_ids", "vote_cnt", "hit", "accept_len"):
+        assert np.array_equal(res[k], exp[k]), k

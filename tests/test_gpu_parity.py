@@ -435,3 +435,59 @@ def test_planted_dominant_tokens(runner):
         _check_against_oracle(res, ref, draft, rule, label=f"planted rule={rule}")
         assert (res["vote_cnt"] == wl.K).mean() > 0.9
         assert res["accept_len"].tolist() == [7, 3, 7, 7]
+
+
+# ------------------------------------------------------------------ sampled path tokens
+@pytest.mark.parametrize("d,V,B,T,K,dtype,tau", [
+    (256, 3000, 1, 8, 16, "bf16", 1.0),    # W-streaming kernel, ragged last vocabulary tile
+    (256, 4096, 2, 6, 16, "bf16", 0.7),    # 256 x 256 tiles
+    (100, 130, 2, 3, 5, "f32", 1.5),       # generic kernel
+    (128, 777, 1, 3, 16, "bf16", 0.25),    # a sharp temperature
+])
+def test_sampled_path_tokens(runner, d, V, B, T, K, dtype, tau):
+    """Path tokens drawn from Softmax(l / tau) by the Gumbel-max construction with the counter-based
+    stream: equal to the oracle's draws except where the oracle's perturbed top-2 gap is inside the
+    floating-point band (the logit error 1e-5 is divided by tau, so the band is 1e-3 * max(1, 1/tau))."""
+    wl, W, h, seeds, draft = _problem("samp", d, V, dtype, B, T, K, 0.2, seed=d + V + K, bonus=True)
+    hd, Wd = to_device(h, dtype), to_device(W, dtype)
+    flag = dmb.DM_FLAG_SAMPLE_PATHS
+    tol = 1e-3 * max(1.0, 1.0 / tau)
+    for rule, step in ((orc.RULE_ANY, 0), (orc.RULE_MAJORITY, 5)):
+        ref = orc.verify(h, W, draft, seeds, K, wl.p, rule=rule, step=step, temperature=tau)
+        res = runner.verify(wl, hd, Wd, draft, seeds, rule=rule, step=step, flags=flag, temperature=tau)
+        mism = res["path_ids"] != ref["path_ids"]
+        assert not (mism & (ref["gap"] >= tol)).any(), "sampled token differs at a row with a clear winner"
+        print(f"[sampled {dtype} M={B*T*K} tau={tau}] near-tie rows={int((ref['gap'] < tol).sum())} flips={int(mism.sum())}", flush=True)
+        exp = ref if not mism.any() else orc.acceptance_from_path_ids(res["path_ids"], draft, rule)
+        for k in ("vote_ids", "vote_cnt", "hit", "accept_mask", "accept_len", "best_node"):
+            assert np.array_equal(res[k], exp[k]), k
+    plain = runner.verify(wl, hd, Wd, draft, seeds)
+    assert (plain["path_ids"] != res["path_ids"]).any()            # it does sample
+    again = runner.verify(wl, hd, Wd, draft, seeds, rule=orc.RULE_MAJORITY, step=5, flags=flag, temperature=tau)
+    assert np.array_equal(again["path_ids"], res["path_ids"])       # and is a pure function of its key
+    # with a clean last path that path stays the greedy token
+    both = runner.verify(wl, hd, Wd, draft, seeds, flags=flag | dmb.DM_FLAG_CLEAN_LAST_PATH, temperature=tau)
+    assert np.array_equal(both["path_ids"][:, :, -1], orc.greedy_ids(h, W))
+    refc = orc.verify(h, W, draft, seeds, K, wl.p, temperature=tau, clean_last_path=True)
+    ok = refc["gap"] >= tol
+    assert np.array_equal(both["path_ids"][ok], refc["path_ids"][ok])
+
+
+def test_sampling_frequencies_on_the_gpu(runner):
+    """Many steps on one small row: the GPU's own draws follow Softmax(l / tau) (chi-square against the
+    distribution computed from the kernel's debug logits)."""
+    import scipy.special
+    import scipy.stats
+    wl, W, h, seeds, draft = _problem("freq", 64, 12, "bf16", 1, 1, 64, 0.0, seed=17)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    tau = 0.05                                     # logits of this problem are small: sharpen them
+    logits = runner.logits(wl, hd, Wd, seeds, 0, wl.V)[0].astype(np.float64)      # p = 0: every path alike
+    want = scipy.special.softmax(logits / tau)
+    counts = np.zeros(wl.V)
+    for step in range(150):
+        ids = runner.verify(wl, hd, Wd, draft, seeds, step=step, flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=tau)["path_ids"]
+        counts += np.bincount(ids.reshape(-1), minlength=wl.V)
+    keep = want * counts.sum() >= 5                 # chi-square needs expected counts of a few at least
+    obs, expct = counts[keep], want[keep] * counts.sum()
+    pval = scipy.stats.chisquare(obs, expct * obs.sum() / expct.sum())[1]
+    assert pval > 1e-3, (counts, want * counts.sum())
