@@ -1,0 +1,103 @@
+"""Seeded random shapes and option combinations against the oracle: ragged vocabulary tails, row
+counts around the tile edges of every kernel, both storage types, every token-level option.  Each
+case is small enough for the oracle to run in well under a second."""
+import numpy as np
+import pytest
+
+from oracle import dropmatch_oracle as orc
+from paper_2603_03333_amd import workloads as wk
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("no GPU", allow_module_level=True)
+
+from paper_2603_03333_amd import binding as dmb  # noqa: E402
+from gpu_harness import Runner, compare_js, compare_path_ids, to_device  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def runner():
+    r = Runner(max_rows=1024, max_d=512, max_V=4096)
+    r.reserve_js(max_positions=64, max_K=64)
+    yield r
+    r.close()
+
+
+def _draw(case):
+    rng = np.random.default_rng(7000 + case)
+    bf16 = rng.random() < 0.75
+    d = int(rng.choice([64, 128, 192, 256, 512])) if (bf16 and rng.random() < 0.8) else int(rng.integers(5, 200))
+    V = int(rng.choice([1, 7, 255, 256, 257, 511, 1000, 2049, 4096]) if rng.random() < 0.5 else rng.integers(2, 3000))
+    K = int(rng.choice([1, 2, 3, 5, 8, 16, 17, 32, 40]))
+    T = int(rng.integers(1, 10))
+    B = int(rng.integers(1, 5))
+    while B * T * K > 1024:
+        T = max(1, T - 1)
+        B = max(1, B - 1)
+    p = float(rng.choice([0.0, 0.05, 0.1, 0.3, 0.5, 0.9]))
+    return rng, ("bf16" if bf16 else "f32"), d, V, B, T, K, p
+
+
+@pytest.mark.parametrize("case", range(48))
+def test_random_token_level_case(runner, case):
+    rng, dtype, d, V, B, T, K, p = _draw(case)
+    wl = wk.Workload(f"rand{case}", d=d, V=V, dtype=dtype, B=B, T=T, K=K, p=p, bonus=bool(rng.integers(0, 2)),
+                     data_seed=9000 + case)
+    W, h = wk.make_weight(wl, sigma=0.1), wk.make_hidden(wl)
+    seeds = rng.integers(0, 2 ** 63, size=B, dtype=np.uint64)
+    step = int(rng.integers(0, 2 ** 32))
+    rule = int(rng.integers(0, 2))
+    share = bool(rng.integers(0, 2))
+    clean = K >= 2 and rng.random() < 0.3
+    tree = T >= 3 and rng.random() < 0.3
+    tau = float(rng.choice([0.5, 1.0, 2.0])) if rng.random() < 0.3 else None
+    greedy = orc.greedy_ids(h, W)
+    parent = None
+    if tree:
+        parent = wk.make_tree_parents(wl.with_(tree=True), max_depth=4, max_branch=3)
+        draft = wk.make_tree_draft_ids(wl, parent, greedy)
+    else:
+        draft = wk.make_draft_ids(wl, greedy)
+    flags = (dmb.DM_FLAG_SHARE_MASK_ACROSS_POS if share else 0) | (dmb.DM_FLAG_CLEAN_LAST_PATH if clean else 0) | \
+            (dmb.DM_FLAG_SAMPLE_PATHS if tau else 0) | (dmb.DM_FLAG_SEPARATE_VOTE if rng.random() < 0.3 else 0) | \
+            (dmb.DM_FLAG_FORCE_GENERIC if rng.random() < 0.2 else 0)
+    ref = orc.verify(h, W, draft, seeds, K, p, step=step, rule=rule, share_mask_across_pos=share, parent=parent,
+                     clean_last_path=clean, temperature=tau)
+    res = runner.verify(wl, to_device(h, dtype), to_device(W, dtype), draft, seeds, step=step, rule=rule, flags=flags,
+                        parent=parent, temperature=tau or 0.0)
+    tol = 1e-3 * (max(1.0, 1.0 / tau) if tau else 1.0)
+    nflip, nnear = compare_path_ids(res["path_ids"], ref["path_ids"], ref["gap"], tol=tol)
+    KU = K - 1 if clean else K
+    exp = ref if nflip == 0 else orc.acceptance_from_path_ids(res["path_ids"][:, :, :KU], draft, rule, parent)
+    for k in ("vote_ids", "vote_cnt", "hit", "accept_mask", "accept_len", "best_node"):
+        assert np.array_equal(res[k], exp[k]), f"case {case} ({dtype} d={d} V={V} B={B} T={T} K={K} p={p} flags={flags}): {k}"
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_random_js_case(runner, case):
+    rng, dtype, d, V, B, T, K, p = _draw(100 + case)
+    V = max(V, 2)
+    while B * T > 64:
+        B = max(1, B - 1)
+    p = min(p, 0.5)
+    wl = wk.Workload(f"randjs{case}", d=d, V=V, dtype=dtype, B=B, T=T, K=K, p=p, bonus=bool(rng.integers(0, 2)),
+                     data_seed=9500 + case)
+    W, h = wk.make_weight(wl, sigma=0.1), wk.make_hidden(wl)
+    seeds = rng.integers(0, 2 ** 63, size=B, dtype=np.uint64)
+    clean = K >= 2 and rng.random() < 0.3
+    rule = int(rng.integers(2, 4))
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    clean_logits = np.einsum("vd,btd->btv", W.astype(np.float64), h.astype(np.float64)).astype(np.float32)
+    probs = wk.make_draft_probs(wl, clean_logits, topk=int(rng.choice([0, 0, 5])) if V > 8 else 0)
+    flags = dmb.DM_FLAG_CLEAN_LAST_PATH if clean else 0
+    ref = orc.verify_js(h, W, draft, probs, seeds, K, p, rule=rule, clean_last_path=clean)
+    res = runner.verify_js(wl, to_device(h, dtype), to_device(W, dtype), draft, probs, seeds, rule=rule, flags=flags)
+    nflip, _ = compare_path_ids(res["path_ids"], ref["path_ids"], ref["gap"])
+    n_tie, gpu_js = compare_js(res, ref, draft, rule == 2, nflip, f"rand js {case} {dtype} d={d} V={V} B={B} T={T} K={K}")
+    KU = K - 1 if clean else K
+    votes = orc.acceptance_from_path_ids(res["path_ids"][:, :, :KU], draft, orc.RULE_MAJORITY)
+    want = gpu_js | (votes["hit"].astype(bool) if rule == 3 else False)
+    assert np.array_equal(res["hit"].astype(bool), want)
+    assert np.array_equal(res["accept_len"], orc.acceptance_from_hits(want)["accept_len"])
