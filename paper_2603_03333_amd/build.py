@@ -34,9 +34,7 @@ def is_stale() -> bool:
     return any(os.path.getmtime(p) > t for p in deps)
 
 
-def build(verbose: bool = True) -> str:
-    """Compile every HIP source into libdropmatch.so (always recompiles)."""
-    cmd = [hipcc()] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB + ".tmp"]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -45,6 +43,22 @@ def build(verbose: bool = True) -> str:
         print("\n".join(lines), flush=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout)
+
+
+def build(verbose: bool = True) -> str:
+    """Compile every HIP source for gfx950 (one hipcc per file, in parallel) and link
+    libdropmatch.so.  Always recompiles."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    cc = hipcc()
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+    objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
+    jobs = [[cc] + compile_flags + ["-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+    with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 1, 8)) as pool:
+        list(pool.map(lambda cmd: _run(cmd, verbose), jobs))
+    _run([cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc"] + objs + ["-o", LIB + ".tmp"], verbose)
     os.replace(LIB + ".tmp", LIB)
     return LIB
 
