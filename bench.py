@@ -87,7 +87,8 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); "
-              "the verify step would shard by vocabulary rows or by sequences, see DESIGN.md", file=sys.stderr)
+              "across GPUs the step would shard by vocabulary rows (one small max-reduce of the argmax keys) "
+              "or by sequences (no exchange)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
