@@ -197,6 +197,12 @@ def main():
     for _ in range(args.warmup):
         timed()
     torch.cuda.synchronize()
+    # ---- the timed region.  The library brackets the contraction kernel of (up to 512 of) these very
+    # calls with two HIP events on the launch stream; a captured graph holds no events, so with
+    # --graph the kernel is timed in the pass after the region instead.
+    live = not args.graph
+    if live:
+        dmb.dm_set_profiling(ctx, 2)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         timed()
@@ -204,14 +210,22 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
     positions = wl.B * wl.T
+    n_live, ms_lm_live = 0, 0.0
+    if live:
+        n_live, stages = dmb.dm_get_profile_stages(ctx)
+        ms_lm_live = stages[1]
+        dmb.dm_set_profiling(ctx, False)
 
-    # ---- per-kernel durations from HIP events recorded by the library on the launch stream
+    # ---- the other kernels: a second pass with events around every kernel
     nprof = min(args.steps, 512)
     dmb.dm_set_profiling(ctx, True)
     for _ in range(nprof):
         step()
     n_calls, (ms_mask, ms_lm, ms_js1, ms_js2, ms_vote) = dmb.dm_get_profile_stages(ctx)
     dmb.dm_set_profiling(ctx, False)
+    ms_lm_pass2 = ms_lm
+    if live:
+        ms_lm, n_calls = ms_lm_live, n_live
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -251,6 +265,7 @@ def main():
                              "js_stats_achieved": pass_bytes / (ms_js1 * 1e-3) / 1e9,
                              "js_terms_achieved": (pass_bytes + wl.B * wl.T * wl.V * 4) / (ms_js2 * 1e-3) / 1e9}
     roof["events_over_calls"] = n_calls
+    roof["kernel_ms_second_pass"] = ms_lm_pass2
 
     result = {
         "metric": "MC-dropout LM-head verify: positions/s; HBM GB/s or MFMA % of peak",

@@ -231,7 +231,9 @@ dm_status dm_debug_logits(dm_ctx* ctx, const dm_params* prm, const void* h, cons
  * number of recorded calls and the mean duration of the three kernels of the token-level path
  * in milliseconds (any output pointer may be NULL); dm_get_profile_stages returns all five
  * stage means in ms[0..4] = mask rows, LM head, JS pass 1, JS pass 2, vote/accept (the JS
- * stages are 0 for dropmatch_verify).  dm_set_profiling(ctx, 0) stops recording and forgets
+ * stages are 0 for dropmatch_verify).  dm_set_profiling(ctx, 2) records only the two events around
+ * the LM-head contraction kernel (the lightest way to time the dominant kernel inside a timed
+ * loop; the other stage means then read 0).  dm_set_profiling(ctx, 0) stops recording and forgets
  * the samples. */
 #define DM_PROFILE_MAX_CALLS 512
 dm_status dm_set_profiling(dm_ctx* ctx, int32_t enabled);

@@ -174,8 +174,9 @@ def dm_debug_logits(ctx, prm: dm_params, h, W, v0: int, v1: int, logits, stream=
     _check(ctx, st)
 
 
-def dm_set_profiling(ctx, enabled: bool) -> None:
-    _check(ctx, load_library().dm_set_profiling(ctx, 1 if enabled else 0))
+def dm_set_profiling(ctx, enabled) -> None:
+    """False/0: off; True/1: events around every kernel; 2: only around the contraction kernel."""
+    _check(ctx, load_library().dm_set_profiling(ctx, int(enabled)))
 
 
 def dm_get_profile(ctx):

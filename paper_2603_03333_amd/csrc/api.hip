@@ -149,7 +149,8 @@ dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g,
   store.K = p->K;  // the debug dump needs K and the clean-path flag even when nothing is stored
   store.clean_last = g.clean_last;
   const bool bf16 = p->dtype == DM_BF16;
-  if (ev) (void)hipEventRecord(ev[0], s);
+  const bool all_stages = ctx->prof_enabled == 1;  // 2: only the contraction kernel is bracketed
+  if (ev && all_stages) (void)hipEventRecord(ev[0], s);
   const bool sample = (p->flags & DM_FLAG_SAMPLE_PATHS) && logits == nullptr;
   hipError_t e = dm::launch_mask_rows(h, ctx->a_ws, ctx->keys, p->seeds, g, bf16, mfma,
                                       sample ? ctx->seeds_dev : nullptr, s);
@@ -219,6 +220,7 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
 
   hipEvent_t* ev = nullptr;
   if (ctx->prof_enabled && ctx->ev && ctx->prof_calls < DM_PROFILE_MAX_CALLS) ev = ctx->ev + kEv * ctx->prof_calls;
+  const bool all_stages = ctx->prof_enabled == 1;
   const int Kv = g.clean_last ? prm->K - 1 : prm->K;
   dm::VoteOut out{accept_len, best_node, accept_mask, hit, path_ids, vote_ids, vote_cnt, js_draft, js_heads};
   // token-level rules on the W-streaming kernel: the acceptance step runs as the tail of that launch
@@ -233,11 +235,11 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
     const float scale = (float)(1.0 / (1.0 - (double)prm->p));
     e = dm::launch_js_stats(ctx->lt, ctx->keys, ctx->part_a, jg, scale, s);
     if (e != hipSuccess) return fail_hip(ctx, "js_stats launch", e);
-    if (ev) (void)hipEventRecord(ev[3], s);
+    if (ev && all_stages) (void)hipEventRecord(ev[3], s);
     e = dm::launch_js_terms(ctx->lt, ctx->keys, ctx->part_a, draft_probs, draft_ids, ctx->part_b, jg, scale, s);
     if (e != hipSuccess) return fail_hip(ctx, "js_terms launch", e);
-    if (ev) (void)hipEventRecord(ev[4], s);
-  } else if (ev) {
+    if (ev && all_stages) (void)hipEventRecord(ev[4], s);
+  } else if (ev && all_stages) {
     (void)hipEventRecord(ev[3], s);
     (void)hipEventRecord(ev[4], s);
   }
@@ -247,7 +249,7 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
     if (e != hipSuccess) return fail_hip(ctx, "vote_accept launch", e);
   }
   if (ev) {
-    (void)hipEventRecord(ev[5], s);
+    if (all_stages) (void)hipEventRecord(ev[5], s);
     ++ctx->prof_calls;
   }
   return DM_OK;
@@ -411,7 +413,7 @@ dm_status dm_set_profiling(dm_ctx* ctx, int32_t enabled) {
       }
     }
   }
-  ctx->prof_enabled = 1;
+  ctx->prof_enabled = enabled == 2 ? 2 : 1;
   return DM_OK;
 }
 
@@ -422,10 +424,11 @@ dm_status dm_get_profile_stages(dm_ctx* ctx, int32_t* n_calls, float* ms /* [5] 
   const int n = ctx->prof_calls;
   double sum[kEv - 1] = {0, 0, 0, 0, 0};
   if (n > 0) {
-    hipError_t e = hipEventSynchronize(ctx->ev[kEv * (n - 1) + kEv - 1]);
+    const bool light = ctx->prof_enabled == 2;  // only events 1 and 2 of every call exist
+    hipError_t e = hipEventSynchronize(ctx->ev[kEv * (n - 1) + (light ? 2 : kEv - 1)]);
     if (e != hipSuccess) return fail_hip(ctx, "hipEventSynchronize", e);
     for (int c = 0; c < n; ++c)
-      for (int k = 0; k < kEv - 1; ++k) {
+      for (int k = light ? 1 : 0; k < (light ? 2 : kEv - 1); ++k) {
         float t = 0.f;
         e = hipEventElapsedTime(&t, ctx->ev[kEv * c + k], ctx->ev[kEv * c + k + 1]);
         if (e != hipSuccess) return fail_hip(ctx, "hipEventElapsedTime", e);
