@@ -231,12 +231,17 @@ dm_status dm_debug_logits(dm_ctx* ctx, const dm_params* prm, const void* h, cons
  * number of recorded calls and the mean duration of the three kernels of the token-level path
  * in milliseconds (any output pointer may be NULL); dm_get_profile_stages returns all five
  * stage means in ms[0..4] = mask rows, LM head, JS pass 1, JS pass 2, vote/accept (the JS
- * stages are 0 for dropmatch_verify).  dm_set_profiling(ctx, 2) records only the two events around
- * the LM-head contraction kernel (the lightest way to time the dominant kernel inside a timed
- * loop; the other stage means then read 0).  dm_set_profiling(ctx, 0) stops recording and forgets
- * the samples. */
+ * stages are 0 for dropmatch_verify).  dm_set_profiling(ctx, 2) times only the LM-head contraction
+ * kernel, with two events that take the begin and end timestamps of that launch itself (events
+ * recorded on the stream around a launch also span the dispatch gap in front of the kernel); the
+ * other stage means then read 0.  This is the way to time the dominant kernel inside a timed loop.  dm_set_profiling(ctx, 0) stops recording and forgets
+ * the samples.  dm_set_profiling_stride(ctx, n) makes the calls that record events every n-th
+ * verify call counted from the next dm_set_profiling (n >= 1, default 1; DM_EINVAL otherwise):
+ * an event pair costs a few microseconds of stream time, so a timed loop samples a fraction of
+ * its calls. */
 #define DM_PROFILE_MAX_CALLS 512
 dm_status dm_set_profiling(dm_ctx* ctx, int32_t enabled);
+dm_status dm_set_profiling_stride(dm_ctx* ctx, int32_t stride);
 dm_status dm_get_profile(dm_ctx* ctx, int32_t* n_calls, float* ms_mask, float* ms_lmhead, float* ms_vote);
 dm_status dm_get_profile_stages(dm_ctx* ctx, int32_t* n_calls, float* ms /* HOST [5] */);
 

@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdropmatch.so")
 
 EXPORTS = ("dm_create", "dm_destroy", "dm_last_error", "dm_validate", "dropmatch_verify",
-           "dm_debug_masks", "dm_debug_logits", "dm_kernel_choice", "dm_set_profiling", "dm_get_profile",
+           "dm_debug_masks", "dm_debug_logits", "dm_kernel_choice", "dm_set_profiling", "dm_set_profiling_stride", "dm_get_profile",
            "dm_get_profile_stages", "dm_reserve_js", "dropmatch_verify_js")
 
 
@@ -73,6 +73,8 @@ def load_library():
     lib.dm_debug_logits.restype = C.c_int
     lib.dm_set_profiling.argtypes = [vp, i32]
     lib.dm_set_profiling.restype = C.c_int
+    lib.dm_set_profiling_stride.argtypes = [vp, i32]
+    lib.dm_set_profiling_stride.restype = C.c_int
     lib.dm_get_profile.argtypes = [vp, C.POINTER(i32)] + [C.POINTER(C.c_float)] * 3
     lib.dm_get_profile.restype = C.c_int
     lib.dm_get_profile_stages.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_float)]
@@ -177,6 +179,10 @@ def dm_debug_logits(ctx, prm: dm_params, h, W, v0: int, v1: int, logits, stream=
 def dm_set_profiling(ctx, enabled) -> None:
     """False/0: off; True/1: events around every kernel; 2: only around the contraction kernel."""
     _check(ctx, load_library().dm_set_profiling(ctx, int(enabled)))
+
+
+def dm_set_profiling_stride(ctx, stride: int) -> None:
+    _check(ctx, load_library().dm_set_profiling_stride(ctx, int(stride)))
 
 
 def dm_get_profile(ctx):

@@ -31,6 +31,8 @@ struct dm_ctx {
   hipEvent_t* ev = nullptr;
   int prof_enabled = 0;
   int prof_calls = 0;
+  int prof_stride = 1;  // events are recorded on every prof_stride-th verify call
+  int prof_seen = 0;    // verify calls since profiling was switched on
 };
 
 namespace {
@@ -155,7 +157,14 @@ dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g,
   hipError_t e = dm::launch_mask_rows(h, ctx->a_ws, ctx->keys, p->seeds, g, bf16, mfma,
                                       sample ? ctx->seeds_dev : nullptr, s);
   if (e != hipSuccess) return fail_hip(ctx, "mask_rows launch", e);
-  if (ev) (void)hipEventRecord(ev[1], s);
+  // all stages: events on the stream around every kernel; otherwise the two events take the
+  // timestamps of the contraction launch itself
+  dm::LaunchSite at{s};
+  if (ev && all_stages) (void)hipEventRecord(ev[1], s);
+  if (ev && !all_stages) {
+    at.start = ev[1];
+    at.stop = ev[2];
+  }
   const float scale = (float)(1.0 / (1.0 - (double)p->p));
   dm::SampleCfg samp{nullptr, 0.f, p->T, p->K, p->step, g.clean_last};
   if (sample) {
@@ -163,13 +172,13 @@ dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g,
     samp.zscale = (float)(1.0 / (1.0 - (double)p->p) / (double)p->temperature);
   }
   if (mfma && g.M <= 128)
-    e = dm::launch_lmhead_mfma(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, store, samp, fuse, fused, s);
+    e = dm::launch_lmhead_mfma(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, store, samp, fuse, fused, at);
   else if (mfma)
-    e = dm::launch_lmhead_mfma_big(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, store, samp, s);
+    e = dm::launch_lmhead_mfma_big(W, ctx->a_ws, ctx->keys, g, p->V, ctx->num_cu, logits, v0, v1, scale, store, samp, at);
   else
-    e = dm::launch_lmhead_generic(W, ctx->a_ws, ctx->keys, g, p->V, bf16, logits, v0, v1, scale, store, samp, s);
+    e = dm::launch_lmhead_generic(W, ctx->a_ws, ctx->keys, g, p->V, bf16, logits, v0, v1, scale, store, samp, at);
   if (e != hipSuccess) return fail_hip(ctx, "lmhead launch", e);
-  if (ev) (void)hipEventRecord(ev[2], s);
+  if (ev && all_stages) (void)hipEventRecord(ev[2], s);
   return DM_OK;
 }
 
@@ -219,7 +228,8 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
   hipStream_t s = static_cast<hipStream_t>(stream);
 
   hipEvent_t* ev = nullptr;
-  if (ctx->prof_enabled && ctx->ev && ctx->prof_calls < DM_PROFILE_MAX_CALLS) ev = ctx->ev + kEv * ctx->prof_calls;
+  if (ctx->prof_enabled && ctx->ev && ctx->prof_calls < DM_PROFILE_MAX_CALLS && (ctx->prof_seen++ % ctx->prof_stride) == 0)
+    ev = ctx->ev + kEv * ctx->prof_calls;
   const bool all_stages = ctx->prof_enabled == 1;
   const int Kv = g.clean_last ? prm->K - 1 : prm->K;
   dm::VoteOut out{accept_len, best_node, accept_mask, hit, path_ids, vote_ids, vote_cnt, js_draft, js_heads};
@@ -400,6 +410,7 @@ dm_status dm_set_profiling(dm_ctx* ctx, int32_t enabled) {
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return fail(ctx, DM_EHIP, "cannot select device %d", ctx->device);
   ctx->prof_calls = 0;
+  ctx->prof_seen = 0;
   ctx->prof_enabled = 0;
   if (!enabled) return DM_OK;
   if (!ctx->ev) {
@@ -414,6 +425,13 @@ dm_status dm_set_profiling(dm_ctx* ctx, int32_t enabled) {
     }
   }
   ctx->prof_enabled = enabled == 2 ? 2 : 1;
+  return DM_OK;
+}
+
+dm_status dm_set_profiling_stride(dm_ctx* ctx, int32_t stride) {
+  if (!ctx) return fail(nullptr, DM_EINVAL, "ctx is NULL");
+  if (stride < 1) return fail(ctx, DM_EINVAL, "stride must be at least 1, got %d", stride);
+  ctx->prof_stride = stride;
   return DM_OK;
 }
 

@@ -2,6 +2,7 @@
 // `stream`; shapes have been validated by the caller (api.hip).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace dm {
@@ -54,11 +55,28 @@ struct SampleCfg {
   int clean_last;
 };
 
+// Where a contraction kernel is launched: the stream and, optionally, two events that receive the
+// begin and end timestamps of that launch itself.  Events recorded on the stream before and after
+// a launch also span the dispatch gap in front of the kernel (measured: 5-9 us on a 160 us kernel).
+struct LaunchSite {
+  hipStream_t stream;
+  hipEvent_t start = nullptr, stop = nullptr;
+};
+
+template <typename... KArgs, typename... Args>
+inline void launch_at(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes, const LaunchSite& at,
+                      Args... args) {
+  if (at.start != nullptr)
+    hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, at.stream, at.start, at.stop, 0, args...);
+  else
+    hipLaunchKernelGGL(kernel, grid, block, lds_bytes, at.stream, args...);
+}
+
 // Eq. (3) + per-row argmax, generic fp32-FMA tiles.  a_ws plain layout.  If logits != null the
 // kernel instead stores scale * accumulator for v in [v0, v1) and touches no keys.
 hipError_t launch_lmhead_generic(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g,
                                  int V, bool is_bf16, float* logits, int v0, int v1, float scale,
-                                 const LogitStore& store, const SampleCfg& samp, hipStream_t stream);
+                                 const LogitStore& store, const SampleCfg& samp, const LaunchSite& at);
 
 // Eq. (3) + per-row argmax on bf16 MFMA; a_ws swizzled layout; d % 64 == 0.
 struct VoteFuse;
@@ -67,13 +85,13 @@ struct VoteFuse;
 hipError_t launch_lmhead_mfma(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g,
                               int V, int num_cu, float* logits, int v0, int v1, float scale,
                               const LogitStore& store, const SampleCfg& samp, const VoteFuse* fuse, bool* fused,
-                              hipStream_t stream);
+                              const LaunchSite& at);
 hipError_t prepare_lmhead_mfma();  // raises the dynamic-LDS limit of the kernels once per process
 
 // Same contract for more than 128 masked rows (256 x 256 tiles); needs M_pad % 256 == 0.
 hipError_t launch_lmhead_mfma_big(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g,
                                   int V, int num_cu, float* logits, int v0, int v1, float scale,
-                                  const LogitStore& store, const SampleCfg& samp, hipStream_t stream);
+                                  const LogitStore& store, const SampleCfg& samp, const LaunchSite& at);
 hipError_t prepare_lmhead_mfma_big();
 
 // Distribution-level rule (Eq. (5), (6)) over the stored logits, in two passes over the vocabulary;

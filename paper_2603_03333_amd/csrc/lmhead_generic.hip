@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256) void lmhead_generic_kernel(const T* __restrict
 
 hipError_t launch_lmhead_generic(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g,
                                  int V, bool is_bf16, float* logits, int v0, int v1, float scale,
-                                 const LogitStore& store, const SampleCfg& samp, hipStream_t stream) {
+                                 const LogitStore& store, const SampleCfg& samp, const LaunchSite& at) {
   const bool dump = logits != nullptr;
   const int tile0 = dump ? v0 / GT : 0;
   const int tile1 = dump ? (v1 + GT - 1) / GT : (V + GT - 1) / GT;
@@ -153,10 +153,8 @@ hipError_t launch_lmhead_generic(const void* W, const void* a_ws, unsigned long 
   const dim3 grid((unsigned)(tile1 - tile0), (unsigned)mtiles), block(256);
   const int mode = dump ? 1 : (store.lt != nullptr ? 2 : 0);
 #define DM_GEN(T, MODE, SAMPLE)                                                                                   \
-  lmhead_generic_kernel<T, MODE, SAMPLE><<<grid, block, 0, stream>>>(static_cast<const T*>(W),                     \
-                                                                     static_cast<const T*>(a_ws), keys, g.M, g.d,  \
-                                                                     g.d_pad, V, tile0, logits, v0, v1, scale,     \
-                                                                     store, samp)
+  launch_at(lmhead_generic_kernel<T, MODE, SAMPLE>, grid, block, (size_t)0, at, static_cast<const T*>(W),           \
+            static_cast<const T*>(a_ws), keys, g.M, g.d, g.d_pad, V, tile0, logits, v0, v1, scale, store, samp)
   const bool sample = mode == 0 && samp.seeds != nullptr;
   if (is_bf16) {
     if (mode == 1) DM_GEN(uint16_t, 1, false); else if (mode == 2) DM_GEN(uint16_t, 2, false);

@@ -330,7 +330,7 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
 template <int MT>
 hipError_t run(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V, int num_cu,
                float* logits, int v0, int v1, float scale, const LogitStore& store, const VoteFuse& fuse,
-               const SampleCfg& samp, hipStream_t stream) {
+               const SampleCfg& samp, const LaunchSite& at) {
   const bool dump = logits != nullptr;
   const int v_lo = dump ? v0 : 0;
   const int v_hi = dump ? v1 : V;
@@ -346,9 +346,9 @@ hipError_t run(const void* W, const void* a_ws, unsigned long long* keys, const 
   rows_per_wg = (rows_per_wg + 3) & ~3;  // ranges start at multiples of 4: one Philox call serves 4 rows when sampling
   const dim3 grid((unsigned)gx, (unsigned)mblocks), block(THREADS);
 #define DM_LAUNCH(MODE, SAMPLE)                                                                                 \
-  lmhead_mfma_kernel<MT, MODE, SAMPLE><<<grid, block, lds_bytes(MT), stream>>>(                                  \
-      static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo, v_hi,    \
-      rows_per_wg, logits, v0, v1, scale, store, fuse, samp)
+  launch_at(lmhead_mfma_kernel<MT, MODE, SAMPLE>, grid, block, (size_t)lds_bytes(MT), at,                        \
+            static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo,    \
+            v_hi, rows_per_wg, logits, v0, v1, scale, store, fuse, samp)
   if (dump)
     DM_LAUNCH(1, false);
   else if (store.lt != nullptr)
@@ -385,7 +385,7 @@ hipError_t prepare_lmhead_mfma() {
 
 hipError_t launch_lmhead_mfma(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V,
                               int num_cu, float* logits, int v0, int v1, float scale, const LogitStore& store,
-                              const SampleCfg& samp, const VoteFuse* fuse_in, bool* fused, hipStream_t stream) {
+                              const SampleCfg& samp, const VoteFuse* fuse_in, bool* fused, const LaunchSite& at) {
   // the acceptance step rides along when this is the plain verify path and its scratch fits the slabs
   VoteFuse fuse{};
   const bool can_fuse = fuse_in != nullptr && fuse_in->counter != nullptr && logits == nullptr &&
@@ -397,12 +397,12 @@ hipError_t launch_lmhead_mfma(const void* W, const void* a_ws, unsigned long lon
   const int mt_total = (int)(g.M_pad >> 5);
   if (mt_total >= 4) {
     if (mt_total % 4 != 0) return hipErrorInvalidValue;
-    return run<4>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, samp, stream);
+    return run<4>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, samp, at);
   }
   switch (mt_total) {
-    case 1: return run<1>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, samp, stream);
-    case 2: return run<2>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, samp, stream);
-    case 3: return run<3>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, samp, stream);
+    case 1: return run<1>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, samp, at);
+    case 2: return run<2>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, samp, at);
+    case 3: return run<3>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, fuse, samp, at);
     default: return hipErrorInvalidValue;
   }
 }

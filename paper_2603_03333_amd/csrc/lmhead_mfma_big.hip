@@ -371,7 +371,7 @@ TileWalk make_walk(int NV, int NMB, int G) {
 template <int BK>
 hipError_t run_big(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V, int num_cu,
                    float* logits, int v0, int v1, float scale, const LogitStore& store, const SampleCfg& samp,
-                   hipStream_t stream) {
+                   const LaunchSite& at) {
   const bool dump = logits != nullptr;
   const int v_lo = dump ? v0 : 0;
   const int v_hi = dump ? v1 : V;
@@ -385,9 +385,9 @@ hipError_t run_big(const void* W, const void* a_ws, unsigned long long* keys, co
   const dim3 grid((unsigned)G), block(THREADS);
   const int mt_total = (int)(g.M_pad >> 5);
 #define DM_LAUNCH(MODE, SAMPLE)                                                                                    \
-  lmhead_mfma_big_kernel<BK, MODE, SAMPLE><<<grid, block, Cfg<BK>::LDS_BYTES, stream>>>(                            \
-      static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo, v_hi, walk, \
-      logits, v0, v1, scale, store, samp)
+  launch_at(lmhead_mfma_big_kernel<BK, MODE, SAMPLE>, grid, block, (size_t)Cfg<BK>::LDS_BYTES, at,                  \
+            static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo, v_hi, \
+            walk, logits, v0, v1, scale, store, samp)
   if (dump)
     DM_LAUNCH(1, false);
   else if (store.lt != nullptr)
@@ -420,9 +420,9 @@ hipError_t prepare_lmhead_mfma_big() {
 
 hipError_t launch_lmhead_mfma_big(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V,
                                   int num_cu, float* logits, int v0, int v1, float scale, const LogitStore& store,
-                                  const SampleCfg& samp, hipStream_t stream) {
+                                  const SampleCfg& samp, const LaunchSite& at) {
   if (g.M_pad % BM != 0) return hipErrorInvalidValue;
-  return run_big<kBigBK>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, samp, stream);
+  return run_big<kBigBK>(W, a_ws, keys, g, V, num_cu, logits, v0, v1, scale, store, samp, at);
 }
 
 }  // namespace dm
