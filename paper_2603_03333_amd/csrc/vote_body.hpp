@@ -67,6 +67,14 @@ __device__ __forceinline__ void vote_accept_body(int b, int tid, int nthreads, i
       const float* src = part_b + (((int64_t)b * T + t) * jg.KS + (i < K ? i : jg.K4)) * jg.NC;
       double s = 0.0;
       int c = 0;
+      // the loop is bound by load latency, so many loads are issued before the first is added
+      for (; c + 32 <= jg.NC; c += 32) {
+        float v[32];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) v[u] = src[c + u];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) s += (double)v[u];
+      }
       for (; c + 8 <= jg.NC; c += 8) {
         float v[8];
 #pragma unroll
