@@ -297,16 +297,22 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
       RowRng rng{0u, 0u, 0u, 0u, false};
       if (SAMPLE) rng = make_row_rng(samp, (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32, M);
       const bool noisy = SAMPLE && rng.on;
+      // First vocabulary row of this lane in the tile.  When sampling it is made opaque to the compiler
+      // for every masked-row tile: otherwise whatever depends on the vocabulary row only (noise
+      // counters, the first Philox round) is shared between the four tiles, kept in registers across
+      // the main loop, and spilled there.
+      int vb = v0 + 64 * wv + 4 * hb;
+      if (SAMPLE) asm volatile("" : "+v"(vb));
 #pragma unroll
       for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
         for (int rq = 0; rq < 4; ++rq) {
           float g[4] = {0.f, 0.f, 0.f, 0.f};
-          if (noisy) gumbel4(rng, (uint32_t)(v0 + 64 * wv + 32 * vt + 8 * rq + 4 * hb), samp.step, g);
+          if (noisy) gumbel4(rng, (uint32_t)(vb + 32 * vt + 8 * rq), samp.step, g);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {  // ascending v for this lane: strict > keeps the smallest index
             const int r = 4 * rq + e;
-            const int v = v0 + 64 * wv + 32 * vt + 8 * rq + 4 * hb + e;
+            const int v = vb + 32 * vt + 8 * rq + e;
             const float val = noisy ? fmaf(acc[mt][vt][r], samp.zscale, g[e]) : acc[mt][vt][r] + 0.0f;
             if (v < v_hi && (bv == 0xFFFFFFFFu || val > best)) {
               best = val;
@@ -314,6 +320,8 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
             }
             acc[mt][vt][r] = 0.f;
           }
+          // the noise of one group of four rows is not computed ahead of the groups before it
+          if (SAMPLE) __builtin_amdgcn_sched_barrier(0);
         }
       unsigned long long key = (bv == 0xFFFFFFFFu) ? 0ull : pack_key(best, bv);
       const unsigned long long other = __shfl_xor(key, 32, 64);
