@@ -491,3 +491,46 @@ def test_sampling_frequencies_on_the_gpu(runner):
     obs, expct = counts[keep], want[keep] * counts.sum()
     pval = scipy.stats.chisquare(obs, expct * obs.sum() / expct.sum())[1]
     assert pval > 1e-3, (counts, want * counts.sum())
+
+
+# ------------------------------------------------------------------ measurement aid
+@pytest.mark.parametrize("d,V,B,T,K,dtype", [
+    (256, 1024, 1, 4, 16, "bf16"),    # W-streaming kernel (64 rows)
+    (256, 1024, 2, 10, 16, "bf16"),   # 256 x 256 tiles (320 rows)
+    (100, 130, 2, 3, 5, "f32"),       # generic kernel
+])
+def test_profiling_modes_time_kernels_and_leave_results_alone(runner, d, V, B, T, K, dtype):
+    """dm_set_profiling: mode 2 times the contraction launch itself on every stride-th call, mode 1
+    brackets every kernel; neither may change a result (mode 2 launches through another runtime call)."""
+    wl, W, h, seeds, draft = _problem("prof", d, V, dtype, B, T, K, 0.1, seed=d + V + B, bonus=False)
+    hd, Wd = to_device(h, dtype), to_device(W, dtype)
+    plain = runner.verify(wl, hd, Wd, draft, seeds)
+    try:
+        dmb.dm_set_profiling_stride(runner.ctx, 3)
+        dmb.dm_set_profiling(runner.ctx, 2)
+        for _ in range(7):
+            res = runner.verify(wl, hd, Wd, draft, seeds)
+            for k in plain:
+                assert np.array_equal(res[k], plain[k]), k
+        n, ms = dmb.dm_get_profile_stages(runner.ctx)
+        assert n == 3                                   # calls 0, 3 and 6
+        assert 0.0 < ms[1] < 50.0 and ms[0] == 0.0 and ms[4] == 0.0
+
+        dmb.dm_set_profiling_stride(runner.ctx, 1)
+        dmb.dm_set_profiling(runner.ctx, 1)
+        for _ in range(4):
+            res = runner.verify(wl, hd, Wd, draft, seeds)
+            for k in plain:
+                assert np.array_equal(res[k], plain[k]), k
+        n, ms = dmb.dm_get_profile_stages(runner.ctx)
+        assert n == 4 and ms[0] > 0.0 and ms[1] > 0.0 and ms[4] >= 0.0 and ms[2] == 0.0 and ms[3] == 0.0  # no JS passes in dropmatch_verify
+        n3, m0, m1, m4 = dmb.dm_get_profile(runner.ctx)
+        assert n3 == 4 and m1 == pytest.approx(ms[1])
+
+        dmb.dm_set_profiling(runner.ctx, 0)
+        assert dmb.dm_get_profile_stages(runner.ctx)[0] == 0
+        with pytest.raises(dmb.DropMatchError):
+            dmb.dm_set_profiling_stride(runner.ctx, 0)
+    finally:
+        dmb.dm_set_profiling(runner.ctx, 0)
+        dmb.dm_set_profiling_stride(runner.ctx, 1)
