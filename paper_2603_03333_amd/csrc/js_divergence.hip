@@ -206,25 +206,29 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
   const int i0 = 4 * grp;
   const bool active = i0 < g.K4;
 
-  // normalisers from the partial sums of pass 1: one wavefront per slot, lanes over chunks, then a
-  // butterfly (a fixed order, the same in every workgroup)
+  // normalisers from the partial sums of pass 1: 8 lanes per slot (a head, or the mean logits), every
+  // lane adds every 8th chunk record (independent loads, all in flight together), then a butterfly over
+  // the 8 lanes: a fixed order, the same in every workgroup
   const float* pa = part_a + (int64_t)pos * g.KS * g.NC;
-  for (int slot = wave; slot <= KU; slot += JT / 64) {
+  for (int slot = tid >> 3; slot <= KU; slot += JT / 8) {
+    const int sub = tid & 7;
     if (slot < KU) {
       double s = 0.0;
-      for (int cc = lane; cc < g.NC; cc += 64) s += (double)pa[(int64_t)slot * g.NC + cc];
-      s = wave_sum(s);
-      if (lane == 0) Zs[slot] = (float)((double)(scale * key_logit(keys[(int64_t)pos * K + slot])) + log(s));
+      for (int cc = sub; cc < g.NC; cc += 8) s += (double)pa[(int64_t)slot * g.NC + cc];
+#pragma unroll
+      for (int off = 4; off >= 1; off >>= 1) s += __shfl_xor(s, off, 8);
+      if (sub == 0) Zs[slot] = (float)((double)(scale * key_logit(keys[(int64_t)pos * K + slot])) + log(s));
     } else {  // mean logits: chunk records are (max, sum of exp relative to that max)
       float m = -INFINITY;
-      for (int cc = lane; cc < g.NC; cc += 64) m = fmaxf(m, pa[(int64_t)g.K4 * g.NC + cc]);
+      for (int cc = sub; cc < g.NC; cc += 8) m = fmaxf(m, pa[(int64_t)g.K4 * g.NC + cc]);
 #pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+      for (int off = 4; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 8));
       double s = 0.0;
-      for (int cc = lane; cc < g.NC; cc += 64)
+      for (int cc = sub; cc < g.NC; cc += 8)
         s += (double)pa[(int64_t)(g.K4 + 1) * g.NC + cc] * exp((double)pa[(int64_t)g.K4 * g.NC + cc] - (double)m);
-      s = wave_sum(s);
-      if (lane == 0) Zs[KP] = (float)((double)m + log(s));
+#pragma unroll
+      for (int off = 4; off >= 1; off >>= 1) s += __shfl_xor(s, off, 8);
+      if (sub == 0) Zs[KP] = (float)((double)m + log(s));
     }
   }
   __syncthreads();
