@@ -12,7 +12,11 @@
 //     [128 wm, +128) of the tile: 2 x 4 accumulator tiles (128 VGPRs);
 //   * 4 producers: global -> LDS copies by LDS-DMA, so that a full memory queue stalls a
 //     producer and not the MFMA stream.
-// k advances in slabs of BK; NS slabs live in LDS (BK = 64: 2 x 64 KB, BK = 32: 4 x 32 KB).
+// k advances in slabs of 64.  LDS holds a ring of three W slabs (two in flight: they come from
+// HBM or the memory-side cache) and a ring of two slabs of masked rows (one in flight: they are
+// re-read from L2 by every workgroup), 3 x 32 KB + 2 x 32 KB = all of the 160 KB; one workgroup
+// barrier per slab: "slab q has landed for everybody, nobody reads slab q-1 any more".  The four
+// wavefronts that share a masked row merge their arg max through the 64-bit key in memory.
 // W rows are stored in LDS with their 16-byte pieces XOR-swizzled by the row number so that
 // the MFMA fragment reads (32 rows, same piece) are bank-conflict free; masked rows arrive in
 // fragment order from the mask kernel.
@@ -36,20 +40,21 @@ constexpr int THREADS = 768;
 
 template <int BK>
 struct Cfg {
-  static constexpr int NS = (BK == 64) ? 2 : 4;        // slabs resident in LDS
   static constexpr int PR = BK / 8;                    // 16-byte pieces per W row per slab
   static constexpr int KSTEPS = BK / 16;               // MFMA k-steps per slab
   static constexpr int ROW_BYTES = BK * 2;
   static constexpr int W_SLAB = BN * ROW_BYTES;
   static constexpr int A_SLAB = BM * ROW_BYTES;
-  static constexpr int SLAB = W_SLAB + A_SLAB;
   static constexpr int W_INSTR = (64 * ROW_BYTES) / 1024;  // W copy instructions per producer per slab
   static constexpr int A_INSTR = KSTEPS * 8 / 4;           // masked-row fragments per producer per slab
-  static constexpr int LOADS = W_INSTR + A_INSTR;
-  static constexpr int RED_BYTES = 4 * BM * 8;
-  static constexpr int LDS_BYTES = NS * SLAB + RED_BYTES;
+  // W slabs come from HBM (long latency), masked-row slabs from L2: W gets the deeper ring.
+  // 3 x 32 KB + 2 x 32 KB = all 160 KB of the LDS at BK = 64.
+  static constexpr int NSW = 3, NSA = 2;
+  static constexpr int A_BASE = NSW * W_SLAB;
+  static constexpr int LDS_BYTES = NSW * W_SLAB + NSA * A_SLAB;
   static constexpr int SWZ_SHIFT = (BK == 64) ? 1 : 2;     // rows per 256-byte bank period: 2 or 4
 };
+static_assert(Cfg<64>::LDS_BYTES <= 160 * 1024, "LDS of a gfx950 compute unit");
 
 // How the persistent grid walks the NV x NMB tiles (filled on the host).
 struct TileWalk {
@@ -140,19 +145,28 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
     const uint32_t aoff = (uint32_t)lane * 16u;
     const char* Wb = reinterpret_cast<const char*>(W);
     const char* Ab = reinterpret_cast<const char*>(A_sw);
-    int it_p = -1, c_p = nchunks, tv_p = 0, tm_p = 0;  // cursor of the next slab to issue
-    auto issue_next = [&](int q) {
-      if (c_p == nchunks) {  // move to the next tile of this workgroup
-        c_p = 0;
+    struct Cursor {
+      int it = -1, c = 0, tv = 0, tm = 0;
+    };
+    Cursor cw, ca;
+    cw.c = ca.c = nchunks;
+    auto advance = [&](Cursor& cu) {  // returns the k chunk of the cursor's next slab
+      if (cu.c == nchunks) {
+        cu.c = 0;
         do {
-          ++it_p;
-        } while (!tile_of(walk, pos, it_p, tv_p, tm_p));
+          ++cu.it;
+        } while (!tile_of(walk, pos, cu.it, cu.tv, cu.tm) && cu.it < nit);
+        if (cu.it >= nit) cu.tv = cu.tm = 0;  // cannot happen (slabs are counted from the same walk); stays in bounds
       }
-      int c = c_p + rot;
+      int c = cu.c + rot;
       c = c >= nchunks ? c - nchunks : c;
-      ++c_p;
-      const int v0 = v_lo + tv_p * BN + 64 * p;  // first vocabulary row of this producer's 64
-      unsigned char* stage = lds + (q % C::NS) * C::SLAB;
+      ++cu.c;
+      return c;
+    };
+    auto issue_w = [&](int q) {
+      const int c = advance(cw);
+      const int v0 = v_lo + cw.tv * BN + 64 * p;
+      unsigned char* stage = lds + (q % C::NSW) * C::W_SLAB;
       const char* wsrc = Wb + ((int64_t)v0 * d + (int64_t)c * BK) * 2;
       if (v0 + 64 <= v_hi) {
 #pragma unroll
@@ -169,32 +183,34 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
                                            DM_LDS_PTR(stage + p * (64 * C::ROW_BYTES) + rb * 1024), 16, 0, 0);
         }
       }
-      const char* asrc = Ab + ((int64_t)(c * C::KSTEPS) * mt_total + tm_p * 8) * 1024;
+    };
+    auto issue_a = [&](int q) {
+      const int c = advance(ca);
+      unsigned char* stage = lds + C::A_BASE + (q % C::NSA) * C::A_SLAB;
+      const char* asrc = Ab + ((int64_t)(c * C::KSTEPS) * mt_total + ca.tm * 8) * 1024;
 #pragma unroll
       for (int x = 0; x < C::A_INSTR; ++x) {
         const int f = p + 4 * x;  // fragment index inside the slab: f = s * 8 + mt
         const int s = f >> 3, mt = f & 7;
-        dma_copy16(asrc + ((int64_t)s * mt_total + mt) * 1024, aoff, stage + C::W_SLAB + f * 1024);
+        dma_copy16(asrc + ((int64_t)s * mt_total + mt) * 1024, aoff, stage + f * 1024);
       }
     };
-    int issued = 0;
-    for (; issued < C::NS - 1 && issued < total; ++issued) issue_next(issued);
+    // issue order: W(0) A(0) W(1) | barrier 0 | A(1) W(2) | barrier 1 | A(2) W(3) | ...
+    // before barrier q everything but the youngest W slab (q+1, if there is one) has landed
+    if (total > 0) {  // a workgroup without tiles has no first slab to look for
+      issue_w(0);
+      issue_a(0);
+    }
+    if (total > 1) issue_w(1);
     for (int q = 0; q < total; ++q) {
-      // own copies of slab q have landed; up to NS-2 younger slabs may still be in flight
-      const int younger = (total - 1 - q) < (C::NS - 2) ? (total - 1 - q) : (C::NS - 2);
-      if (younger >= 2) {
-        DM_WAIT_VMCNT(2 * C::LOADS);
-      } else if (younger == 1) {
-        DM_WAIT_VMCNT(C::LOADS);
+      if (q + 1 < total) {
+        DM_WAIT_VMCNT(C::W_INSTR);
       } else {
         DM_WAIT_VMCNT(0);
       }
       DM_BARRIER();  // slab q complete for everyone; slab q-1 consumed by everyone
-      if (issued < total) {
-        issue_next(issued);
-        ++issued;
-      }
-      if (MODE != 1 && (q % nchunks) == nchunks - 1) DM_BARRIER();  // pairs with the consumers' tile-end barrier
+      if (q + 1 < total) issue_a(q + 1);
+      if (q + 2 < total) issue_w(q + 2);
     }
     return;
   }
@@ -216,9 +232,8 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
   int it_c = -1, tv_c = 0, tm_c = 0;
   for (int q = 0; q < total; ++q) {
     DM_BARRIER();
-    const unsigned char* stage = lds + (q % C::NS) * C::SLAB;
-    const unsigned char* wbase = stage + wv * (64 * C::ROW_BYTES) + i32 * C::ROW_BYTES;
-    const unsigned char* abase = stage + C::W_SLAB + (4 * wm) * 1024 + lane * 16;
+    const unsigned char* wbase = lds + (q % C::NSW) * C::W_SLAB + wv * (64 * C::ROW_BYTES) + i32 * C::ROW_BYTES;
+    const unsigned char* abase = lds + C::A_BASE + (q % C::NSA) * C::A_SLAB + (4 * wm) * 1024 + lane * 16;
 #pragma unroll
     for (int s = 0; s < C::KSTEPS; ++s) {
       bf16x8 wf[2], af[4];
@@ -240,7 +255,8 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
     // ---- tile finished ----
     do {
       ++it_c;
-    } while (!tile_of(walk, pos, it_c, tv_c, tm_c));
+    } while (!tile_of(walk, pos, it_c, tv_c, tm_c) && it_c < nit);
+    if (it_c >= nit) tv_c = tm_c = 0;  // cannot happen (slabs are counted from the same walk); stays in bounds
     const int v0 = v_lo + tv_c * BN;
     // accumulator (mt, vt, r): v = v0 + 64 wv + 32 vt + 8 (r/4) + 4 hb + r%4,  m = 256 tm + 128 wm + 32 mt + lane%32
     if (DUMP) {
@@ -289,7 +305,6 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
         }
     }
 
-    unsigned long long* red = reinterpret_cast<unsigned long long*>(lds + C::NS * C::SLAB);  // [4 wv][256 m]
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
       float best = -INFINITY;
@@ -326,20 +341,9 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
       unsigned long long key = (bv == 0xFFFFFFFFu) ? 0ull : pack_key(best, bv);
       const unsigned long long other = __shfl_xor(key, 32, 64);
       key = other > key ? other : key;
-      if (hb == 0) red[wv * BM + wm * 128 + mt * 32 + i32] = key;
-    }
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-    DM_BARRIER();
-    if (tid < BM) {
-      unsigned long long key = red[tid];
-#pragma unroll
-      for (int w = 1; w < 4; ++w) {
-        const unsigned long long other = red[w * BM + tid];
-        key = other > key ? other : key;
-      }
-      const int64_t m = (int64_t)tm_c * BM + tid;
-      if (m < M && key != 0ull) atomicMax(&keys[m], key);
+      // no LDS left for a reduction over the four wavefronts that share a masked row: each merges its own
+      const int64_t mrow = (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32;
+      if (hb == 0 && mrow < M && key != 0ull) atomicMax(&keys[mrow], key);
     }
   }
 }
