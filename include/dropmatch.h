@@ -239,7 +239,8 @@ dm_status dm_debug_logits(dm_ctx* ctx, const dm_params* prm, const void* h, cons
  * the samples.  dm_set_profiling_stride(ctx, n) makes the calls that record events every n-th
  * verify call counted from the next dm_set_profiling (n >= 1, default 1; DM_EINVAL otherwise):
  * an event pair costs a few microseconds of stream time, so a timed loop samples a fraction of
- * its calls. */
+ * its calls.  Recording must be off while a stream is captured into a graph (events cannot be
+ * recorded into a capture this way). */
 #define DM_PROFILE_MAX_CALLS 512
 dm_status dm_set_profiling(dm_ctx* ctx, int32_t enabled);
 dm_status dm_set_profiling_stride(dm_ctx* ctx, int32_t stride);
