@@ -215,7 +215,7 @@ def make_tree_parents(wl: Workload, max_depth: int = 6, max_branch: int = 4) -> 
 
 
 def make_tree_draft_ids(wl: Workload, parent: np.ndarray, greedy: Optional[np.ndarray]) -> np.ndarray:
-    """Token of every tree node: uniform in [0, V), children of one parent distinct;
+    """Token of every tree node: uniform in [0, V), children of one parent distinct (while V allows);
     then, for every parent independently with probability 1/2, its first child gets
     the caller-supplied greedy token of the PARENT row (row n predicts n's children).
     The root's token is -1 (it is the last committed token, never verified)."""
@@ -230,7 +230,8 @@ def make_tree_draft_ids(wl: Workload, parent: np.ndarray, greedy: Optional[np.nd
             q = int(parent[b, n])
             first_child.setdefault(q, n)
             tok = int(rng.integers(0, wl.V))
-            while tok in used.setdefault(q, set()):
+            # distinct among siblings as long as the vocabulary has unused tokens left for them
+            while tok in used.setdefault(q, set()) and len(used[q]) < wl.V:
                 tok = int(rng.integers(0, wl.V))
             used[q].add(tok)
             ids[b, n] = tok

@@ -96,3 +96,15 @@ def test_create_without_gpu_fails_loudly():
     prm, keep = _prm()
     st = dmb.load_library().dropmatch_verify(None, ctypes.byref(prm), *([None] * 11))
     assert st == dmb.DM_EINVAL and "ctx" in dmb.dm_last_error(None)
+
+
+def test_tree_inputs_for_a_vocabulary_smaller_than_a_sibling_group():
+    """The seeded tree generator keeps siblings distinct only while the vocabulary allows it
+    (with V = 1 every node carries token 0)."""
+    import numpy as np
+    from paper_2603_03333_amd import workloads as wk
+    wl = wk.Workload("t", d=8, V=1, dtype="f32", B=2, T=9, K=2, p=0.1, tree=True, data_seed=5)
+    parent = wk.make_tree_parents(wl, max_depth=4, max_branch=3)
+    ids = wk.make_tree_draft_ids(wl, parent, greedy=np.zeros((2, 9), dtype=np.int32))
+    assert (ids[:, 0] == -1).all() and (ids[:, 1:] == 0).all()
+    assert (parent[:, 1:] < np.arange(1, 9)[None, :]).all() and (parent[:, 0] == -1).all()
