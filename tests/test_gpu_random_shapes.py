@@ -101,3 +101,47 @@ def test_random_js_case(runner, case):
     want = gpu_js | (votes["hit"].astype(bool) if rule == 3 else False)
     assert np.array_equal(res["hit"].astype(bool), want)
     assert np.array_equal(res["accept_len"], orc.acceptance_from_hits(want)["accept_len"])
+
+
+@pytest.fixture(scope="module")
+def medium_runner():
+    r = Runner(max_rows=8192, max_d=512, max_V=70000)
+    yield r
+    r.close()
+
+
+def _draw_medium(case):
+    rng = np.random.default_rng(31000 + case)
+    d = int(rng.choice([64, 128, 256, 512]))
+    V = int(rng.integers(256, 66000)) if case % 4 else int(rng.choice([256, 257, 511, 512, 65536, 65537]))
+    K = int(rng.choice([4, 8, 16, 32]))
+    T = int(rng.integers(2, 17))
+    B = int(rng.integers(1, 33))
+    while B * T * K > 8192 or B * T * K * V > 6e7:   # keeps the oracle's float64 logits near 0.5 GB
+        B = max(1, B // 2)
+        if B == 1:
+            T = max(1, T // 2)
+        if B == 1 and T == 1:
+            V = V // 2 + 256
+    return rng, d, V, B, T, K
+
+
+@pytest.mark.parametrize("case", [0, 3, 4, 7, 9, 12, 16, 18, 26, 27, 28, 36])
+def test_random_medium_case(medium_runner, case):
+    """Several row blocks times hundreds of vocabulary tiles (the persistent tile walk of the 256 x 256
+    kernel, ragged in both directions), every path token against the oracle; every fifth case samples."""
+    rng, d, V, B, T, K = _draw_medium(case)
+    wl = wk.Workload(f"med{case}", d=d, V=V, dtype="bf16", B=B, T=T, K=K, p=0.1, bonus=False, data_seed=12000 + case)
+    W, h = wk.make_weight(wl, sigma=0.1), wk.make_hidden(wl)
+    seeds = rng.integers(0, 2 ** 63, size=B, dtype=np.uint64)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    tau = 1.0 if case % 5 == 0 else None
+    rule = case % 2
+    ref = orc.verify(h, W, draft, seeds, K, 0.1, rule=rule, temperature=tau)
+    res = medium_runner.verify(wl, to_device(h, "bf16"), to_device(W, "bf16"), draft, seeds, rule=rule,
+                               flags=dmb.DM_FLAG_SAMPLE_PATHS if tau else 0, temperature=tau or 0.0)
+    nflip, nnear = compare_path_ids(res["path_ids"], ref["path_ids"], ref["gap"])
+    print(f"[medium {case}: d={d} V={V} B={B} T={T} K={K} rows={B*T*K} tau={tau}] near-tie rows={nnear} flips={nflip}", flush=True)
+    exp = ref if nflip == 0 else orc.acceptance_from_path_ids(res["path_ids"], draft, rule, None)
+    for k in ("vote_ids", "vote_cnt", "hit", "accept_mask", "accept_len", "best_node"):
+        assert np.array_equal(res[k], exp[k]), f"medium case {case}: {k}"
