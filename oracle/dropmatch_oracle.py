@@ -41,8 +41,10 @@ listed with its reason in the design notes of the repository):
     is drawn from Softmax(l^(i) / tau) by the Gumbel-max construction,
     y = argmax_v (l[v] / tau + g[v]), g[v] = -ln(-ln u[v]), with u[v] = ((w >> 9) + 1/2) 2^-23
     and w the Philox4x32-10 word (v & 3) of counter (v >> 2, t, i, step) under the key
-    seed + 0x9E3779B97F4A7C15 (mod 2^64) - a stream separate from the masks'.  Truncation
-    to a nucleus (top-p < 1) is not implemented;
+    seed + 0x9E3779B97F4A7C15 (mod 2^64) - a stream separate from the masks'.  With top_p < 1
+    the draw is restricted to the nucleus of Softmax(l / tau): most probable tokens first until
+    their probabilities add up to top_p, tokens exactly as probable as the last one included
+    (so the set does not depend on an order among equals); same noise, arg max over the set;
   * `clean_last_path` (the paper does not say which token is emitted after a rejection
     or as the bonus token): path K-1 of every row is the plain LM head, h_t itself
     with no mask and no scale; its token is reported in path_ids[..., K-1] and the
@@ -211,10 +213,32 @@ def gumbel_noise(u: np.ndarray) -> np.ndarray:
     return -np.log(-np.log1p(-(1.0 - u)))      # ln u through log1p: exact near u = 1, where g is largest
 
 
-def sampled_token(logits: np.ndarray, tau: float, g: np.ndarray):
+def nucleus(z: np.ndarray, top_p: float):
+    """The nucleus (top-p set, Holtzman et al. 2020, the sampling the paper names for path tokens)
+    of Softmax(z): the tokens in order of decreasing probability (equal ones: smaller id first)
+    up to and including the first at which the running sum reaches top_p; tokens exactly as
+    probable as the last one taken are all in, so that the set does not depend on how equal
+    tokens are ordered.  Returns (boolean mask over the vocabulary, number n of tokens taken
+    before the ties were added)."""
+    q = softmax(np.asarray(z, dtype=np.float64))
+    order = np.argsort(-q, kind="stable")
+    cum = np.cumsum(q[order])
+    n = min(int(np.searchsorted(cum, float(top_p), side="left")) + 1, q.size)
+    return q >= q[order[n - 1]], n
+
+
+def sampled_token(logits: np.ndarray, tau: float, g: np.ndarray, top_p=None):
     """Gumbel-max draw from Softmax(logits / tau): argmax_v (logits[v] / tau + g[v]), ties ->
-    smallest v.  Also returns the top-1 minus top-2 gap of the perturbed values."""
-    return path_token(np.asarray(logits, dtype=np.float64) / float(tau) + g)
+    smallest v.  With top_p the arg max runs over the nucleus of that distribution only, which
+    is a draw from the distribution renormalised on the nucleus (the noise of the other tokens
+    is simply not looked at).  Also returns the top-1 minus top-2 gap of the perturbed values
+    (inf when a single token is eligible)."""
+    z = np.asarray(logits, dtype=np.float64) / float(tau)
+    y = z + g
+    if top_p is not None:
+        y = np.where(nucleus(z, top_p)[0], y, -np.inf)
+    tok, gap = path_token(y)
+    return tok, (gap if np.isfinite(gap) else np.inf)
 
 
 # --------------------------------------------------------------------------- #
@@ -402,7 +426,7 @@ def acceptance_from_hits(hit):
 # --------------------------------------------------------------------------- #
 def verify(h, W, draft_ids, seeds, K: int, p, step: int = 0, rule: int = RULE_ANY,
            share_mask_across_pos: bool = False, parent=None, want_logits=None,
-           clean_last_path: bool = False, temperature=None):
+           clean_last_path: bool = False, temperature=None, top_p=None):
     """One DropMatch verification step for B sequences.
 
     h          [B, T, d]  final hidden states (any float dtype; used as float64)
@@ -414,6 +438,7 @@ def verify(h, W, draft_ids, seeds, K: int, p, step: int = 0, rule: int = RULE_AN
     temperature None: path token = arg max.  A positive number: path token sampled from
                Softmax(l / temperature) (see sampled_token; a clean last path stays arg max);
                `gap` then refers to the perturbed values
+    top_p      with a temperature: sample from the nucleus of that distribution only (see nucleus)
 
     Returns a dict of numpy arrays: path_ids[B,T,K], gap[B,T,K] (top-1 minus top-2
     logit of each path), vote_ids[B,T], vote_cnt[B,T], hit[B,T], accept_mask[B,T],
@@ -445,7 +470,7 @@ def verify(h, W, draft_ids, seeds, K: int, p, step: int = 0, rule: int = RULE_AN
                     path_ids[b, t, i], gap[b, t, i] = path_token(L[:, i])
                 else:
                     g = gumbel_noise(sampling_uniforms(seeds[b], step, t, i, V))
-                    path_ids[b, t, i], gap[b, t, i] = sampled_token(L[:, i], temperature, g)
+                    path_ids[b, t, i], gap[b, t, i] = sampled_token(L[:, i], temperature, g, top_p)
                 if logits_out is not None:
                     logits_out[(b * T + t) * K + i] = L[v0:v1, i]
 

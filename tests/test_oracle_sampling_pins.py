@@ -90,3 +90,100 @@ def test_verify_with_sampled_paths():
     plain = orc.verify(h, W, draft, seeds, wl.K, wl.p)
     assert (out["path_ids"] != plain["path_ids"]).any()
     assert np.array_equal(orc.verify(h, W, draft, seeds, wl.K, wl.p, temperature=1e-5)["path_ids"], plain["path_ids"])
+
+
+# ------------------------------------------------------------------ nucleus (top-p) truncation
+def test_nucleus_hand_cases():
+    q = np.array([0.05, 0.5, 0.15, 0.3])
+    z = np.log(q)
+    for top_p, members in ((0.4, [1]), (0.51, [1, 3]), (0.79, [1, 3]), (0.81, [1, 2, 3]), (0.94, [1, 2, 3]),
+                           (0.96, [0, 1, 2, 3]), (1.0, [0, 1, 2, 3])):
+        mask, n = orc.nucleus(z, top_p)
+        assert np.flatnonzero(mask).tolist() == members and n == len(members), top_p
+    # tokens exactly as probable as the last one taken are all in: 0.4 + 0.2 reaches 0.5 with two
+    # tokens, the other two 0.2s come along
+    mask, n = orc.nucleus(np.log(np.array([0.2, 0.4, 0.2, 0.2])), 0.5)
+    assert n == 2 and mask.all()
+    # a shift of the logits changes nothing
+    assert np.array_equal(orc.nucleus(z + 123.0, 0.81)[0], orc.nucleus(z, 0.81)[0])
+
+
+def test_nucleus_is_the_smallest_heaviest_set():
+    """Brute force over all subsets of a small vocabulary: among the subsets whose probability
+    reaches top_p, the nucleus has the fewest tokens, and among those of that size the most mass."""
+    import itertools
+    rng = np.random.default_rng(12)
+    for trial in range(20):
+        V = int(rng.integers(2, 9))
+        z = rng.normal(size=V) * 2.0
+        q = scipy.special.softmax(z)
+        top_p = float(rng.uniform(0.05, 0.999))
+        mask, n = orc.nucleus(z, top_p)
+        best = None
+        for size in range(1, V + 1):
+            ok = [(q[list(c)].sum(), c) for c in itertools.combinations(range(V), size) if q[list(c)].sum() >= top_p]
+            if ok:
+                best = max(ok)[1]
+                break
+        assert mask.sum() == n == len(best) and set(np.flatnonzero(mask)) == set(best)
+
+
+def test_nucleus_sets_are_nested_and_limits():
+    rng = np.random.default_rng(4)
+    z = rng.normal(size=200) * 3.0
+    prev = np.zeros(200, dtype=bool)
+    for top_p in (1e-9, 0.1, 0.3, 0.5, 0.9, 0.99, 0.999999, 1.0):
+        mask, n = orc.nucleus(z, top_p)
+        assert (mask | prev).sum() == mask.sum()          # the earlier set is inside
+        assert scipy.special.softmax(z)[mask].sum() >= min(top_p, 1.0) - 1e-12
+        prev = mask
+    assert orc.nucleus(z, 1e-9)[0].sum() == 1 and orc.nucleus(z, 1.0)[0].all()
+    g = orc.gumbel_noise(orc.sampling_uniforms(3, 0, 0, 0, 200))
+    # top_p -> 0: the arg max whatever the noise; top_p = 1: the unrestricted draw
+    assert orc.sampled_token(z, 1.0, g, 1e-9) == (int(np.argmax(z)), np.inf)
+    assert orc.sampled_token(z, 0.7, g, 1.0)[0] == orc.sampled_token(z, 0.7, g)[0]
+
+
+def test_nucleus_draws_follow_the_renormalised_distribution():
+    rng = np.random.default_rng(8)
+    logits = rng.normal(size=9) * 1.5
+    tau, top_p = 0.9, 0.8
+    q = scipy.special.softmax(logits / tau)
+    mask, _ = orc.nucleus(logits / tau, top_p)
+    assert 1 < mask.sum() < 9
+    want = np.where(mask, q, 0.0) / q[mask].sum()
+    counts = np.zeros(9)
+    n = 8000
+    for step in range(n):
+        g = orc.gumbel_noise(orc.sampling_uniforms(21, step, 2, 1, 9))
+        counts[orc.sampled_token(logits, tau, g, top_p)[0]] += 1
+    assert counts[~mask].sum() == 0
+    assert scipy.stats.chisquare(counts[mask], want[mask] * n)[1] > 1e-3
+    assert scipy.stats.chisquare(counts[mask], q[mask] / q[mask].sum() * n * 1.0)[1] > 1e-3
+    # and not the unrestricted distribution (which puts mass outside the set)
+    assert q[~mask].sum() > 0.05
+
+
+def test_verify_with_nucleus_sampling():
+    wl = wk.Workload("nuc", d=32, V=60, dtype="f32", B=2, T=3, K=5, p=0.2, bonus=True, data_seed=17)
+    W, h, seeds = wk.make_weight(wl, sigma=0.4), wk.make_hidden(wl), wk.make_seeds(wl, base_seed=2)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    tau, top_p = 1.2, 0.6
+    out = orc.verify(h, W, draft, seeds, wl.K, wl.p, temperature=tau, top_p=top_p, want_logits=(0, wl.V))
+    L = out["logits"].reshape(wl.B, wl.T, wl.K, wl.V)
+    inside = 0
+    for b in range(wl.B):
+        for t in range(wl.T):
+            for i in range(wl.K):
+                q = scipy.special.softmax(L[b, t, i] / tau)
+                order = np.argsort(-q, kind="stable")
+                n = int(np.argmax(np.cumsum(q[order]) >= top_p)) + 1
+                keep = q >= q[order[n - 1]]
+                g = scipy.stats.gumbel_r.ppf(orc.sampling_uniforms(seeds[b], 0, t, i, wl.V))
+                y = np.where(keep, L[b, t, i] / tau + g, -np.inf)
+                assert out["path_ids"][b, t, i] == int(np.argmax(y))
+                inside += int(keep.sum())
+    assert inside < wl.B * wl.T * wl.K * wl.V            # the truncation did cut something
+    free = orc.verify(h, W, draft, seeds, wl.K, wl.p, temperature=tau)
+    assert (free["path_ids"] != out["path_ids"]).any()
+    assert np.array_equal(orc.verify(h, W, draft, seeds, wl.K, wl.p, temperature=tau, top_p=1.0)["path_ids"], free["path_ids"])
