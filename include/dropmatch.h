@@ -79,8 +79,16 @@ typedef enum {
  * it is a pure function of (seed, step, i, t): y = argmax_v (l[v] / temperature + g[v]),
  * g[v] = -ln(-ln u[v]), u[v] = ((w >> 9) + 1/2) 2^-23, w = word (v & 3) of Philox4x32-10 with counter
  * (v >> 2, t, i, step) and key = seed + 0x9E3779B97F4A7C15 (mod 2^64; a stream apart from the masks').
- * Ties -> smallest v.  Truncation to a nucleus (top-p < 1) is not implemented.  Needs
- * prm->temperature > 0; token-level rules only (dropmatch_verify); a clean last path stays arg max. */
+ * Ties -> smallest v.  Needs prm->temperature > 0; token-level rules only (dropmatch_verify); a
+ * clean last path stays arg max.
+ * With 0 < prm->top_p < 1 the arg max runs over the nucleus of that distribution only (Holtzman et
+ * al.'s top-p set): most probable tokens first until their probabilities add up to top_p, tokens
+ * exactly as probable as the last one included; same noise, so the draw follows the distribution
+ * renormalised on the set and top_p -> 1 gives the unrestricted draw.  This variant keeps the
+ * logits of the call (dm_reserve_js must have been called for B*T positions and K paths;
+ * K <= DM_MAX_K_JS, T*K <= DM_MAX_TK_JS), finds each row's threshold exactly (probability mass in
+ * 64-bit integers, floor(e^-t 2^44) with t the distance from the row's maximum over the temperature:
+ * reproducible run to run) and then draws from the stored logits. */
 #define DM_FLAG_SAMPLE_PATHS 16u
 
 /* Testing aid: always run the acceptance step as its own kernel.  (Without it, calls that go to the
@@ -111,6 +119,8 @@ typedef struct {
                             0 <= parent[b,n] < n.  A node whose parent index breaks this is
                             treated as rejected (never read out of bounds). */
   float temperature;     /* DM_FLAG_SAMPLE_PATHS only: > 0, finite.  Ignored otherwise. */
+  float top_p;           /* DM_FLAG_SAMPLE_PATHS only: 0 or 1 = draw from the whole distribution;
+                            0 < top_p < 1 = from its nucleus (see the flag).  Ignored otherwise. */
 } dm_params;
 
 /* Create a context on HIP device `device` able to serve calls with B*T*K <= max_rows,

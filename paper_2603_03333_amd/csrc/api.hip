@@ -26,6 +26,9 @@ struct dm_ctx {
   float* part_a = nullptr;
   float* part_b = nullptr;
   size_t part_floats = 0;
+  // nucleus sampling (also dm_reserve_js): per-row digit histograms, search state, keys of the drawn tokens
+  dm::NucBuffers nuc{nullptr, nullptr, nullptr, nullptr, nullptr};
+  size_t nuc_rows = 0;
   char err[512] = {0};
   // measurement aid: kEv events per recorded call
   hipEvent_t* ev = nullptr;
@@ -95,6 +98,17 @@ const char* check_params(const dm_params* p, char* scratch, size_t n) {
     if (!(p->temperature > 0.0f) || !std::isfinite(p->temperature))
       return "DM_FLAG_SAMPLE_PATHS needs a finite temperature > 0";
     if (p->rule >= DM_RULE_JS) return "sampled path tokens go with the token-level rules only";
+    if (!(p->top_p >= 0.0f && p->top_p <= 1.0f)) return "top_p must satisfy 0 <= top_p <= 1 (0 and 1: no truncation)";
+    if (p->top_p > 0.0f && p->top_p < 1.0f) {
+      if (p->K > DM_MAX_K_JS) {
+        snprintf(scratch, n, "nucleus sampling takes K <= %d", DM_MAX_K_JS);
+        return scratch;
+      }
+      if ((int64_t)p->T * p->K > DM_MAX_TK_JS) {
+        snprintf(scratch, n, "nucleus sampling takes T*K <= %d", DM_MAX_TK_JS);
+        return scratch;
+      }
+    }
   }
   if (!p->seeds) return "seeds is NULL";
   return nullptr;
@@ -154,9 +168,10 @@ dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g,
   const bool bf16 = p->dtype == DM_BF16;
   const bool all_stages = ctx->prof_enabled == 1;  // 2: only the contraction kernel is bracketed
   if (ev && all_stages) (void)hipEventRecord(ev[0], s);
-  const bool sample = (p->flags & DM_FLAG_SAMPLE_PATHS) && logits == nullptr;
+  const bool want_seeds = (p->flags & DM_FLAG_SAMPLE_PATHS) && logits == nullptr;
+  const bool sample = want_seeds && store.lt == nullptr;  // stored logits: the draw is made from them afterwards
   hipError_t e = dm::launch_mask_rows(h, ctx->a_ws, ctx->keys, p->seeds, g, bf16, mfma,
-                                      sample ? ctx->seeds_dev : nullptr, s);
+                                      want_seeds ? ctx->seeds_dev : nullptr, s);
   if (e != hipSuccess) return fail_hip(ctx, "mask_rows launch", e);
   // all stages: events on the stream around every kernel; otherwise the two events take the
   // timestamps of the contraction launch itself
@@ -181,6 +196,16 @@ dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g,
   if (e != hipSuccess) return fail_hip(ctx, "lmhead launch", e);
   if (ev && all_stages) (void)hipEventRecord(ev[2], s);
   return DM_OK;
+}
+
+void free_nucleus(dm_ctx* ctx) {
+  if (ctx->nuc.hist) (void)hipFree(ctx->nuc.hist);
+  if (ctx->nuc.prefix) (void)hipFree(ctx->nuc.prefix);
+  if (ctx->nuc.below) (void)hipFree(ctx->nuc.below);
+  if (ctx->nuc.target) (void)hipFree(ctx->nuc.target);
+  if (ctx->nuc.keys_s) (void)hipFree(ctx->nuc.keys_s);
+  ctx->nuc = dm::NucBuffers{nullptr, nullptr, nullptr, nullptr, nullptr};
+  ctx->nuc_rows = 0;
 }
 
 void drop_events(dm_ctx* ctx) {
@@ -224,6 +249,25 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
       return fail(ctx, DM_EINVAL, "B*T = %d positions with K = %d exceed what dm_reserve_js reserved", jg.P, jg.K);
     store = dm::LogitStore{ctx->lt, jg.K, jg.K4, jg.V, g.clean_last};
   }
+  const bool nucleus = !js && (prm->flags & DM_FLAG_SAMPLE_PATHS) && prm->top_p > 0.0f && prm->top_p < 1.0f;
+  dm::NucGeom ng{};
+  if (nucleus) {
+    ng.P = prm->B * prm->T;
+    ng.K = prm->K;
+    ng.K4 = (int)round_up(prm->K, 4);
+    ng.KP = 4;
+    while (ng.KP < ng.K4) ng.KP *= 2;
+    ng.KU = g.clean_last ? prm->K - 1 : prm->K;
+    ng.V = prm->V;
+    if ((int64_t)prm->B * prm->T > 0x7FFFFFFF) return fail(ctx, DM_EINVAL, "B*T too large");
+    if ((int64_t)(256 / prm->K + 2) * prm->V * ng.K4 * 4 >= ((int64_t)1 << 32))
+      return fail(ctx, DM_EUNSUPPORTED, "V = %d is too large for nucleus sampling with K = %d", prm->V, prm->K);
+    if (!ctx->lt || !ctx->nuc.hist)
+      return fail(ctx, DM_EINVAL, "nucleus sampling (0 < top_p < 1) keeps the logits: call dm_reserve_js first");
+    if ((size_t)ng.P * (size_t)ng.V * (size_t)ng.K4 > ctx->lt_floats || (size_t)ng.P * (size_t)ng.K > ctx->nuc_rows)
+      return fail(ctx, DM_EINVAL, "B*T = %d positions with K = %d exceed what dm_reserve_js reserved", ng.P, ng.K);
+    store = dm::LogitStore{ctx->lt, ng.K, ng.K4, ng.V, g.clean_last};
+  }
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return fail(ctx, DM_EHIP, "cannot select device %d", ctx->device);
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -250,18 +294,28 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
     e = dm::launch_js_terms(ctx->lt, ctx->keys, ctx->part_a, draft_probs, draft_ids, ctx->part_b, jg, scale, s);
     if (e != hipSuccess) return fail_hip(ctx, "js_terms launch", e);
     if (ev && all_stages) (void)hipEventRecord(ev[4], s);
+  } else if (nucleus) {
+    const float scale = (float)(1.0 / (1.0 - (double)prm->p));
+    const dm::SampleCfg samp{ctx->seeds_dev, 0.f, prm->T, prm->K, prm->step, g.clean_last};
+    e = dm::launch_nucleus(ctx->lt, ctx->keys, ctx->nuc, ng, samp, scale, (float)(1.0 / (double)prm->temperature),
+                           (double)prm->top_p, s);
+    if (e != hipSuccess) return fail_hip(ctx, "nucleus launch", e);
+    if (ev && all_stages) {  // reported in the two slots of the distribution-level passes
+      (void)hipEventRecord(ev[3], s);
+      (void)hipEventRecord(ev[4], s);
+    }
   } else if (ev && all_stages) {
     (void)hipEventRecord(ev[3], s);
     (void)hipEventRecord(ev[4], s);
   }
   if (!fused) {
-    e = dm::launch_vote_accept(ctx->keys, draft_ids, prm->parent, prm->B, prm->T, prm->K, Kv, prm->rule, out,
+    e = dm::launch_vote_accept(nucleus ? ctx->nuc.keys_s : ctx->keys, draft_ids, prm->parent, prm->B, prm->T, prm->K, Kv, prm->rule, out,
                                js ? ctx->part_b : nullptr, js ? &jg : nullptr, s);
     if (e != hipSuccess) return fail_hip(ctx, "vote_accept launch", e);
   }
   if (ev) {
     if (all_stages) (void)hipEventRecord(ev[5], s);
-    ctx->prof_kind[ctx->prof_calls] = (uint8_t)((js ? 1 : 0) | (fused ? 0 : 2));
+    ctx->prof_kind[ctx->prof_calls] = (uint8_t)(((js || nucleus) ? 1 : 0) | (fused ? 0 : 2));
     ++ctx->prof_calls;
   }
   return DM_OK;
@@ -325,7 +379,7 @@ dm_status dm_create(dm_ctx** out, int device, int64_t max_rows, int32_t max_d, i
     return fail(nullptr, DM_ENOMEM, "workspace allocation of %zu bytes failed: %s", a_bytes, hipGetErrorString(e));
   }
   if ((e = dm::prepare_lmhead_mfma()) != hipSuccess || (e = dm::prepare_lmhead_mfma_big()) != hipSuccess ||
-      (e = dm::prepare_vote_accept()) != hipSuccess) {
+      (e = dm::prepare_vote_accept()) != hipSuccess || (e = dm::prepare_nucleus()) != hipSuccess) {
     (void)hipFree(ctx->a_ws);
     (void)hipFree(ctx->keys);
     (void)hipFree(ctx->done);
@@ -350,6 +404,7 @@ dm_status dm_destroy(dm_ctx* ctx) {
   if (ctx->lt) (void)hipFree(ctx->lt);
   if (ctx->part_a) (void)hipFree(ctx->part_a);
   if (ctx->part_b) (void)hipFree(ctx->part_b);
+  free_nucleus(ctx);
   delete ctx;
   return st;
 }
@@ -388,6 +443,7 @@ dm_status dm_reserve_js(dm_ctx* ctx, int64_t max_positions, int32_t max_K) {
   if (ctx->part_b) (void)hipFree(ctx->part_b);
   ctx->lt = ctx->part_a = ctx->part_b = nullptr;
   ctx->lt_floats = ctx->part_floats = 0;
+  free_nucleus(ctx);
   const size_t K4 = (size_t)round_up(max_K, 4);
   const size_t lt_floats = (size_t)max_positions * (size_t)ctx->max_V * K4;
   const size_t nc = (size_t)((ctx->max_V + dm::kJsChunk - 1) / dm::kJsChunk);
@@ -404,6 +460,19 @@ dm_status dm_reserve_js(dm_ctx* ctx, int64_t max_positions, int32_t max_K) {
   }
   ctx->lt_floats = lt_floats;
   ctx->part_floats = part_floats;
+  // nucleus sampling: 256 digit bins of 8 bytes per row, kept zero between calls
+  const size_t rows = (size_t)max_positions * (size_t)max_K;
+  if ((e = hipMalloc((void**)&ctx->nuc.hist, rows * 256 * 8)) != hipSuccess ||
+      (e = hipMalloc((void**)&ctx->nuc.prefix, rows * 4)) != hipSuccess ||
+      (e = hipMalloc((void**)&ctx->nuc.below, rows * 8)) != hipSuccess ||
+      (e = hipMalloc((void**)&ctx->nuc.target, rows * 8)) != hipSuccess ||
+      (e = hipMalloc((void**)&ctx->nuc.keys_s, rows * 8)) != hipSuccess ||
+      (e = hipMemset(ctx->nuc.hist, 0, rows * 256 * 8)) != hipSuccess) {
+    (void)hipGetLastError();
+    free_nucleus(ctx);
+    return fail(ctx, DM_ENOMEM, "nucleus buffers for %zu rows could not be allocated: %s", rows, hipGetErrorString(e));
+  }
+  ctx->nuc_rows = rows;
   return DM_OK;
 }
 

@@ -155,4 +155,28 @@ __host__ __device__ inline unsigned long long pack_key(float val, uint32_t v) {
   return ((unsigned long long)u << 32) | (unsigned long long)(0xFFFFFFFFu - v);
 }
 
+// Sampled path tokens restricted to the nucleus (top-p set) of Softmax(l / tau), over the stored logits:
+// four histogram + scan levels find each row's threshold exactly, a last pass draws inside it.
+constexpr int kNucChunk = 1024;  // vocabulary rows per workgroup
+constexpr int kNucMaxK = 64;     // paths per row
+struct NucGeom {
+  int P;    // positions B*T
+  int K;    // rows per position in the key arrays
+  int K4;   // floats per (position, vocabulary row) in the store
+  int KP;   // K4 rounded up to a power of two (thread mapping)
+  int KU;   // paths that draw (K, or K-1 when the last path is the clean one)
+  int V;
+};
+struct NucBuffers {
+  unsigned long long* hist;    // [rows][256] masses per digit, zero between calls
+  uint32_t* prefix;            // [rows] bits of the threshold fixed so far
+  unsigned long long* below;   // [rows] mass of the elements below the digits fixed so far
+  unsigned long long* target;  // [rows] mass the nucleus has to reach
+  unsigned long long* keys_s;  // [rows] packed keys of the drawn tokens
+};
+hipError_t launch_nucleus(const float* lt, const unsigned long long* keys, const NucBuffers& nb, const NucGeom& g,
+                          const SampleCfg& samp, float scale, float inv_tau, double top_p, hipStream_t stream);
+hipError_t prepare_nucleus();
+
+
 }  // namespace dm

@@ -26,11 +26,12 @@ class Runner:
             dmb.dm_destroy(self.ctx)
             self.ctx = None
 
-    def params(self, wl, seeds, p=None, step=0, rule=dmb.DM_RULE_ANY, flags=0, parent=None, K=None, temperature=0.0):
+    def params(self, wl, seeds, p=None, step=0, rule=dmb.DM_RULE_ANY, flags=0, parent=None, K=None, temperature=0.0,
+               top_p=0.0):
         dtype = dmb.DM_BF16 if wl.dtype == "bf16" else dmb.DM_F32
         return dmb.make_params(wl.B, wl.T, wl.K if K is None else K, wl.d, wl.V, dtype,
                                wl.p if p is None else p, [int(s) for s in seeds], step=step, rule=rule,
-                               flags=flags, parent=parent, temperature=temperature)
+                               flags=flags, parent=parent, temperature=temperature, top_p=top_p)
 
     def verify(self, wl, h_dev, W_dev, draft, seeds, parent=None, **kw):
         K = kw.get("K") or wl.K

@@ -49,7 +49,9 @@ def test_validate_accepts_the_benchmark_shapes():
                dict(d=8192, V=128256, dtype=dmb.DM_BF16, B=32, T=8, K=16, seeds=list(range(32))),
                dict(d=4096, V=151936, dtype=dmb.DM_BF16, B=4, T=8, K=32, p=0.2, seeds=[1, 2, 3, 4]),
                dict(p=0.0), dict(rule=dmb.DM_RULE_MAJORITY, flags=dmb.DM_FLAG_SHARE_MASK_ACROSS_POS),
-               dict(rule=dmb.DM_RULE_JS, K=5, p=0.3), dict(rule=dmb.DM_RULE_JS_OR_MAJORITY, K=64)):
+               dict(rule=dmb.DM_RULE_JS, K=5, p=0.3), dict(rule=dmb.DM_RULE_JS_OR_MAJORITY, K=64),
+               dict(flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=0.7, top_p=0.9, K=64),
+               dict(flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=0.7, top_p=1.0, K=200), dict(top_p=7.0)):
         prm, keep = _prm(**kw)
         assert dmb.dm_validate(prm) == (dmb.DM_OK, "")
 
@@ -62,6 +64,11 @@ def test_validate_accepts_the_benchmark_shapes():
     (dict(flags=32), "flags"), (dict(flags=dmb.DM_FLAG_SAMPLE_PATHS), "temperature"),
     (dict(flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=float("inf")), "temperature"),
     (dict(flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=1.0, rule=dmb.DM_RULE_JS), "token-level"), (dict(flags=dmb.DM_FLAG_CLEAN_LAST_PATH, K=1), "K >= 2"),
+    (dict(flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=1.0, top_p=1.5), "top_p"),
+    (dict(flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=1.0, top_p=-0.1), "top_p"),
+    (dict(flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=1.0, top_p=float("nan")), "top_p"),
+    (dict(flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=1.0, top_p=0.9, K=65), "K <= 64"),
+    (dict(flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=1.0, top_p=0.9, T=1024, K=16), "T*K"),
 ])
 def test_validate_rejects(kw, word):
     prm, keep = _prm(**kw)

@@ -1,0 +1,168 @@
+"""Sampled path tokens restricted to the nucleus (top-p set), HIP path against the oracle through the C ABI.
+
+The nucleus boundary is decided by a running sum of probabilities and the draw by an arg max of
+perturbed logits; the GPU does both in float32 (masses as 64-bit integers), the oracle in float64.
+What is unique is checked exactly, the rest for validity:
+  * the GPU's token lies inside the largest nucleus the tolerances allow,
+  * it beats (to within the perturbed-value tolerance) every token of the smallest one,
+  * where boundary and winner are clear of the tolerances it IS the oracle's token (counted: most rows),
+  * vote / hit / accepted length follow bit-exactly from the GPU's own path tokens.
+Tolerances: logits carry about 1e-5 absolute error (fp32 accumulation of bf16 products), i.e.
+1e-5 / tau on z = l / tau; the mass fractions inherit a relative error of that size, bounded here by
+MASS_EPS; perturbed values within PERT_TOL * max(1, 1 / tau) count as tied."""
+import numpy as np
+import pytest
+
+from oracle import dropmatch_oracle as orc
+from paper_2603_03333_amd import workloads as wk
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("no GPU", allow_module_level=True)
+
+from paper_2603_03333_amd import binding as dmb  # noqa: E402
+from gpu_harness import Runner, to_device  # noqa: E402
+
+MASS_EPS = 1e-4
+Z_DELTA = 5e-5
+PERT_TOL = 1e-3
+
+
+@pytest.fixture(scope="module")
+def runner():
+    r = Runner(max_rows=2048, max_d=512, max_V=8192)
+    r.reserve_js(max_positions=128, max_K=64)
+    yield r
+    r.close()
+
+
+def check_nucleus_tokens(gpu_ids, logits, seeds, step, tau, top_p, B, T, K, KU):
+    """gpu_ids [B,T,K], logits [B*T*K, V] (oracle, float64).  Returns (#rows, #rows equal to the oracle's draw)."""
+    f = max(1.0, 1.0 / tau)
+    rows = same = 0
+    for b in range(B):
+        for t in range(T):
+            for i in range(KU):
+                z = logits[(b * T + t) * K + i] / tau
+                V = z.size
+                y = z + orc.gumbel_noise(orc.sampling_uniforms(seeds[b], step, t, i, V))
+                q = orc.softmax(z)
+                order = np.argsort(-q, kind="stable")
+                cum = np.cumsum(q[order])
+                n_lo = min(int(np.searchsorted(cum, top_p - MASS_EPS, side="left")) + 1, V)
+                n_hi = min(int(np.searchsorted(cum, top_p + MASS_EPS, side="left")) + 1, V)
+                sure = z >= z[order[n_lo - 1]] + Z_DELTA * f          # inside whatever the rounding does
+                maybe = z >= z[order[n_hi - 1]] - Z_DELTA * f         # the largest set the tolerances allow
+                tok = int(gpu_ids[b, t, i])
+                assert 0 <= tok < V and maybe[tok], f"row ({b},{t},{i}): token {tok} lies outside the nucleus"
+                if sure.any():
+                    assert y[tok] >= y[sure].max() - PERT_TOL * f, f"row ({b},{t},{i}): token {tok} is not the best of the nucleus"
+                want, gap = orc.sampled_token(logits[(b * T + t) * K + i], tau, y - z, top_p)
+                clear = (sure.sum() == maybe.sum()) and gap >= PERT_TOL * f
+                if clear:
+                    assert tok == want, f"row ({b},{t},{i}): {tok} != {want} at a row clear of every tolerance"
+                rows += 1
+                same += int(tok == want)
+    return rows, same
+
+
+def _run(runner, wl, W, h, seeds, draft, tau, top_p, step=0, rule=orc.RULE_ANY, flags=0, parent=None):
+    ref = orc.verify(h, W, draft, seeds, wl.K, wl.p, rule=rule, step=step, parent=parent, temperature=tau, top_p=top_p,
+                     clean_last_path=bool(flags & dmb.DM_FLAG_CLEAN_LAST_PATH), want_logits=(0, wl.V))
+    res = runner.verify(wl, to_device(h, wl.dtype), to_device(W, wl.dtype), draft, seeds, rule=rule, step=step,
+                        flags=flags | dmb.DM_FLAG_SAMPLE_PATHS, parent=parent, temperature=tau, top_p=top_p)
+    KU = wl.K - 1 if flags & dmb.DM_FLAG_CLEAN_LAST_PATH else wl.K
+    rows, same = check_nucleus_tokens(res["path_ids"], ref["logits"], seeds, step, tau, top_p, wl.B, wl.T, wl.K, KU)
+    exp = orc.acceptance_from_path_ids(res["path_ids"][:, :, :KU], draft, rule, parent)
+    for k in ("vote_ids", "vote_cnt", "hit", "accept_mask", "accept_len", "best_node"):
+        assert np.array_equal(res[k], exp[k]), k
+    return ref, res, rows, same
+
+
+@pytest.mark.parametrize("d,V,B,T,K,dtype,tau,top_p", [
+    (256, 3000, 1, 8, 16, "bf16", 1.0, 0.9),     # W-streaming kernel, ragged last vocabulary chunk
+    (256, 4096, 2, 6, 16, "bf16", 0.7, 0.5),     # 256 x 256 tiles
+    (100, 130, 2, 3, 5, "f32", 1.5, 0.8),        # generic kernel, K not a multiple of 4
+    (128, 777, 1, 3, 12, "bf16", 0.25, 0.95),    # K4 = 12: thread mapping padded to 16 paths
+    (64, 2049, 3, 2, 33, "bf16", 1.0, 0.3),      # 33 paths: 64-wide mapping, one vocabulary row past a chunk
+    (128, 1500, 1, 4, 64, "bf16", 2.0, 0.99),    # the most paths the variant takes
+])
+def test_nucleus_tokens_flat_distributions(runner, d, V, B, T, K, dtype, tau, top_p):
+    wl = wk.Workload("nuc", d=d, V=V, dtype=dtype, B=B, T=T, K=K, p=0.2, bonus=True, data_seed=d + V + K)
+    W, h = wk.make_weight(wl), wk.make_hidden(wl)
+    seeds = wk.make_seeds(wl, base_seed=23)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    for rule, step in ((orc.RULE_ANY, 0), (orc.RULE_MAJORITY, 9)):
+        ref, res, rows, same = _run(runner, wl, W, h, seeds, draft, tau, top_p, step=step, rule=rule)
+        print(f"[nucleus {dtype} M={B*T*K} V={V} tau={tau} top_p={top_p}] rows={rows} equal to the oracle's draw={same}", flush=True)
+        assert same >= 0.9 * rows
+
+
+def test_nucleus_tokens_peaked_distributions(runner):
+    """Planted dominant tokens (the shape of a real LM's next-token distribution): small nuclei."""
+    wl = wk.Workload("nucp", d=256, V=4096, dtype="bf16", B=2, T=6, K=8, p=0.1, bonus=False, data_seed=77)
+    W = wk.make_weight(wl, sigma=0.1)
+    h, planted = wk.make_planted_hidden(wl, W, alpha=9.0)
+    seeds = wk.make_seeds(wl, base_seed=3)
+    draft = planted.copy()
+    for top_p in (0.5, 0.9):
+        ref, res, rows, same = _run(runner, wl, W, h, seeds, draft, 1.0, top_p)
+        sizes = [int(orc.nucleus(ref["logits"][r], top_p)[0].sum()) for r in range(0, rows, 7)]
+        print(f"[nucleus peaked top_p={top_p}] rows={rows} equal={same} nucleus sizes (sample)={sizes[:8]}", flush=True)
+        assert same >= 0.9 * rows and max(sizes) < wl.V // 4
+
+
+def test_nucleus_limits_and_options(runner):
+    wl = wk.Workload("nucl", d=128, V=1000, dtype="bf16", B=2, T=5, K=8, p=0.3, bonus=True, data_seed=5)
+    W, h = wk.make_weight(wl, sigma=0.05), wk.make_hidden(wl)
+    seeds = wk.make_seeds(wl, base_seed=11)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    flag = dmb.DM_FLAG_SAMPLE_PATHS
+    plain = runner.verify(wl, hd, Wd, draft, seeds)
+    free = runner.verify(wl, hd, Wd, draft, seeds, flags=flag, temperature=0.9)
+    # top_p = 1 and 0 are the unrestricted draw (the same code path), a vanishing top_p is the arg max
+    for tp in (1.0, 0.0):
+        assert np.array_equal(runner.verify(wl, hd, Wd, draft, seeds, flags=flag, temperature=0.9, top_p=tp)["path_ids"],
+                              free["path_ids"])
+    tiny = runner.verify(wl, hd, Wd, draft, seeds, flags=flag, temperature=0.9, top_p=1e-7)
+    assert np.array_equal(tiny["path_ids"], plain["path_ids"])
+    # all but a sliver of the mass: nearly always the unrestricted draw, and never an invalid token
+    wide = runner.verify(wl, hd, Wd, draft, seeds, flags=flag, temperature=0.9, top_p=0.99999)
+    assert (wide["path_ids"] == free["path_ids"]).mean() > 0.95
+    # reproducible, also right after a call with other parameters
+    a = runner.verify(wl, hd, Wd, draft, seeds, flags=flag, temperature=0.9, top_p=0.6)
+    runner.verify(wl, hd, Wd, draft, seeds, flags=flag, temperature=0.5, top_p=0.2, step=3)
+    b = runner.verify(wl, hd, Wd, draft, seeds, flags=flag, temperature=0.9, top_p=0.6)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    # a clean last path keeps its arg max and stays out of the rules; a tree works like a chain
+    _run(runner, wl, W, h, seeds, draft, 0.9, 0.6, flags=dmb.DM_FLAG_CLEAN_LAST_PATH)
+    c = runner.verify(wl, hd, Wd, draft, seeds, flags=flag | dmb.DM_FLAG_CLEAN_LAST_PATH, temperature=0.9, top_p=0.6)
+    assert np.array_equal(c["path_ids"][:, :, -1], orc.greedy_ids(h, W))
+    wt = wl.with_(tree=True, bonus=False)
+    parent = wk.make_tree_parents(wt, max_depth=3, max_branch=2)
+    _run(runner, wt, W, h, seeds, wk.make_tree_draft_ids(wt, parent, orc.greedy_ids(h, W)), 0.9, 0.6, parent=parent,
+         rule=orc.RULE_MAJORITY)
+
+
+def test_nucleus_needs_the_reserved_store():
+    r = Runner(max_rows=64, max_d=64, max_V=64)
+    try:
+        wl = wk.Workload("nucr", d=64, V=64, dtype="bf16", B=1, T=2, K=4, p=0.1, data_seed=1)
+        W, h = wk.make_weight(wl), wk.make_hidden(wl)
+        seeds, draft = wk.make_seeds(wl), np.zeros((1, 2), dtype=np.int32)
+        with pytest.raises(dmb.DropMatchError, match="dm_reserve_js"):
+            r.verify(wl, to_device(h, "bf16"), to_device(W, "bf16"), draft, seeds, flags=dmb.DM_FLAG_SAMPLE_PATHS,
+                     temperature=1.0, top_p=0.5)
+        r.reserve_js(max_positions=1, max_K=4)
+        with pytest.raises(dmb.DropMatchError, match="exceed"):
+            r.verify(wl, to_device(h, "bf16"), to_device(W, "bf16"), draft, seeds, flags=dmb.DM_FLAG_SAMPLE_PATHS,
+                     temperature=1.0, top_p=0.5)
+        r.reserve_js(max_positions=2, max_K=4)
+        r.verify(wl, to_device(h, "bf16"), to_device(W, "bf16"), draft, seeds, flags=dmb.DM_FLAG_SAMPLE_PATHS,
+                 temperature=1.0, top_p=0.5)
+    finally:
+        r.close()
