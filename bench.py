@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--p-drop", type=float, default=-1.0, help="override the dropout probability p (bigvocab sweep)")
     ap.add_argument("--temperature", type=float, default=0.0,
                     help="> 0: path tokens sampled from Softmax(l / temperature) instead of the arg max")
+    ap.add_argument("--top-p", type=float, default=0.0,
+                    help="with --temperature: 0 < top-p < 1 samples from the nucleus of that distribution only")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of a HIP graph that holds one captured step instead of eager calls")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (for profiler runs)")
@@ -57,7 +59,7 @@ def read_traffic(workload):
     return None
 
 
-def cpu_baseline(wl, W, h, draft, seeds, parent, probs=None, rule=0):
+def cpu_baseline(wl, W, h, draft, seeds, parent, probs=None, rule=0, temperature=None, top_p=None):
     """The oracle, as it stands, on the first rows of sequence 0 of the same inputs."""
     import numpy as np
     from oracle import dropmatch_oracle as orc
@@ -75,7 +77,7 @@ def cpu_baseline(wl, W, h, draft, seeds, parent, probs=None, rule=0):
                                 rule=rule)
         else:
             out = orc.verify(h[:1, :n_pos], W, draft[:1, :n_pos], seeds[:1], wl.K, wl.p, rule=rule,
-                             parent=None if parent is None else parent[:1, :n_pos])
+                             parent=None if parent is None else parent[:1, :n_pos], temperature=temperature, top_p=top_p)
         total += time.perf_counter() - t0
         reps += 1
         assert out["path_ids"].shape == (1, n_pos, wl.K)
@@ -155,12 +157,16 @@ def main():
         del clean
 
     ctx = dmb.dm_create(0, wl.rows, wl.d, wl.V)
-    if js:
+    nucleus = args.temperature > 0 and 0.0 < args.top_p < 1.0
+    if nucleus and js:
+        print("bench.py: sampled path tokens go with the token-level rules", file=sys.stderr)
+        sys.exit(2)
+    if js or nucleus:
         dmb.dm_reserve_js(ctx, wl.B * wl.T, wl.K)
     prm, keep = dmb.make_params(wl.B, wl.T, wl.K, wl.d, wl.V, dmb.DM_BF16 if bf16 else dmb.DM_F32, wl.p,
                                 [int(s) for s in seeds], parent=parent_dev, rule=rule,
                                 flags=dmb.DM_FLAG_SAMPLE_PATHS if args.temperature > 0 else 0,
-                                temperature=args.temperature)
+                                temperature=args.temperature, top_p=args.top_p)
     kernel = dmb.dm_kernel_choice(prm)
     out = dict(accept_len=torch.zeros(wl.B, dtype=torch.int32, device="cuda"),
                best_node=torch.zeros(wl.B, dtype=torch.int32, device="cuda"),
@@ -245,7 +251,7 @@ def main():
     else:
         m_pad = (M + 127) // 128 * 128
     alg_bytes = wl.V * wl.d * esize + m_pad * wl.d * esize + M * 8
-    if js:                                   # the contraction also writes every logit once for Eq. (5)/(6)
+    if js or nucleus:                        # the contraction also writes every logit once (Eq. (5)/(6), nucleus)
         alg_bytes += M * wl.V * 4
     alg_flops = 2.0 * M * wl.d * wl.V
     sec = ms_lm * 1e-3
@@ -268,6 +274,12 @@ def main():
         roof["js_passes"] = {"bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBS,
                              "js_stats_achieved": pass_bytes / (ms_js1 * 1e-3) / 1e9,
                              "js_terms_achieved": (pass_bytes + wl.B * wl.T * wl.V * 4) / (ms_js2 * 1e-3) / 1e9}
+    if nucleus:
+        k4 = (wl.K + 3) // 4 * 4
+        pass_bytes = wl.B * wl.T * wl.V * 4 * k4          # stored logits read once per pass, five passes
+        roof["other_kernels_ms"]["nucleus_passes"] = ms_js1
+        roof["nucleus"] = {"bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBS, "passes": 5,
+                           "achieved": 5 * pass_bytes / (ms_js1 * 1e-3) / 1e9}
     roof["events_over_calls"] = n_calls
     roof["kernel_ms_source"] = (f"HIP events on the launch, every {EVENT_STRIDE}th timed step" if live
                                 else "HIP events on the stream, pass after the timed region")
@@ -284,11 +296,14 @@ def main():
                                + (" tree" if wl.tree else " chain") + (" +bonus row" if wl.bonus else ""),
                    "rows": M, "positions_per_step": positions, "rule": args.rule,
                    "launch": "hip graph replay" if args.graph else "eager",
-                   "path_tokens": f"sampled, temperature {args.temperature}" if args.temperature > 0 else "arg max"},
+                   "path_tokens": (f"sampled, temperature {args.temperature}"
+                                   + (f", nucleus top-p {args.top_p}" if nucleus else "")) if args.temperature > 0 else "arg max"},
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, W, h, draft, seeds, parent, probs, rule)
+        result["cpu_baseline"] = cpu_baseline(wl, W, h, draft, seeds, parent, probs, rule,
+                                              args.temperature if args.temperature > 0 else None,
+                                              args.top_p if nucleus else None)
     dmb.dm_destroy(ctx)
     print(json.dumps(result), flush=True)
 

@@ -242,7 +242,8 @@ dm_status dm_debug_logits(dm_ctx* ctx, const dm_params* prm, const void* h, cons
  * in milliseconds (any output pointer may be NULL); dm_get_profile_stages returns all five
  * stage means in ms[0..4] = mask rows, LM head, JS pass 1, JS pass 2, vote/accept (a stage
  * that launched no kernel in a call counts 0 for that call: the JS passes of dropmatch_verify,
- * the vote/accept stage when that step ran inside the LM-head launch).  dm_set_profiling(ctx, 2) times only the LM-head contraction
+ * the vote/accept stage when that step ran inside the LM-head launch; with nucleus sampling
+ * ms[2] is the time of all its passes together).  dm_set_profiling(ctx, 2) times only the LM-head contraction
  * kernel, with two events that take the begin and end timestamps of that launch itself (events
  * recorded on the stream around a launch also span the dispatch gap in front of the kernel); the
  * other stage means then read 0.  This is the way to time the dominant kernel inside a timed loop.  dm_set_profiling(ctx, 0) stops recording and forgets

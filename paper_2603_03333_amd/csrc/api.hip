@@ -34,7 +34,8 @@ struct dm_ctx {
   hipEvent_t* ev = nullptr;
   int prof_enabled = 0;
   int prof_calls = 0;
-  uint8_t prof_kind[DM_PROFILE_MAX_CALLS] = {};  // per recorded call: bit 0 = JS passes ran, bit 1 = separate vote kernel ran
+  // per recorded call: bit 0 = stage 2 ran (JS pass 1, or all nucleus passes), bit 1 = separate vote kernel, bit 2 = JS pass 2
+  uint8_t prof_kind[DM_PROFILE_MAX_CALLS] = {};
   int prof_stride = 1;  // events are recorded on every prof_stride-th verify call
   int prof_seen = 0;    // verify calls since profiling was switched on
 };
@@ -315,7 +316,7 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
   }
   if (ev) {
     if (all_stages) (void)hipEventRecord(ev[5], s);
-    ctx->prof_kind[ctx->prof_calls] = (uint8_t)(((js || nucleus) ? 1 : 0) | (fused ? 0 : 2));
+    ctx->prof_kind[ctx->prof_calls] = (uint8_t)(((js || nucleus) ? 1 : 0) | (fused ? 0 : 2) | (js ? 4 : 0));
     ++ctx->prof_calls;
   }
   return DM_OK;
@@ -519,7 +520,8 @@ dm_status dm_get_profile_stages(dm_ctx* ctx, int32_t* n_calls, float* ms /* [5] 
     for (int c = 0; c < n; ++c)
       for (int k = light ? 1 : 0; k < (light ? 2 : kEv - 1); ++k) {
         // a bracket with no kernel inside would read the cost of an event pair (a few microseconds)
-        if ((k == 2 || k == 3) && !(ctx->prof_kind[c] & 1)) continue;
+        if (k == 2 && !(ctx->prof_kind[c] & 1)) continue;
+        if (k == 3 && !(ctx->prof_kind[c] & 4)) continue;
         if (k == 4 && !(ctx->prof_kind[c] & 2)) continue;
         float t = 0.f;
         e = hipEventElapsedTime(&t, ctx->ev[kEv * c + k], ctx->ev[kEv * c + k + 1]);

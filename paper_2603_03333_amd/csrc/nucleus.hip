@@ -28,9 +28,13 @@
 namespace dm {
 namespace {
 
-constexpr int NT = 256;          // threads per workgroup
+constexpr int NT = 256;          // threads per workgroup (scan, draw)
+constexpr int HT = 1024;         // threads per workgroup of the histogram passes
+constexpr int kHistChunk = 4096; // vocabulary rows per histogram workgroup: every workgroup ends with up to
+                                 // 256 atomic adds to memory per path, so few large ones are cheaper
 constexpr int kBins = 256;       // 8 bits per level
 constexpr float kMassScale = 17592186044416.0f;  // 2^44
+constexpr int kNucBatch = 8;     // vocabulary rows a thread has in flight
 
 __device__ __forceinline__ float nkey_logit(unsigned long long key) {
   uint32_t u = (uint32_t)(key >> 32);
@@ -41,13 +45,19 @@ __device__ __forceinline__ float nkey_logit(unsigned long long key) {
 // distance of a stored logit from its row's maximum in units of tau; the same expression in every pass
 __device__ __forceinline__ float dist_t(float lmax, float l, float inv_tau) { return (lmax - l) * inv_tau; }
 
+// floor(e^-t * 2^44).  The product is a float with 24 significant bits below 2^45, so it splits
+// exactly into a multiple of 2^20 and a remainder below 2^20: two 32-bit conversions instead of the
+// long software sequence of a float -> 64-bit integer conversion.
 __device__ __forceinline__ unsigned long long mass_of(float t) {
-  return (unsigned long long)(__builtin_amdgcn_exp2f(-t * 1.44269504088896341f) * kMassScale);
+  const float m = __builtin_amdgcn_exp2f(-t * 1.44269504088896341f) * kMassScale;
+  const uint32_t hi = (uint32_t)(m * 9.5367431640625e-07f);        // m / 2^20, truncated
+  const uint32_t lo = (uint32_t)(m - (float)hi * 1048576.0f);       // exact remainder
+  return ((unsigned long long)hi << 20) + lo;
 }
 
 // LEVEL 0..3: digit = bits [31-8*LEVEL .. 24-8*LEVEL] of t.
 template <int LEVEL>
-__global__ __launch_bounds__(NT) void nucleus_hist_kernel(const float* __restrict__ lt,
+__global__ __launch_bounds__(HT) void nucleus_hist_kernel(const float* __restrict__ lt,
                                                           const unsigned long long* __restrict__ keys,
                                                           const uint32_t* __restrict__ prefix,
                                                           unsigned long long* __restrict__ ghist, NucGeom g,
@@ -56,28 +66,51 @@ __global__ __launch_bounds__(NT) void nucleus_hist_kernel(const float* __restric
   const int pos = blockIdx.x, c = blockIdx.y;
   const int tid = threadIdx.x;
   constexpr int shift = 24 - 8 * LEVEL;
-  for (int x = tid; x < g.KP * kBins; x += NT) hist[x] = 0ull;
+  for (int x = tid; x < g.KP * kBins; x += HT) hist[x] = 0ull;
   __syncthreads();
 
   const int i = tid % g.KP;            // path of this thread (KP: K4 rounded up to a power of two, divides 256)
-  const int vstep = NT / g.KP;         // vocabulary rows per sweep of the workgroup
+  const int vstep = HT / g.KP;         // vocabulary rows per sweep of the workgroup
   const bool live = i < g.KU;
   const int64_t row = (int64_t)pos * g.K + i;
   const float lmax = live ? scale * nkey_logit(keys[row]) : 0.f;
   const uint32_t pre = (LEVEL > 0 && live) ? prefix[row] : 0u;
   const float* base = lt + (int64_t)pos * g.V * g.K4 + i;
-  const int v_end = min(g.V, (c + 1) * kNucChunk);
+  const int v_end = min(g.V, (c + 1) * kHistChunk);
   if (live) {
-    for (int v = c * kNucChunk + tid / g.KP; v < v_end; v += vstep) {
-      const float t = dist_t(lmax, base[(int64_t)v * g.K4], inv_tau);
-      const uint32_t key = __float_as_uint(t);
-      if (LEVEL > 0 && (key >> (shift + 8)) != (pre >> (shift + 8))) continue;
-      const unsigned long long m = mass_of(t);
-      if (m != 0ull) atomicAdd(&hist[i * kBins + ((key >> shift) & 255u)], m);
+    // the pass is bound by load latency unless many loads are in flight: kNucBatch rows are fetched
+    // before the first is used (rows past the end re-read the last row and are skipped)
+    for (int v0 = c * kHistChunk + tid / g.KP; v0 < v_end; v0 += kNucBatch * vstep) {
+      float x[kNucBatch];
+#pragma unroll
+      for (int u = 0; u < kNucBatch; ++u) {
+        const int v = v0 + u * vstep;
+        x[u] = base[(int64_t)(v < v_end ? v : v_end - 1) * g.K4];
+      }
+      // LDS takes 64-bit atomics a lane at a time, so masses that fall into the bin of the element
+      // before them (most do at the first level) are added up in registers first
+      uint32_t run_bin = 0u;
+      unsigned long long run_mass = 0ull;
+#pragma unroll
+      for (int u = 0; u < kNucBatch; ++u) {
+        if (v0 + u * vstep >= v_end) break;
+        const float t = dist_t(lmax, x[u], inv_tau);
+        const uint32_t key = __float_as_uint(t);
+        if (LEVEL > 0 && (key >> (shift + 8)) != (pre >> (shift + 8))) continue;
+        const unsigned long long m = mass_of(t);
+        const uint32_t bin = (key >> shift) & 255u;
+        if (bin != run_bin && run_mass != 0ull) {
+          atomicAdd(&hist[i * kBins + run_bin], run_mass);
+          run_mass = 0ull;
+        }
+        run_bin = bin;
+        run_mass += m;
+      }
+      if (run_mass != 0ull) atomicAdd(&hist[i * kBins + run_bin], run_mass);
     }
   }
   __syncthreads();
-  for (int x = tid; x < g.KU * kBins; x += NT) {
+  for (int x = tid; x < g.KU * kBins; x += HT) {
     const unsigned long long m = hist[x];
     if (m != 0ull) atomicAdd(&ghist[((int64_t)pos * g.K + x / kBins) * kBins + (x % kBins)], m);
   }
@@ -171,25 +204,35 @@ __global__ __launch_bounds__(NT) void nucleus_draw_kernel(const float* __restric
     const RowRng rng = make_row_rng(samp, row, (int64_t)g.P * g.K);
     const float* base = lt + (int64_t)pos * g.V * g.K4 + i;
     const int v_end = min(g.V, (c + 1) * kNucChunk);
-    for (int v4 = c * kNucChunk + 4 * slot; v4 < v_end; v4 += 4 * nslot) {
-      float l[4];
-      bool in[4];
-      bool any = false;
+    constexpr int NB = 4;  // blocks of four rows in flight per thread
+    for (int vb = c * kNucChunk + 4 * slot; vb < v_end; vb += NB * 4 * nslot) {
+      float l[NB][4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int v = v4 + e;
-        l[e] = v < v_end ? base[(int64_t)v * g.K4] : 0.f;
-        in[e] = v < v_end && __float_as_uint(dist_t(lmax, l[e], inv_tau)) <= tmax;
-        any |= in[e];
-      }
-      if (!any) continue;
-      float gn[4];
-      gumbel4(rng, (uint32_t)v4, samp.step, gn);
+      for (int u = 0; u < NB; ++u)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        if (!in[e]) continue;
-        const unsigned long long k = pack_key(fmaf(l[e], inv_tau, gn[e]) + 0.0f, (uint32_t)(v4 + e));
-        best = k > best ? k : best;
+        for (int e = 0; e < 4; ++e) {
+          const int v = vb + u * 4 * nslot + e;
+          l[u][e] = base[(int64_t)(v < v_end ? v : v_end - 1) * g.K4];
+        }
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        const int v4 = vb + u * 4 * nslot;
+        bool in[4];
+        bool any = false;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          in[e] = v4 + e < v_end && __float_as_uint(dist_t(lmax, l[u][e], inv_tau)) <= tmax;
+          any |= in[e];
+        }
+        if (!any) continue;
+        float gn[4];
+        gumbel4(rng, (uint32_t)v4, samp.step, gn);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (!in[e]) continue;
+          const unsigned long long k = pack_key(fmaf(l[u][e], inv_tau, gn[e]) + 0.0f, (uint32_t)(v4 + e));
+          best = k > best ? k : best;
+        }
       }
     }
   } else if (i < g.K && slot == 0 && c == 0) {
@@ -229,13 +272,15 @@ hipError_t launch_nucleus(const float* lt, const unsigned long long* keys, const
       g.V < 1)
     return hipErrorInvalidValue;
   const int NC = (g.V + kNucChunk - 1) / kNucChunk;
+  const int NH = (g.V + kHistChunk - 1) / kHistChunk;
   if (NC > 65535) return hipErrorInvalidValue;
   const dim3 grid((unsigned)g.P, (unsigned)NC), block(NT);
+  const dim3 hgrid((unsigned)g.P, (unsigned)NH), hblock(HT);
   const size_t hist_lds = (size_t)g.KP * kBins * 8;
   const int64_t rows = (int64_t)g.P * g.K;
   const dim3 sgrid((unsigned)((rows + NT / 64 - 1) / (NT / 64)));
 #define DM_NUC_LEVEL(L)                                                                                        \
-  nucleus_hist_kernel<L><<<grid, block, hist_lds, stream>>>(lt, keys, nb.prefix, nb.hist, g, scale, inv_tau);   \
+  nucleus_hist_kernel<L><<<hgrid, hblock, hist_lds, stream>>>(lt, keys, nb.prefix, nb.hist, g, scale, inv_tau); \
   nucleus_scan_kernel<L><<<sgrid, block, 0, stream>>>(nb.hist, nb.prefix, nb.below, nb.target, nb.keys_s, g, top_p)
   DM_NUC_LEVEL(0);
   DM_NUC_LEVEL(1);
