@@ -211,3 +211,42 @@ def test_head8b_sampled_tokens_on_sampled_rows():
     exp = orc.acceptance_from_path_ids(res["path_ids"], draft, orc.RULE_ANY)
     for k in ("vote_ids", "vote_cnt", "hit", "accept_len"):
         assert np.array_equal(res[k], exp[k]), k
+
+
+def test_head8b_nucleus_tokens_on_sampled_rows():
+    """Top-p draws at the full head8b size (126 chunks of vocabulary rows per position in the launch
+    configuration bench.py times): two positions, all 16 paths, checked as in test_gpu_nucleus.py."""
+    from test_gpu_nucleus import check_nucleus_tokens
+    wl = wk.CONFIGS["head8b"]
+    tau, top_p = 0.8, 0.9
+    W, h, seeds = wk.make_weight(wl), wk.make_hidden(wl), wk.make_seeds(wl)
+    draft = wk.make_draft_ids(wl, None)
+    r = Runner(wl.rows, wl.d, wl.V)
+    try:
+        r.reserve_js(wl.B * wl.T, wl.K)
+        hd, Wd = to_device(h, wl.dtype), to_device(W, wl.dtype)
+        kw = dict(flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=tau, top_p=top_p)
+        res = r.verify(wl, hd, Wd, draft, seeds, **kw)
+        res2 = r.verify(wl, hd, Wd, draft, seeds, **kw)
+        assert np.array_equal(res["path_ids"], res2["path_ids"])
+        free = r.verify(wl, hd, Wd, draft, seeds, flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=tau)
+        del hd, Wd
+    finally:
+        r.close()
+    torch.cuda.empty_cache()
+    W64 = W.astype(np.float64)
+    rows = same = 0
+    for t in (1, 6):
+        Hm = np.stack([orc.masked_state(h[0, t], orc.keep_mask(int(seeds[0]), 0, t, i, wl.d, wl.p), wl.p)
+                       for i in range(wl.K)])
+        L = (W64 @ Hm.T).T                                # [K, V]
+        # check_nucleus_tokens indexes logits by (b*T + t)*K + i: give it a one-position problem
+        n, s = check_nucleus_tokens(res["path_ids"][:, t:t + 1], L, [int(seeds[0])], 0, tau, top_p, 1, 1, wl.K, wl.K, t0=t)
+        rows += n
+        same += s
+    print(f"[head8b/nucleus] rows={rows} equal to the oracle's draw={same} "
+          f"differ from the unrestricted draw={(res['path_ids'] != free['path_ids']).sum()} of {res['path_ids'].size}", flush=True)
+    assert same >= 0.9 * rows
+    exp = orc.acceptance_from_path_ids(res["path_ids"], draft, orc.RULE_ANY)
+    for k in ("vote_ids", "vote_cnt", "hit", "accept_len"):
+        assert np.array_equal(res[k], exp[k]), k

@@ -38,8 +38,9 @@ def runner():
     r.close()
 
 
-def check_nucleus_tokens(gpu_ids, logits, seeds, step, tau, top_p, B, T, K, KU):
-    """gpu_ids [B,T,K], logits [B*T*K, V] (oracle, float64).  Returns (#rows, #rows equal to the oracle's draw)."""
+def check_nucleus_tokens(gpu_ids, logits, seeds, step, tau, top_p, B, T, K, KU, t0=0):
+    """gpu_ids [B,T,K], logits [B*T*K, V] (oracle, float64); t0: position of row 0 in the call the
+    tokens come from (the noise is keyed on it).  Returns (#rows, #rows equal to the oracle's draw)."""
     f = max(1.0, 1.0 / tau)
     rows = same = 0
     for b in range(B):
@@ -47,7 +48,7 @@ def check_nucleus_tokens(gpu_ids, logits, seeds, step, tau, top_p, B, T, K, KU):
             for i in range(KU):
                 z = logits[(b * T + t) * K + i] / tau
                 V = z.size
-                y = z + orc.gumbel_noise(orc.sampling_uniforms(seeds[b], step, t, i, V))
+                y = z + orc.gumbel_noise(orc.sampling_uniforms(seeds[b], step, t0 + t, i, V))
                 q = orc.softmax(z)
                 order = np.argsort(-q, kind="stable")
                 cum = np.cumsum(q[order])
