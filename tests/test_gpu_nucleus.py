@@ -167,3 +167,55 @@ def test_nucleus_needs_the_reserved_store():
                  temperature=1.0, top_p=0.5)
     finally:
         r.close()
+
+
+@pytest.fixture(scope="module")
+def small_runner():
+    r = Runner(max_rows=1024, max_d=512, max_V=4096)
+    r.reserve_js(max_positions=64, max_K=64)
+    yield r
+    r.close()
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_random_nucleus_case(small_runner, case):
+    """Seeded random shapes and options: vocabularies from 1 token up, 1 to 64 paths, both storage types,
+    flat and peaked distributions, top_p from 1e-6 to 0.999, clean last path, shared masks."""
+    rng = np.random.default_rng(52000 + case)
+    bf16 = rng.random() < 0.75
+    d = int(rng.choice([64, 128, 192, 256, 512])) if (bf16 and rng.random() < 0.8) else int(rng.integers(5, 200))
+    V = int(rng.choice([1, 2, 3, 7, 255, 256, 257, 1000, 2049, 4096]) if rng.random() < 0.5 else rng.integers(2, 3000))
+    K = int(rng.choice([1, 2, 3, 5, 8, 12, 16, 17, 32, 40, 64]))
+    T = int(rng.integers(1, 10))
+    B = int(rng.integers(1, 5))
+    while B * T * K > 1024 or B * T > 64:
+        T = max(1, T - 1)
+        B = max(1, B - 1)
+    p = float(rng.choice([0.0, 0.1, 0.3, 0.5]))
+    tau = float(rng.choice([0.3, 0.8, 1.0, 2.0]))
+    top_p = float(rng.choice([1e-6, 0.05, 0.3, 0.5, 0.8, 0.9, 0.95, 0.999]))
+    clean = K >= 2 and rng.random() < 0.3
+    peaked = rng.random() < 0.4
+    dtype = "bf16" if bf16 else "f32"
+    wl = wk.Workload(f"n{case}", d=d, V=V, dtype=dtype, B=B, T=T, K=K, p=p, bonus=bool(rng.integers(0, 2)),
+                     data_seed=33000 + case)
+    W = wk.make_weight(wl, sigma=0.1)
+    h = wk.make_planted_hidden(wl, W, alpha=8.0)[0] if peaked else wk.make_hidden(wl)
+    seeds = rng.integers(0, 2 ** 63, size=B, dtype=np.uint64)
+    step = int(rng.integers(0, 2 ** 32))
+    rule = int(rng.integers(0, 2))
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    flags = (dmb.DM_FLAG_CLEAN_LAST_PATH if clean else 0) | (dmb.DM_FLAG_FORCE_GENERIC if rng.random() < 0.2 else 0) | \
+            (dmb.DM_FLAG_SHARE_MASK_ACROSS_POS if rng.random() < 0.3 else 0)
+    ref = orc.verify(h, W, draft, seeds, K, p, rule=rule, step=step, temperature=tau, top_p=top_p, clean_last_path=clean,
+                     share_mask_across_pos=bool(flags & dmb.DM_FLAG_SHARE_MASK_ACROSS_POS), want_logits=(0, V))
+    res = small_runner.verify(wl, to_device(h, dtype), to_device(W, dtype), draft, seeds, rule=rule, step=step,
+                              flags=flags | dmb.DM_FLAG_SAMPLE_PATHS, temperature=tau, top_p=top_p)
+    KU = K - 1 if clean else K
+    rows, same = check_nucleus_tokens(res["path_ids"], ref["logits"], seeds, step, tau, top_p, B, T, K, KU)
+    exp = orc.acceptance_from_path_ids(res["path_ids"][:, :, :KU], draft, rule, None)
+    for k in ("vote_ids", "vote_cnt", "hit", "accept_mask", "accept_len", "best_node"):
+        assert np.array_equal(res[k], exp[k]), f"case {case}: {k}"
+    if clean:
+        assert np.array_equal(res["path_ids"][:, :, -1], orc.greedy_ids(h, W))
+    assert same >= 0.9 * rows, f"case {case}: only {same} of {rows} rows equal the oracle's draw"
