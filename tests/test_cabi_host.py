@@ -115,3 +115,24 @@ def test_tree_inputs_for_a_vocabulary_smaller_than_a_sibling_group():
     ids = wk.make_tree_draft_ids(wl, parent, greedy=np.zeros((2, 9), dtype=np.int32))
     assert (ids[:, 0] == -1).all() and (ids[:, 1:] == 0).all()
     assert (parent[:, 1:] < np.arange(1, 9)[None, :]).all() and (parent[:, 0] == -1).all()
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 with a plain C compiler, warnings on,
+    and every declared function must be usable from C (address taken, nothing linked)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = open(os.path.join(ROOT, "include", "dropmatch.h")).read()
+    names = sorted(set(re.findall(r"\b(dm_[a-z_]+|dropmatch_[a-z_]+)\s*\(", src)) & set(dmb.EXPORTS))
+    assert names == sorted(dmb.EXPORTS)
+    c = tmp_path / "use_header.c"
+    c.write_text('#include "dropmatch.h"\n#include <stddef.h>\n'
+                 "int main(void) {\n  dm_params p;\n  const void* f[] = {" +
+                 ", ".join(f"(const void*)(size_t)&{n}" for n in names) +
+                 "};\n  p.top_p = 0.0f; p.temperature = 0.0f;\n  return (int)(sizeof f / sizeof f[0]) * 0 + (int)p.top_p;\n}\n")
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-fsyntax-only",
+                        "-I", os.path.join(ROOT, "include"), str(c)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
