@@ -125,7 +125,8 @@ typedef struct {
 
 /* Create a context on HIP device `device` able to serve calls with B*T*K <= max_rows,
  * d <= max_d, V <= max_V.  Allocates the workspace (masked rows: max_rows rounded up to
- * 256 times max_d rounded up to 64 elements of 4 bytes, plus 16 bytes per row).  The context
+ * 256 times max_d rounded up to 64 elements of 4 bytes, plus 16 bytes per row; for max_rows > 128
+ * also 256 KB per compute unit, 64 MB on an MI355X, for the noise of sampled path tokens).  The context
  * may be used from one host thread at a time; calls on one context must be enqueued on
  * one stream (or be ordered by the caller), since they share the workspace. */
 dm_status dm_create(dm_ctx** out, int device, int64_t max_rows, int32_t max_d, int32_t max_V);

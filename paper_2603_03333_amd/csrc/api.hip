@@ -20,6 +20,7 @@ struct dm_ctx {
   unsigned long long* keys = nullptr; // packed (logit, index) argmax per row
   unsigned int* done = nullptr;       // workgroups done, for the acceptance step fused into the contraction
   uint64_t* seeds_dev = nullptr;      // seeds of the current call, for the sampling epilogues
+  float* noise = nullptr;             // Gumbel noise of one tile per workgroup of the 256 x 256 kernel
   // distribution-level rule (dm_reserve_js): stored logits and per-chunk partial sums
   float* lt = nullptr;
   size_t lt_floats = 0;
@@ -183,7 +184,7 @@ dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g,
     at.stop = ev[2];
   }
   const float scale = (float)(1.0 / (1.0 - (double)p->p));
-  dm::SampleCfg samp{nullptr, 0.f, p->T, p->K, p->step, g.clean_last};
+  dm::SampleCfg samp{nullptr, 0.f, p->T, p->K, p->step, g.clean_last, ctx->noise};
   if (sample) {
     samp.seeds = ctx->seeds_dev;
     samp.zscale = (float)(1.0 / (1.0 - (double)p->p) / (double)p->temperature);
@@ -297,7 +298,7 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
     if (ev && all_stages) (void)hipEventRecord(ev[4], s);
   } else if (nucleus) {
     const float scale = (float)(1.0 / (1.0 - (double)prm->p));
-    const dm::SampleCfg samp{ctx->seeds_dev, 0.f, prm->T, prm->K, prm->step, g.clean_last};
+    const dm::SampleCfg samp{ctx->seeds_dev, 0.f, prm->T, prm->K, prm->step, g.clean_last, nullptr};
     e = dm::launch_nucleus(ctx->lt, ctx->keys, ctx->nuc, ng, samp, scale, (float)(1.0 / (double)prm->temperature),
                            (double)prm->top_p, s);
     if (e != hipSuccess) return fail_hip(ctx, "nucleus launch", e);
@@ -370,12 +371,17 @@ dm_status dm_create(dm_ctx** out, int device, int64_t max_rows, int32_t max_d, i
   if ((e = hipMalloc(&ctx->a_ws, a_bytes)) != hipSuccess ||
       (e = hipMalloc((void**)&ctx->keys, (size_t)ctx->rows_pad * 8)) != hipSuccess ||
       (e = hipMalloc((void**)&ctx->done, 256)) != hipSuccess || (e = hipMemset(ctx->done, 0, 256)) != hipSuccess ||
-      (e = hipMalloc((void**)&ctx->seeds_dev, (size_t)ctx->rows_pad * 8)) != hipSuccess) {
+      (e = hipMalloc((void**)&ctx->seeds_dev, (size_t)ctx->rows_pad * 8)) != hipSuccess ||
+      // more than 128 rows go to the 256 x 256 kernel, whose copy wavefronts leave a tile of noise (256 KB)
+      // per workgroup (at most one per compute unit) when path tokens are sampled
+      (max_rows > 128 &&
+       (e = hipMalloc((void**)&ctx->noise, (size_t)ctx->num_cu * 256 * 256 * 4)) != hipSuccess)) {
     (void)hipGetLastError();
     if (ctx->a_ws) (void)hipFree(ctx->a_ws);
     if (ctx->keys) (void)hipFree(ctx->keys);
     if (ctx->done) (void)hipFree(ctx->done);
     if (ctx->seeds_dev) (void)hipFree(ctx->seeds_dev);
+    if (ctx->noise) (void)hipFree(ctx->noise);
     delete ctx;
     return fail(nullptr, DM_ENOMEM, "workspace allocation of %zu bytes failed: %s", a_bytes, hipGetErrorString(e));
   }
@@ -385,6 +391,7 @@ dm_status dm_create(dm_ctx** out, int device, int64_t max_rows, int32_t max_d, i
     (void)hipFree(ctx->keys);
     (void)hipFree(ctx->done);
     (void)hipFree(ctx->seeds_dev);
+    if (ctx->noise) (void)hipFree(ctx->noise);
     delete ctx;
     return fail_hip(nullptr, "raising the dynamic LDS limit", e);
   }
@@ -402,6 +409,7 @@ dm_status dm_destroy(dm_ctx* ctx) {
   if (ctx->keys) (void)hipFree(ctx->keys);
   if (ctx->done) (void)hipFree(ctx->done);
   if (ctx->seeds_dev) (void)hipFree(ctx->seeds_dev);
+  if (ctx->noise) (void)hipFree(ctx->noise);
   if (ctx->lt) (void)hipFree(ctx->lt);
   if (ctx->part_a) (void)hipFree(ctx->part_a);
   if (ctx->part_b) (void)hipFree(ctx->part_b);

@@ -53,6 +53,7 @@ struct SampleCfg {
   int T, K;
   uint32_t step;
   int clean_last;
+  float* noise;  // DEVICE scratch, 256 KB per workgroup of the 256 x 256 kernel (its copy wavefronts draw the noise), or null
 };
 
 // Where a contraction kernel is launched: the stream and, optionally, two events that receive the

@@ -37,6 +37,7 @@ namespace {
 constexpr int BN = 256;  // vocabulary rows per tile
 constexpr int BM = 256;  // masked rows per tile
 constexpr int THREADS = 768;
+constexpr int kNoiseMinChunks = 16;  // tiles of fewer slabs draw their noise in the epilogue
 
 template <int BK>
 struct Cfg {
@@ -96,8 +97,9 @@ __device__ __forceinline__ bool tile_of(const TileWalk& w, const TilePos& p, int
 
 // MODE 0: argmax keys only; MODE 1: debug dump of logits[M, dv1 - dv0]; MODE 2: argmax keys and every
 // scaled logit stored in the layout [position][vocabulary row][path] for the distribution-level rule.
-// SAMPLE (MODE 0 only): arg max over zscale * logit + Gumbel noise = a draw from Softmax(logit / temperature).
-template <int BK, int MODE, bool SAMPLE>
+// SAMPLE (MODE 0 only): arg max over zscale * logit + Gumbel noise = a draw from Softmax(logit / temperature);
+// 1: the noise is drawn in the epilogue (tiles of few slabs), 2: by the copy wavefronts during the tile.
+template <int BK, int MODE, int SAMPLE>
 __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf16* __restrict__ W,
                                                                      const __bf16* __restrict__ A_sw,
                                                                      unsigned long long* __restrict__ keys, int d,
@@ -195,6 +197,29 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
         dma_copy16(asrc + ((int64_t)s * mt_total + mt) * 1024, aoff, stage + f * 1024);
       }
     };
+    // SAMPLE == 2: the copy wavefronts, idle most of the time, also draw the Gumbel noise of the tile
+    // the MFMA wavefronts are working on: 256 "items" of 64 lanes x 4 vocabulary rows (one Philox block
+    // per lane) per tile, spread over the tile's slabs and left in memory in the order the MFMA
+    // wavefronts read them in their epilogue.  (Drawn in the epilogue, the noise also costs the main
+    // loop registers it does not have.)  Item w = (MFMA wavefront w >> 5, masked-row tile (w >> 3) & 3,
+    // vocabulary tile (w >> 2) & 1, group of four rows w & 3).  Items of a tile are made after the
+    // barrier of its first slab (the epilogue of the tile before has been read by then) and are
+    // complete, by the wait for ALL own memory operations in front of every barrier, before the
+    // barrier of its last slab.
+    constexpr bool prod_noise = SAMPLE == 2;
+    Cursor cn;
+    cn.c = nchunks;
+    int items_done = 0;
+    float4* const noise_wg = reinterpret_cast<float4*>(samp.noise) + (int64_t)blockIdx.x * (BN * BM / 4);
+    auto noise_item = [&](int w, int tv, int tm) {
+      const int cwv = w >> 5, mt = (w >> 3) & 3, vt = (w >> 2) & 1, rq = w & 3;
+      const int64_t m = (int64_t)tm * BM + (cwv >> 2) * 128 + mt * 32 + (lane & 31);
+      const int v4 = v_lo + tv * BN + 64 * (cwv & 3) + 32 * vt + 8 * rq + 4 * (lane >> 5);
+      const RowRng rng = make_row_rng(samp, m, M);
+      float g[4] = {0.f, 0.f, 0.f, 0.f};
+      if (rng.on) gumbel4(rng, (uint32_t)v4, samp.step, g);
+      noise_wg[w * 64 + lane] = make_float4(g[0], g[1], g[2], g[3]);
+    };
     // issue order: W(0) A(0) W(1) | barrier 0 | A(1) W(2) | barrier 1 | A(2) W(3) | ...
     // before barrier q everything but the youngest W slab (q+1, if there is one) has landed
     if (total > 0) {  // a workgroup without tiles has no first slab to look for
@@ -203,14 +228,23 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
     }
     if (total > 1) issue_w(1);
     for (int q = 0; q < total; ++q) {
-      if (q + 1 < total) {
+      if (q + 1 < total && !prod_noise) {
         DM_WAIT_VMCNT(C::W_INSTR);
       } else {
-        DM_WAIT_VMCNT(0);
+        DM_WAIT_VMCNT(0);  // with noise: also the noise stores issued since the last barrier
       }
       DM_BARRIER();  // slab q complete for everyone; slab q-1 consumed by everyone
       if (q + 1 < total) issue_a(q + 1);
       if (q + 2 < total) issue_w(q + 2);
+      if (prod_noise) {
+        (void)advance(cn);         // tile of slab q
+        const int sl = cn.c - 1;   // slab q's index inside its tile
+        if (sl == 0) items_done = 0;
+        if (sl < nchunks - 1) {    // this wavefront's 64 items, evenly over the tile's first nchunks - 1 slabs
+          const int target = (64 * (sl + 1) + (nchunks - 2)) / (nchunks - 1);
+          for (; items_done < target; ++items_done) noise_item(p + 4 * items_done, cn.tv, cn.tm);
+        }
+      }
     }
     return;
   }
@@ -219,7 +253,12 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
   const int wv = wave & 3, wm = wave >> 2;
   const int i32 = lane & 31;
   const int hb = lane >> 5;
-  const int swz = (i32 >> C::SWZ_SHIFT) & (C::PR - 1);
+  // W fragment of k-step s, half hb: piece (2 s + hb) ^ swz = (2 s) ^ (hb ^ swz) of the lane's row.  Every
+  // other term of the address is a multiple of the row size, so the k-step is an XOR on ONE lane
+  // offset instead of one precomputed register per k-step.
+  static_assert(C::ROW_BYTES == 16 * C::PR && C::W_SLAB % C::ROW_BYTES == 0, "piece index = low bits of the address");
+  const uint32_t wlane = (uint32_t)(wv * (64 * C::ROW_BYTES) + i32 * C::ROW_BYTES +
+                                    16 * (hb ^ ((i32 >> C::SWZ_SHIFT) & (C::PR - 1))));
 
   f32x16 acc[4][2];
 #pragma unroll
@@ -232,14 +271,14 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
   int it_c = -1, tv_c = 0, tm_c = 0;
   for (int q = 0; q < total; ++q) {
     DM_BARRIER();
-    const unsigned char* wbase = lds + (q % C::NSW) * C::W_SLAB + wv * (64 * C::ROW_BYTES) + i32 * C::ROW_BYTES;
+    const uint32_t wq = (uint32_t)((q % C::NSW) * C::W_SLAB) + wlane;
     const unsigned char* abase = lds + C::A_BASE + (q % C::NSA) * C::A_SLAB + (4 * wm) * 1024 + lane * 16;
 #pragma unroll
     for (int s = 0; s < C::KSTEPS; ++s) {
       bf16x8 wf[2], af[4];
 #pragma unroll
       for (int vt = 0; vt < 2; ++vt)
-        wf[vt] = *reinterpret_cast<const bf16x8*>(wbase + vt * (32 * C::ROW_BYTES) + 16 * ((2 * s + hb) ^ swz));
+        wf[vt] = *reinterpret_cast<const bf16x8*>(lds + (wq ^ (uint32_t)(32 * s)) + vt * (32 * C::ROW_BYTES));
 #pragma unroll
       for (int mt = 0; mt < 4; ++mt) af[mt] = *reinterpret_cast<const bf16x8*>(abase + (s * 8 + mt) * 1024);
 #pragma unroll
@@ -310,20 +349,35 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
       float best = -INFINITY;
       uint32_t bv = 0xFFFFFFFFu;
       RowRng rng{0u, 0u, 0u, 0u, false};
-      if (SAMPLE) rng = make_row_rng(samp, (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32, M);
-      const bool noisy = SAMPLE && rng.on;
+      if (SAMPLE == 1) rng = make_row_rng(samp, (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32, M);
+      const bool noisy = SAMPLE == 1 ? rng.on
+                                     : (SAMPLE == 2 && row_draws(samp, (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32, M));
+      // SAMPLE == 2: noise made by the copy wavefronts during the tile, item (wave, mt, vt, rq), this lane's four values
+      // (a uniform base and one lane offset, opaque so that the 32 addresses are not kept across the tile)
+      const char* nz = reinterpret_cast<const char*>(samp.noise) + (int64_t)blockIdx.x * (BN * BM * 4) +
+                       (wave * 32 + mt * 8) * 1024;
+      uint32_t nlane = (uint32_t)lane * 16u;
+      if (SAMPLE == 2) asm volatile("" : "+v"(nlane));
       // First vocabulary row of this lane in the tile.  When sampling it is made opaque to the compiler
       // for every masked-row tile: otherwise whatever depends on the vocabulary row only (noise
       // counters, the first Philox round) is shared between the four tiles, kept in registers across
       // the main loop, and spilled there.
       int vb = v0 + 64 * wv + 4 * hb;
-      if (SAMPLE) asm volatile("" : "+v"(vb));
+      if (SAMPLE == 1) asm volatile("" : "+v"(vb));
 #pragma unroll
       for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
         for (int rq = 0; rq < 4; ++rq) {
           float g[4] = {0.f, 0.f, 0.f, 0.f};
-          if (noisy) gumbel4(rng, (uint32_t)(vb + 32 * vt + 8 * rq), samp.step, g);
+          if (SAMPLE == 2) {
+            const float4 g4 = *reinterpret_cast<const float4*>(nz + (vt * 4 + rq) * 1024 + nlane);
+            g[0] = g4.x;
+            g[1] = g4.y;
+            g[2] = g4.z;
+            g[3] = g4.w;
+          } else if (noisy) {
+            gumbel4(rng, (uint32_t)(vb + 32 * vt + 8 * rq), samp.step, g);
+          }
 #pragma unroll
           for (int e = 0; e < 4; ++e) {  // ascending v for this lane: strict > keeps the smallest index
             const int r = 4 * rq + e;
@@ -336,7 +390,7 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
             acc[mt][vt][r] = 0.f;
           }
           // the noise of one group of four rows is not computed ahead of the groups before it
-          if (SAMPLE) __builtin_amdgcn_sched_barrier(0);
+          if (SAMPLE == 1) __builtin_amdgcn_sched_barrier(0);
         }
       unsigned long long key = (bv == 0xFFFFFFFFu) ? 0ull : pack_key(best, bv);
       const unsigned long long other = __shfl_xor(key, 32, 64);
@@ -401,20 +455,22 @@ hipError_t run_big(const void* W, const void* a_ws, unsigned long long* keys, co
             static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo, v_hi, \
             walk, logits, v0, v1, scale, store, samp)
   if (dump)
-    DM_LAUNCH(1, false);
+    DM_LAUNCH(1, 0);
   else if (store.lt != nullptr)
-    DM_LAUNCH(2, false);
+    DM_LAUNCH(2, 0);
+  else if (samp.seeds != nullptr && samp.noise != nullptr && g.d / BK >= kNoiseMinChunks)
+    DM_LAUNCH(0, 2);
   else if (samp.seeds != nullptr)
-    DM_LAUNCH(0, true);
+    DM_LAUNCH(0, 1);
   else
-    DM_LAUNCH(0, false);
+    DM_LAUNCH(0, 0);
 #undef DM_LAUNCH
   return hipGetLastError();
 }
 
 constexpr int kBigBK = 64;
 
-template <int MODE, bool SAMPLE>
+template <int MODE, int SAMPLE>
 hipError_t raise_lds_big() {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_mfma_big_kernel<kBigBK, MODE, SAMPLE>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, Cfg<kBigBK>::LDS_BYTES);
@@ -424,10 +480,11 @@ hipError_t raise_lds_big() {
 
 hipError_t prepare_lmhead_mfma_big() {
   hipError_t e;
-  if ((e = raise_lds_big<0, false>()) != hipSuccess) return e;
-  if ((e = raise_lds_big<0, true>()) != hipSuccess) return e;
-  if ((e = raise_lds_big<1, false>()) != hipSuccess) return e;
-  return raise_lds_big<2, false>();
+  if ((e = raise_lds_big<0, 0>()) != hipSuccess) return e;
+  if ((e = raise_lds_big<0, 1>()) != hipSuccess) return e;
+  if ((e = raise_lds_big<0, 2>()) != hipSuccess) return e;
+  if ((e = raise_lds_big<1, 0>()) != hipSuccess) return e;
+  return raise_lds_big<2, 0>();
 }
 
 hipError_t launch_lmhead_mfma_big(const void* W, const void* a_ws, unsigned long long* keys, const RowGeom& g, int V,

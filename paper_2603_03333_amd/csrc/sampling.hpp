@@ -10,8 +10,16 @@ __device__ __forceinline__ RowRng make_row_rng(const SampleCfg& sc, int64_t m, i
   RowRng r{0u, 0u, 0u, 0u, false};
   if (sc.seeds == nullptr || m >= M) return r;
   const int TK = sc.T * sc.K;
-  const int64_t b = m / TK;
-  const int rem = (int)(m - b * TK);
+  int64_t b;
+  int rem;
+  if (M <= 0x7fffffff) {  // every practical size: 32-bit divisions (the 64-bit one is ~100 instructions)
+    const uint32_t b32 = (uint32_t)m / (uint32_t)TK;
+    b = b32;
+    rem = (int)((uint32_t)m - b32 * (uint32_t)TK);
+  } else {
+    b = m / TK;
+    rem = (int)(m - b * TK);
+  }
   const int t = rem / sc.K;
   const int i = rem - t * sc.K;
   const uint64_t key = sc.seeds[b] + kSampleKeyOffset;
@@ -21,6 +29,14 @@ __device__ __forceinline__ RowRng make_row_rng(const SampleCfg& sc, int64_t m, i
   r.i = (uint32_t)i;
   r.on = !(sc.clean_last && i == sc.K - 1);
   return r;
+}
+
+// Whether masked row m draws its token (false: padding row, or the clean last path).
+__device__ __forceinline__ bool row_draws(const SampleCfg& sc, int64_t m, int64_t M) {
+  if (sc.seeds == nullptr || m >= M) return false;
+  if (!sc.clean_last) return true;
+  const int i = M <= 0x7fffffff ? (int)((uint32_t)m % (uint32_t)sc.K) : (int)(m % sc.K);
+  return i != sc.K - 1;
 }
 
 // Gumbel noise of vocabulary entries v4 .. v4+3 (v4 a multiple of 4) for one row: one Philox call.
