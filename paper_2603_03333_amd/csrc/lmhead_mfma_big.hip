@@ -201,24 +201,27 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
     // the MFMA wavefronts are working on: 256 "items" of 64 lanes x 4 vocabulary rows (one Philox block
     // per lane) per tile, spread over the tile's slabs and left in memory in the order the MFMA
     // wavefronts read them in their epilogue.  (Drawn in the epilogue, the noise also costs the main
-    // loop registers it does not have.)  Item w = (MFMA wavefront w >> 5, masked-row tile (w >> 3) & 3,
-    // vocabulary tile (w >> 2) & 1, group of four rows w & 3).  Items of a tile are made after the
-    // barrier of its first slab (the epilogue of the tile before has been read by then) and are
-    // complete, by the wait for ALL own memory operations in front of every barrier, before the
-    // barrier of its last slab.
+    // loop registers it does not have.)  Copy wavefront p makes the 64 items with row group rq = p:
+    // item k = ((wm * 4 + mt) * 8 + wv * 2 + vt) of MFMA wavefront (wv, wm), masked-row tile mt,
+    // vocabulary tile vt, stored at float4 index (4 k + rq) * 64 + lane.  Eight consecutive items share
+    // their 32 masked rows, so the rows' streams are set up once per eight.  Items of a tile are made
+    // after the barrier of its first slab (the epilogue of the tile before has been read by then) and
+    // are complete, by a wait for ALL own memory operations, before the barrier of its last slab.
     constexpr bool prod_noise = SAMPLE == 2;
     Cursor cn;
     cn.c = nchunks;
     int items_done = 0;
-    float4* const noise_wg = reinterpret_cast<float4*>(samp.noise) + (int64_t)blockIdx.x * (BN * BM / 4);
-    auto noise_item = [&](int w, int tv, int tm) {
-      const int cwv = w >> 5, mt = (w >> 3) & 3, vt = (w >> 2) & 1, rq = w & 3;
-      const int64_t m = (int64_t)tm * BM + (cwv >> 2) * 128 + mt * 32 + (lane & 31);
-      const int v4 = v_lo + tv * BN + 64 * (cwv & 3) + 32 * vt + 8 * rq + 4 * (lane >> 5);
-      const RowRng rng = make_row_rng(samp, m, M);
+    RowRng nrng{0u, 0u, 0u, 0u, false};
+    f32x4* const noise_wg = reinterpret_cast<f32x4*>(samp.noise) + (int64_t)blockIdx.x * (BN * BM / 4);
+    auto noise_item = [&](int k, int tv, int tm) {
+      const int rs = k >> 3, wv_k = (k >> 1) & 3, vt = k & 1;
+      if ((k & 7) == 0) nrng = make_row_rng(samp, (int64_t)tm * BM + (rs >> 2) * 128 + (rs & 3) * 32 + (lane & 31), M);
+      const int v4 = v_lo + tv * BN + 64 * wv_k + 32 * vt + 8 * p + 4 * (lane >> 5);
       float g[4] = {0.f, 0.f, 0.f, 0.f};
-      if (rng.on) gumbel4(rng, (uint32_t)v4, samp.step, g);
-      noise_wg[w * 64 + lane] = make_float4(g[0], g[1], g[2], g[3]);
+      if (nrng.on) gumbel4(nrng, (uint32_t)v4, samp.step, g);
+      // written once, read once, by this compute unit: streaming, so that it does not displace the W and
+      // masked-row slabs the workgroups of the XCD share through L2
+      __builtin_nontemporal_store(f32x4{g[0], g[1], g[2], g[3]}, noise_wg + (4 * k + p) * 64 + lane);
     };
     // issue order: W(0) A(0) W(1) | barrier 0 | A(1) W(2) | barrier 1 | A(2) W(3) | ...
     // before barrier q everything but the youngest W slab (q+1, if there is one) has landed
@@ -228,10 +231,13 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
     }
     if (total > 1) issue_w(1);
     for (int q = 0; q < total; ++q) {
-      if (q + 1 < total && !prod_noise) {
+      // Copies complete in issue order, so "at most the youngest W slab outstanding" means slab q has landed;
+      // noise stores in between (which may complete out of order) only make that wait more conservative.
+      // Before the barrier of a tile's last slab the noise stores themselves must be complete: wait for all.
+      if (q + 1 < total && !(prod_noise && q % nchunks == nchunks - 1)) {
         DM_WAIT_VMCNT(C::W_INSTR);
       } else {
-        DM_WAIT_VMCNT(0);  // with noise: also the noise stores issued since the last barrier
+        DM_WAIT_VMCNT(0);
       }
       DM_BARRIER();  // slab q complete for everyone; slab q-1 consumed by everyone
       if (q + 1 < total) issue_a(q + 1);
@@ -242,7 +248,7 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
         if (sl == 0) items_done = 0;
         if (sl < nchunks - 1) {    // this wavefront's 64 items, evenly over the tile's first nchunks - 1 slabs
           const int target = (64 * (sl + 1) + (nchunks - 2)) / (nchunks - 1);
-          for (; items_done < target; ++items_done) noise_item(p + 4 * items_done, cn.tv, cn.tm);
+          for (; items_done < target; ++items_done) noise_item(items_done, cn.tv, cn.tm);
         }
       }
     }
@@ -352,10 +358,10 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
       if (SAMPLE == 1) rng = make_row_rng(samp, (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32, M);
       const bool noisy = SAMPLE == 1 ? rng.on
                                      : (SAMPLE == 2 && row_draws(samp, (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32, M));
-      // SAMPLE == 2: noise made by the copy wavefronts during the tile, item (wave, mt, vt, rq), this lane's four values
+      // SAMPLE == 2: noise made by the copy wavefronts during the tile, items (wm, mt, wv, vt = 0) onwards
       // (a uniform base and one lane offset, opaque so that the 32 addresses are not kept across the tile)
       const char* nz = reinterpret_cast<const char*>(samp.noise) + (int64_t)blockIdx.x * (BN * BM * 4) +
-                       (wave * 32 + mt * 8) * 1024;
+                       (((wm * 4 + mt) * 8 + wv * 2) * 4) * 1024;
       uint32_t nlane = (uint32_t)lane * 16u;
       if (SAMPLE == 2) asm volatile("" : "+v"(nlane));
       // First vocabulary row of this lane in the tile.  When sampling it is made opaque to the compiler
@@ -370,7 +376,7 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
         for (int rq = 0; rq < 4; ++rq) {
           float g[4] = {0.f, 0.f, 0.f, 0.f};
           if (SAMPLE == 2) {
-            const float4 g4 = *reinterpret_cast<const float4*>(nz + (vt * 4 + rq) * 1024 + nlane);
+            const f32x4 g4 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(nz + (vt * 4 + rq) * 1024 + nlane));
             g[0] = g4.x;
             g[1] = g4.y;
             g[2] = g4.z;

@@ -8,6 +8,7 @@ namespace dm {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #define DM_GLOBAL_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
 #define DM_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
