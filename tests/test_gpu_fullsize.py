@@ -250,3 +250,42 @@ def test_head8b_nucleus_tokens_on_sampled_rows():
     exp = orc.acceptance_from_path_ids(res["path_ids"], draft, orc.RULE_ANY)
     for k in ("vote_ids", "vote_cnt", "hit", "accept_len"):
         assert np.array_equal(res[k], exp[k]), k
+
+
+def test_batched_sampled_tokens_on_sampled_rows():
+    """Sampled path tokens at the full size of the compute-bound configuration (4096 rows, d = 8192:
+    the 256 x 256 kernel whose copy wavefronts draw the noise, 31 tiles per workgroup): three positions
+    from different sequences and row tiles, all 16 paths each over the full vocabulary."""
+    wl = wk.CONFIGS["batched"]
+    tau = 0.8
+    W, h, seeds = wk.make_weight(wl), wk.make_hidden(wl), wk.make_seeds(wl)
+    draft = wk.make_draft_ids(wl, None)
+    r = Runner(wl.rows, wl.d, wl.V)
+    try:
+        hd, Wd = to_device(h, wl.dtype), to_device(W, wl.dtype)
+        res = r.verify(wl, hd, Wd, draft, seeds, flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=tau)
+        res2 = r.verify(wl, hd, Wd, draft, seeds, flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=tau)
+        assert np.array_equal(res["path_ids"], res2["path_ids"])
+        del hd, Wd
+    finally:
+        r.close()
+    torch.cuda.empty_cache()
+    near = flips = 0
+    chunk = 16384                                       # vocabulary rows per float64 block of W
+    for b, t in ((0, 0), (13, 3), (wl.B - 1, wl.T - 1)):
+        Hm = np.stack([orc.masked_state(h[b, t], orc.keep_mask(int(seeds[b]), 0, t, i, wl.d, wl.p), wl.p)
+                       for i in range(wl.K)])
+        L = np.concatenate([W[v:v + chunk].astype(np.float64) @ Hm.T for v in range(0, wl.V, chunk)])
+        for i in range(wl.K):
+            g = orc.gumbel_noise(orc.sampling_uniforms(int(seeds[b]), 0, t, i, wl.V))
+            y, gap = orc.sampled_token(L[:, i], tau, g)
+            near += gap < 1.25e-3
+            if res["path_ids"][b, t, i] != y:
+                flips += 1
+                assert gap < 1.25e-3, (b, t, i, gap)
+        del L
+        gc.collect()
+    print(f"[batched/sampled] rows=48 near-tie={near} flips={flips}", flush=True)
+    exp = orc.acceptance_from_path_ids(res["path_ids"], draft, orc.RULE_ANY)
+    for k in ("vote_ids", "vote_cnt", "hit", "accept_len"):
+        assert np.array_equal(res[k], exp[k]), k

@@ -443,6 +443,9 @@ def test_planted_dominant_tokens(runner):
     (256, 4096, 2, 6, 16, "bf16", 0.7),    # 256 x 256 tiles
     (100, 130, 2, 3, 5, "f32", 1.5),       # generic kernel
     (128, 777, 1, 3, 16, "bf16", 0.25),    # a sharp temperature
+    (1024, 2000, 2, 6, 16, "bf16", 0.7),   # 256 x 256 tiles of 16 slabs: noise drawn by the copy wavefronts; 192 of 256 rows
+    (2048, 3000, 3, 7, 16, "bf16", 1.2),   # two row tiles (336 rows), ragged vocabulary, 32 slabs
+    (1088, 600, 2, 5, 32, "bf16", 0.5),    # 17 slabs, K = 32, three vocabulary tiles
 ])
 def test_sampled_path_tokens(runner, d, V, B, T, K, dtype, tau):
     """Path tokens drawn from Softmax(l / tau) by the Gumbel-max construction with the counter-based

@@ -145,3 +145,35 @@ def test_random_medium_case(medium_runner, case):
     exp = ref if nflip == 0 else orc.acceptance_from_path_ids(res["path_ids"], draft, rule, None)
     for k in ("vote_ids", "vote_cnt", "hit", "accept_mask", "accept_len", "best_node"):
         assert np.array_equal(res[k], exp[k]), f"medium case {case}: {k}"
+
+
+def test_sampled_tokens_over_several_tiles_per_workgroup():
+    """Sampled path tokens where every workgroup of the 256 x 256 kernel walks two or three tiles
+    (548 tiles on 256 compute units) of 16 slabs each: the copy wavefronts draw a tile's noise while
+    the tile before is still being reduced.  Every path token against the oracle; one sequence has
+    a clean last path."""
+    import gc
+    d, V, B, T, K, tau = 1024, 70000, 4, 8, 16, 0.9
+    wl = wk.Workload("samp_multi", d=d, V=V, dtype="bf16", B=B, T=T, K=K, p=0.1, bonus=True, data_seed=4242)
+    W, h = wk.make_weight(wl, sigma=0.1), wk.make_hidden(wl)
+    seeds = np.random.default_rng(99).integers(0, 2 ** 63, size=B, dtype=np.uint64)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    r = Runner(max_rows=B * T * K, max_d=d, max_V=V)
+    try:
+        hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+        for clean in (False, True):
+            flags = dmb.DM_FLAG_SAMPLE_PATHS | (dmb.DM_FLAG_CLEAN_LAST_PATH if clean else 0)
+            res = r.verify(wl, hd, Wd, draft, seeds, rule=1, step=3, flags=flags, temperature=tau)
+            ref = orc.verify(h, W, draft, seeds, K, 0.1, rule=1, step=3, temperature=tau, clean_last_path=clean)
+            nflip, nnear = compare_path_ids(res["path_ids"], ref["path_ids"], ref["gap"], tol=1e-3 / tau)
+            print(f"[sampled, several tiles per workgroup, clean={clean}] rows={B*T*K} near-tie rows={nnear} flips={nflip}", flush=True)
+            KU = K - 1 if clean else K
+            exp = ref if nflip == 0 else orc.acceptance_from_path_ids(res["path_ids"][:, :, :KU], draft, 1, None)
+            for k in ("vote_ids", "vote_cnt", "hit", "accept_mask", "accept_len", "best_node"):
+                assert np.array_equal(res[k], exp[k]), k
+            if clean:
+                assert np.array_equal(res["path_ids"][:, :, -1], orc.greedy_ids(h, W))
+            del ref
+            gc.collect()
+    finally:
+        r.close()
