@@ -83,12 +83,13 @@ typedef enum {
  * clean last path stays arg max.
  * With 0 < prm->top_p < 1 the arg max runs over the nucleus of that distribution only (Holtzman et
  * al.'s top-p set): most probable tokens first until their probabilities add up to top_p, tokens
- * exactly as probable as the last one included; same noise, so the draw follows the distribution
+ * as probable as the last one included; same noise, so the draw follows the distribution
  * renormalised on the set and top_p -> 1 gives the unrestricted draw.  This variant keeps the
  * logits of the call (dm_reserve_js must have been called for B*T positions and K paths;
- * K <= DM_MAX_K_JS, T*K <= DM_MAX_TK_JS), finds each row's threshold exactly (probability mass in
- * 64-bit integers, floor(e^-t 2^44) with t the distance from the row's maximum over the temperature:
- * reproducible run to run) and then draws from the stored logits. */
+ * K <= DM_MAX_K_JS, T*K <= DM_MAX_TK_JS), finds each row's threshold (with t the distance from the
+ * row's maximum over the temperature: probability mass in 64-bit integers, floor(e^-t 2^44), so
+ * reproducible run to run; tokens whose t agree to 2^-19 count as equally probable) and then draws
+ * from the stored logits. */
 #define DM_FLAG_SAMPLE_PATHS 16u
 
 /* Testing aid: always run the acceptance step as its own kernel.  (Without it, calls that go to the

@@ -157,7 +157,7 @@ __host__ __device__ inline unsigned long long pack_key(float val, uint32_t v) {
 }
 
 // Sampled path tokens restricted to the nucleus (top-p set) of Softmax(l / tau), over the stored logits:
-// four histogram + scan levels find each row's threshold exactly, a last pass draws inside it.
+// three histogram + scan levels find each row's threshold, a last pass draws inside it.
 constexpr int kNucChunk = 1024;  // vocabulary rows per workgroup
 constexpr int kNucMaxK = 64;     // paths per row
 struct NucGeom {

@@ -8,8 +8,9 @@
 // needed are all in).  Masses are summed as 64-bit integers, floor(e^-t * 2^44): integer sums
 // do not depend on the order of the additions, so every run makes the same decisions.
 //
-// t* is found exactly by a radix search over the 32 bits of t (the bit pattern of a
-// non-negative float grows with its value), 8 bits per level:
+// t* is found by a radix search over t in fixed point, 24 bits in units of 2^-19 (order_key; the
+// whole range in which a token has any mass, at fifty times the resolution the float32 logits
+// themselves are good for; tokens that share a key count as equally probable), 8 bits per level:
 //   nucleus_hist_kernel   per (position, chunk of vocabulary rows): the mass of every 8-bit digit
 //                         among the row's elements that match the digits fixed so far - first in
 //                         LDS (one histogram per path of the position), then the non-empty bins
@@ -17,7 +18,7 @@
 //   nucleus_scan_kernel   per row: walk the bins in order of growing t until the target mass is
 //                         reached; that digit is fixed, the mass below it carried on, the bins
 //                         cleared for the next level.  Level 0 also turns top_p into the target.
-// After four levels t* is known to the bit.
+// After three levels the key of t* is known.
 //   nucleus_draw_kernel   arg max of l[v] / tau + Gumbel noise over the nucleus (the same noise
 //                         stream as the unrestricted draw, so top_p -> 1 gives that draw), merged
 //                         into a second array of packed keys that the acceptance step then reads.
@@ -33,6 +34,7 @@ constexpr int HT = 1024;         // threads per workgroup of the histogram passe
 constexpr int kHistChunk = 4096; // vocabulary rows per histogram workgroup: every workgroup ends with up to
                                  // 256 atomic adds to memory per path, so few large ones are cheaper
 constexpr int kBins = 256;       // 8 bits per level
+constexpr int kLevels = 3;       // levels of the search: 24 key bits
 constexpr float kMassScale = 17592186044416.0f;  // 2^44
 constexpr int kNucBatch = 8;     // vocabulary rows a thread has in flight
 
@@ -45,6 +47,10 @@ __device__ __forceinline__ float nkey_logit(unsigned long long key) {
 // distance of a stored logit from its row's maximum in units of tau; the same expression in every pass
 __device__ __forceinline__ float dist_t(float lmax, float l, float inv_tau) { return (lmax - l) * inv_tau; }
 
+// The search key of t: t in units of 2^-19, saturated at 2^24 - 1.  (From t = 30.5 on, floor(e^-t * 2^44)
+// is 0: whatever saturates carries no mass.)  Monotone in t, exact for the floats it is applied to.
+__device__ __forceinline__ uint32_t order_key(float t) { return (uint32_t)fminf(t * 524288.0f, 16777215.0f); }
+
 // floor(e^-t * 2^44).  The product is a float with 24 significant bits below 2^45, so it splits
 // exactly into a multiple of 2^20 and a remainder below 2^20: two 32-bit conversions instead of the
 // long software sequence of a float -> 64-bit integer conversion.
@@ -55,7 +61,7 @@ __device__ __forceinline__ unsigned long long mass_of(float t) {
   return ((unsigned long long)hi << 20) + lo;
 }
 
-// LEVEL 0..3: digit = bits [31-8*LEVEL .. 24-8*LEVEL] of t.
+// LEVEL 0..2: digit = bits [23-8*LEVEL .. 16-8*LEVEL] of the key of t.
 template <int LEVEL>
 __global__ __launch_bounds__(HT) void nucleus_hist_kernel(const float* __restrict__ lt,
                                                           const unsigned long long* __restrict__ keys,
@@ -65,7 +71,7 @@ __global__ __launch_bounds__(HT) void nucleus_hist_kernel(const float* __restric
   extern __shared__ unsigned long long hist[];  // [KP][kBins]
   const int pos = blockIdx.x, c = blockIdx.y;
   const int tid = threadIdx.x;
-  constexpr int shift = 24 - 8 * LEVEL;
+  constexpr int shift = 8 * (kLevels - 1 - LEVEL);
   for (int x = tid; x < g.KP * kBins; x += HT) hist[x] = 0ull;
   __syncthreads();
 
@@ -95,7 +101,7 @@ __global__ __launch_bounds__(HT) void nucleus_hist_kernel(const float* __restric
       for (int u = 0; u < kNucBatch; ++u) {
         if (v0 + u * vstep >= v_end) break;
         const float t = dist_t(lmax, x[u], inv_tau);
-        const uint32_t key = __float_as_uint(t);
+        const uint32_t key = order_key(t);
         if (LEVEL > 0 && (key >> (shift + 8)) != (pre >> (shift + 8))) continue;
         const unsigned long long m = mass_of(t);
         const uint32_t bin = (key >> shift) & 255u;
@@ -129,10 +135,10 @@ __global__ __launch_bounds__(NT) void nucleus_scan_kernel(unsigned long long* __
   if (row >= (int64_t)g.P * g.K) return;
   const int i = (int)(row % g.K);
   if (i >= g.KU) {  // the clean path draws nothing; its bins were never touched
-    if (LEVEL == 3 && lane == 0) keys_s[row] = 0ull;
+    if (LEVEL == kLevels - 1 && lane == 0) keys_s[row] = 0ull;
     return;
   }
-  constexpr int shift = 24 - 8 * LEVEL;
+  constexpr int shift = 8 * (kLevels - 1 - LEVEL);
   unsigned long long* bins = ghist + row * kBins;
   unsigned long long b[4], run = 0ull;
 #pragma unroll
@@ -180,7 +186,7 @@ __global__ __launch_bounds__(NT) void nucleus_scan_kernel(unsigned long long* __
     prefix[row] = old | ((uint32_t)(4 * lane + digit) << shift);
     below[row] = acc;
     if (LEVEL == 0) target[row] = want;
-    if (LEVEL == 3) keys_s[row] = 0ull;
+    if (LEVEL == kLevels - 1) keys_s[row] = 0ull;
   }
 }
 
@@ -221,7 +227,7 @@ __global__ __launch_bounds__(NT) void nucleus_draw_kernel(const float* __restric
         bool any = false;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          in[e] = v4 + e < v_end && __float_as_uint(dist_t(lmax, l[u][e], inv_tau)) <= tmax;
+          in[e] = v4 + e < v_end && order_key(dist_t(lmax, l[u][e], inv_tau)) <= tmax;
           any |= in[e];
         }
         if (!any) continue;
@@ -260,9 +266,8 @@ hipError_t prepare_nucleus() {
                                hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
   if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&nucleus_hist_kernel<1>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
-  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&nucleus_hist_kernel<2>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&nucleus_hist_kernel<3>),
+  static_assert(kLevels == 3, "one instance per level");
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&nucleus_hist_kernel<2>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, lds);
 }
 
@@ -285,7 +290,6 @@ hipError_t launch_nucleus(const float* lt, const unsigned long long* keys, const
   DM_NUC_LEVEL(0);
   DM_NUC_LEVEL(1);
   DM_NUC_LEVEL(2);
-  DM_NUC_LEVEL(3);
 #undef DM_NUC_LEVEL
   const size_t red_lds = (size_t)NT * 8;
   nucleus_draw_kernel<<<grid, block, red_lds, stream>>>(lt, keys, nb.prefix, nb.keys_s, g, samp, scale, inv_tau);
