@@ -8,9 +8,9 @@
 // needed are all in).  Masses are summed as 64-bit integers, floor(e^-t * 2^44): integer sums
 // do not depend on the order of the additions, so every run makes the same decisions.
 //
-// t* is found by a radix search over t in fixed point, 24 bits in units of 2^-19 (order_key; the
-// whole range in which a token has any mass, at fifty times the resolution the float32 logits
-// themselves are good for; tokens that share a key count as equally probable), 8 bits per level:
+// t* is found by a radix search over t in fixed point, 24 bits in units of 2^-19 (order_key: the
+// whole range in which a token has any mass; at temperatures up to 1 a finer resolution than the
+// float32 logits are good for; tokens that share a key count as equally probable), 8 bits per level:
 //   nucleus_hist_kernel   per (position, chunk of vocabulary rows): the mass of every 8-bit digit
 //                         among the row's elements that match the digits fixed so far - first in
 //                         LDS (one histogram per path of the position), then the non-empty bins
