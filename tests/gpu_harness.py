@@ -140,3 +140,29 @@ def compare_js(res, ref, draft, rule_js_only, path_flips, label=""):
           f"near-tie rows={int(near.sum())} max|d js_heads|={np.abs(res['js_heads'] - jh_ref).max():.2e} "
           f"max|d js_draft|={np.abs(res['js_draft'][has] - jd_ref[has]).max() if has.any() else 0:.2e}", flush=True)
     return int(near.sum()), gpu_js
+
+
+def check_graph_replays(enqueue, out, eager, between, reps=4):
+    """Capture enqueue(stream) (one library call writing the tensors in `out`) in a HIP graph and
+    replay it: every replay must reproduce `eager` (host arrays by the same keys), with eager work
+    (`between()`) and synchronisations between the replays."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up on the capture stream
+        enqueue(side)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        enqueue(torch.cuda.current_stream())
+    for rep in range(reps):
+        for v in out.values():
+            v.fill_(7 if v.dtype == torch.uint8 else -1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, v in out.items():
+            got, want = v.cpu().numpy(), eager[k]
+            same = np.array_equal(got, want) if got.dtype.kind != "f" else np.array_equal(got, want, equal_nan=True)
+            assert same, f"replay {rep}: {k}"
+        between()
+    del graph

@@ -17,7 +17,7 @@ if not torch.cuda.is_available():
     pytest.skip("no GPU", allow_module_level=True)
 
 from paper_2603_03333_amd import binding as dmb  # noqa: E402
-from gpu_harness import Runner, compare_js, compare_path_ids, to_device  # noqa: E402
+from gpu_harness import Runner, check_graph_replays, compare_js, compare_path_ids, to_device  # noqa: E402
 
 
 @pytest.fixture(scope="module")
@@ -122,6 +122,30 @@ def test_js_is_deterministic_and_optional_outputs(runner):
     torch.cuda.synchronize()
     only = runner.verify_js(wl, hd, Wd, draft, probs, seeds, rule=dmb.DM_RULE_JS)
     assert np.array_equal(acc.cpu().numpy(), only["accept_len"])
+
+
+@pytest.mark.parametrize("B,T,K", [(1, 6, 8), (4, 6, 16)])     # W-streaming kernel / 256 x 256 kernel in store mode
+def test_verify_js_can_be_captured_in_a_hip_graph(runner, B, T, K):
+    """Store-mode contraction, both JS passes and the acceptance step replayed from a HIP graph: every
+    replay equals the eager call, with other eager calls (which overwrite the stored logits and the
+    partial sums) in between."""
+    wl, W, h, seeds, draft, probs = _problem(256, 3000, "bf16", B, T, K, 0.1, seed=450 + K)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    eager = runner.verify_js(wl, hd, Wd, draft, probs, seeds)
+    prm, keep = runner.params(wl, seeds, rule=dmb.DM_RULE_JS_OR_MAJORITY)
+    draft_dev, probs_dev = torch.from_numpy(draft).cuda(), torch.from_numpy(probs).cuda()
+    out = dict(accept_len=torch.zeros(B, dtype=torch.int32, device="cuda"),
+               hit=torch.zeros((B, T), dtype=torch.uint8, device="cuda"),
+               path_ids=torch.zeros((B, T, K), dtype=torch.int32, device="cuda"),
+               js_draft=torch.zeros((B, T), dtype=torch.float32, device="cuda"),
+               js_heads=torch.zeros((B, T, K), dtype=torch.float32, device="cuda"))
+
+    def between():
+        other = runner.verify_js(wl, hd, Wd, draft, probs, seeds, step=5)
+        assert (other["path_ids"] != eager["path_ids"]).any()
+
+    check_graph_replays(lambda st: dmb.dropmatch_verify_js(runner.ctx, prm, hd, Wd, draft_dev, probs_dev, stream=st, **out),
+                        out, eager, between)
 
 
 def test_js_argument_errors(runner):

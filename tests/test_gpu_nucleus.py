@@ -23,7 +23,7 @@ if not torch.cuda.is_available():
     pytest.skip("no GPU", allow_module_level=True)
 
 from paper_2603_03333_amd import binding as dmb  # noqa: E402
-from gpu_harness import Runner, to_device  # noqa: E402
+from gpu_harness import Runner, check_graph_replays, to_device  # noqa: E402
 
 MASS_EPS = 1e-4
 Z_DELTA = 5e-5
@@ -113,6 +113,32 @@ def test_nucleus_tokens_peaked_distributions(runner):
         sizes = [int(orc.nucleus(ref["logits"][r], top_p)[0].sum()) for r in range(0, rows, 7)]
         print(f"[nucleus peaked top_p={top_p}] rows={rows} equal={same} nucleus sizes (sample)={sizes[:8]}", flush=True)
         assert same >= 0.9 * rows and max(sizes) < wl.V // 4
+
+
+@pytest.mark.parametrize("B,T,K", [(1, 8, 16), (3, 6, 16)])     # W-streaming kernel / 256 x 256 kernel in store mode
+def test_nucleus_verify_can_be_captured_in_a_hip_graph(runner, B, T, K):
+    """The seven nucleus launches keep state between calls (bins cleared by the scans, the second key
+    array cleared at the last level): replayed from a HIP graph they must leave it as an eager call
+    does.  Every replay equals the eager call, with eager calls on other inputs in between."""
+    wl = wk.Workload("nucg", d=256, V=3000, dtype="bf16", B=B, T=T, K=K, p=0.1, bonus=True, data_seed=91 + B)
+    W, h, seeds = wk.make_weight(wl, sigma=0.1), wk.make_hidden(wl), wk.make_seeds(wl, base_seed=5)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    kw = dict(flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=0.9, top_p=0.8)
+    eager = runner.verify(wl, hd, Wd, draft, seeds, **kw)
+    prm, keep = runner.params(wl, seeds, **kw)
+    draft_dev = torch.from_numpy(draft).cuda()
+    out = dict(accept_len=torch.zeros(B, dtype=torch.int32, device="cuda"),
+               hit=torch.zeros((B, T), dtype=torch.uint8, device="cuda"),
+               path_ids=torch.zeros((B, T, K), dtype=torch.int32, device="cuda"),
+               vote_ids=torch.zeros((B, T), dtype=torch.int32, device="cuda"))
+
+    def between():
+        other = runner.verify(wl, hd, Wd, draft, seeds, step=3, flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=0.9, top_p=0.5)
+        assert (other["path_ids"] != eager["path_ids"]).any()
+
+    check_graph_replays(lambda st: dmb.dropmatch_verify(runner.ctx, prm, hd, Wd, draft_dev, stream=st, **out),
+                        out, eager, between)
 
 
 def test_nucleus_limits_and_options(runner):

@@ -16,7 +16,7 @@ if not torch.cuda.is_available():
     pytest.skip("no GPU", allow_module_level=True)
 
 from paper_2603_03333_amd import binding as dmb  # noqa: E402
-from gpu_harness import Runner, compare_path_ids, to_device  # noqa: E402
+from gpu_harness import Runner, check_graph_replays, compare_path_ids, to_device  # noqa: E402
 
 
 @pytest.fixture(scope="module")
@@ -326,38 +326,32 @@ def test_size_limits(d, V, B, T, K):
 
 
 # ------------------------------------------------------------------ HIP graph capture
-def test_verify_can_be_captured_in_a_hip_graph(runner):
+@pytest.mark.parametrize("d,V,B,T,K,tau", [
+    (256, 3000, 2, 6, 8, 0.0),      # W-streaming kernel, acceptance step fused into it
+    (1024, 2000, 2, 6, 16, 0.7),    # 256 x 256 kernel, sampled tokens: noise scratch written and read per tile
+    (256, 3000, 1, 8, 16, 1.3),     # W-streaming kernel, sampling epilogue
+])
+def test_verify_can_be_captured_in_a_hip_graph(runner, d, V, B, T, K, tau):
     """The step only launches kernels on the caller's stream (no allocation, no synchronisation,
     no memset), so a caller may capture it and replay it.  Every replay is checked against the
     eager result, with eager work and synchronisations between the replays."""
-    wl, W, h, seeds, draft = _problem("graph", 256, 3000, "bf16", 2, 6, 8, 0.1, seed=321, bonus=True)
+    wl, W, h, seeds, draft = _problem("graph", d, V, "bf16", B, T, K, 0.1, seed=321, bonus=True)
     hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
-    eager = runner.verify(wl, hd, Wd, draft, seeds)
-    prm, keep = runner.params(wl, seeds)
+    kw = dict(flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=tau) if tau else {}
+    eager = runner.verify(wl, hd, Wd, draft, seeds, **kw)
+    prm, keep = runner.params(wl, seeds, **kw)
     draft_dev = torch.from_numpy(draft).cuda()
     out = dict(accept_len=torch.zeros(wl.B, dtype=torch.int32, device="cuda"),
                hit=torch.zeros((wl.B, wl.T), dtype=torch.uint8, device="cuda"),
                path_ids=torch.zeros((wl.B, wl.T, wl.K), dtype=torch.int32, device="cuda"),
                vote_ids=torch.zeros((wl.B, wl.T), dtype=torch.int32, device="cuda"))
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):                      # warm-up on the capture stream
-        dmb.dropmatch_verify(runner.ctx, prm, hd, Wd, draft_dev, stream=side, **out)
-    side.synchronize()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph, stream=side):
-        dmb.dropmatch_verify(runner.ctx, prm, hd, Wd, draft_dev, stream=torch.cuda.current_stream(), **out)
-    for rep in range(4):
-        for v in out.values():
-            v.fill_(-1 if v.dtype != torch.uint8 else 7)
-        torch.cuda.synchronize()
-        graph.replay()
-        torch.cuda.synchronize()
-        for k, v in out.items():
-            assert np.array_equal(v.cpu().numpy(), eager[k]), f"replay {rep}: {k}"
-        again = runner.verify(wl, hd, Wd, draft, seeds)      # eager work between replays
-        assert np.array_equal(again["path_ids"], eager["path_ids"])
-    del graph
+
+    def between():                                          # eager work between replays, other inputs
+        other = runner.verify(wl, hd, Wd, draft, seeds, step=9, **kw)
+        assert (other["path_ids"] != eager["path_ids"]).any()
+
+    check_graph_replays(lambda st: dmb.dropmatch_verify(runner.ctx, prm, hd, Wd, draft_dev, stream=st, **out),
+                        out, eager, between)
 
 
 # ------------------------------------------------------------------ clean last path
