@@ -89,6 +89,8 @@ def _run(runner, wl, W, h, seeds, draft, tau, top_p, step=0, rule=orc.RULE_ANY, 
     (128, 777, 1, 3, 12, "bf16", 0.25, 0.95),    # K4 = 12: thread mapping padded to 16 paths
     (64, 2049, 3, 2, 33, "bf16", 1.0, 0.3),      # 33 paths: 64-wide mapping, one vocabulary row past a chunk
     (128, 1500, 1, 4, 64, "bf16", 2.0, 0.99),    # the most paths the variant takes
+    (256, 3000, 1, 8, 16, "bf16", 50.0, 0.5),    # nearly uniform: distances of ~1e-5 in l / tau against the 2^-19 search key
+    (256, 3000, 2, 4, 16, "bf16", 0.05, 0.9),    # very sharp: most tokens beyond the range of the key (no mass)
 ])
 def test_nucleus_tokens_flat_distributions(runner, d, V, B, T, K, dtype, tau, top_p):
     wl = wk.Workload("nuc", d=d, V=V, dtype=dtype, B=B, T=T, K=K, p=0.2, bonus=True, data_seed=d + V + K)
