@@ -177,3 +177,52 @@ def test_sampled_tokens_over_several_tiles_per_workgroup():
             gc.collect()
     finally:
         r.close()
+
+
+def _draw_sampled_big(case):
+    rng = np.random.default_rng(52000 + case)
+    d = int(rng.choice([1024, 1088, 1536, 2048, 3072]))
+    V = int(rng.integers(300, 9000)) if case % 3 else int(rng.choice([256, 257, 512, 4096, 4097]))
+    K = int(rng.choice([3, 5, 8, 16, 17, 32]))
+    T = int(rng.integers(2, 9))
+    B = int(rng.integers(1, 5))
+    while B * T * K <= 128:                       # more than 128 rows: the 256 x 256 kernel
+        T += 1
+    while B * T * K > 1024:
+        T = max(1, T - 1)
+    return rng, d, V, B, T, K
+
+
+@pytest.mark.parametrize("case", range(10))
+def test_random_sampled_case_on_the_big_kernel(case):
+    """Sampled path tokens on the 256 x 256 kernel with 16 to 48 slabs per tile (the copy wavefronts draw
+    the noise): ragged row and vocabulary counts, path counts that do not divide a row tile, several
+    seeds, both token rules, with and without the clean path; every path token against the oracle."""
+    import gc
+    rng, d, V, B, T, K = _draw_sampled_big(case)
+    assert B * T * K > 128
+    tau = float(rng.choice([0.5, 1.0, 2.0]))
+    clean = K >= 2 and bool(rng.integers(0, 2))
+    rule = int(rng.integers(0, 2))
+    step = int(rng.integers(0, 2 ** 32))
+    wl = wk.Workload(f"sbig{case}", d=d, V=V, dtype="bf16", B=B, T=T, K=K, p=float(rng.choice([0.05, 0.1, 0.3])),
+                     bonus=bool(rng.integers(0, 2)), data_seed=15000 + case)
+    W, h = wk.make_weight(wl, sigma=0.05), wk.make_hidden(wl)
+    seeds = rng.integers(0, 2 ** 63, size=B, dtype=np.uint64)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    flags = dmb.DM_FLAG_SAMPLE_PATHS | (dmb.DM_FLAG_CLEAN_LAST_PATH if clean else 0)
+    ref = orc.verify(h, W, draft, seeds, K, wl.p, rule=rule, step=step, temperature=tau, clean_last_path=clean)
+    r = Runner(max_rows=B * T * K, max_d=d, max_V=V)
+    try:
+        res = r.verify(wl, to_device(h, "bf16"), to_device(W, "bf16"), draft, seeds, rule=rule, step=step, flags=flags,
+                       temperature=tau)
+    finally:
+        r.close()
+    tol = 1e-3 * max(1.0, 1.0 / tau)
+    nflip, nnear = compare_path_ids(res["path_ids"], ref["path_ids"], ref["gap"], tol=tol)
+    print(f"[sampled big {case}: d={d} V={V} B={B} T={T} K={K} rows={B*T*K} tau={tau} clean={clean}] near-tie rows={nnear} flips={nflip}", flush=True)
+    KU = K - 1 if clean else K
+    exp = ref if nflip == 0 else orc.acceptance_from_path_ids(res["path_ids"][:, :, :KU], draft, rule, None)
+    for k in ("vote_ids", "vote_cnt", "hit", "accept_mask", "accept_len", "best_node"):
+        assert np.array_equal(res[k], exp[k]), f"case {case}: {k}"
+    gc.collect()
