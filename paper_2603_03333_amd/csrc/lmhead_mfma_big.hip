@@ -350,6 +350,33 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
         }
     }
 
+    if (SAMPLE == 0 && v0 + BN <= v_hi) {
+      // Plain arg max over a full tile (all but the last vocabulary tile): no bounds checks, the winner is
+      // tracked as a 5-bit code and turned into its row once, -0 becomes +0 once (for the comparisons the
+      // two are equal; the packed key orders them, and ties must go to the smaller index in every tile).
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+        float best = acc[mt][0][0];
+        int code = 0;
+        acc[mt][0][0] = 0.f;
+#pragma unroll
+        for (int c = 1; c < 32; ++c) {  // ascending v for this lane: strict > keeps the smallest index
+          const float val = acc[mt][c >> 4][c & 15];
+          const bool gt = val > best;
+          best = gt ? val : best;
+          code = gt ? c : code;
+          acc[mt][c >> 4][c & 15] = 0.f;
+        }
+        const int v = v0 + 64 * wv + 4 * hb + 32 * (code >> 4) + 8 * ((code & 15) >> 2) + (code & 3);
+        unsigned long long key = pack_key(best + 0.0f, (uint32_t)v);
+        const unsigned long long other = __shfl_xor(key, 32, 64);
+        key = other > key ? other : key;
+        const int64_t mrow = (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32;
+        if (hb == 0 && mrow < M) atomicMax(&keys[mrow], key);
+      }
+      continue;
+    }
+
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
       float best = -INFINITY;
