@@ -66,6 +66,22 @@ __host__ __device__ constexpr int lds_bytes(int MT) { return NS * slab_bytes(MT)
 //         layout [position][vocabulary row][path] (store.lt, see LogitStore).
 // SAMPLE (MODE 0 only): the per-row arg max runs over zscale * logit + Gumbel noise, i.e. the path token
 //         is drawn from Softmax(logit / temperature) instead of being the arg max.
+// acc[B / 8][(B / 4) & 1][4 * (B & 3) + e] += g[e]: noise block B of a tile (its 4 consecutive vocabulary
+// rows of masked-row tile B / 8) goes to fixed registers, so the block number has to be a constant.
+template <int MT, int B>
+__device__ __forceinline__ void add_noise_block(f32x16 (&acc)[MT][2], const float (&g)[4]) {
+  if constexpr (B / 8 < MT) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[B / 8][(B / 4) & 1][4 * (B & 3) + e] += g[e];
+  }
+}
+
+// Sampled tokens: how many of a tile's 8 MT noise blocks are added to the accumulators during the k loop
+// instead of being drawn in the epilogue.  Up to 64 rows the MFMA wavefronts wait for data half of every
+// slab and take all of them (sampling then costs 2 % instead of 8 %); with more rows they have no such
+// slack (measured at 128 rows: 192 us against 188 us) and the epilogue keeps the work.
+__host__ __device__ constexpr int noise_blocks_in_loop(int MT) { return MT <= 2 ? 8 * MT : 0; }
+
 template <int MT, int MODE, bool SAMPLE>
 __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* __restrict__ W,
                                                                  const __bf16* __restrict__ A_sw,
@@ -186,6 +202,10 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
     }
 
     RowRng rng[MT];
+    constexpr int NBL = noise_blocks_in_loop(MT);  // SAMPLE: noise blocks 0 .. NBL-1 of a tile are added in the k loop
+    static_assert(NBL <= 16, "the switch below has 16 cases");
+    int noise_b = 0;                               // next of them
+    const float inv_zscale = SAMPLE ? 1.0f / samp.zscale : 0.f;
     if (SAMPLE) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) rng[mt] = make_row_rng(samp, (int64_t)(mblk * MT + mt) * 32 + i32, M);
@@ -213,6 +233,35 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
       asm volatile("" ::: "memory");
 
       const int n = q / nchunks;
+      if constexpr (SAMPLE && NBL > 0) {
+        // arg max over zscale * l + g = arg max over l + g / zscale, and l is a sum: noise can be added to the
+        // accumulators during the k loop, block by block (4 vocabulary rows of one masked-row tile = one
+        // Philox call), evenly over the slabs of the tile, while the wavefront would wait for data anyway
+        const int sl = q - n * nchunks;
+        const int due = ((sl + 1) * NBL) / nchunks;  // blocks added by the end of this slab; all NBL at the last
+        const int vb = row_begin + n * BN + 64 * wave + 4 * hb;
+        for (; noise_b < due; ++noise_b) {
+          const int mt = noise_b >> 3;
+          RowRng r = rng[0];
+#pragma unroll
+          for (int k = 1; k < MT; ++k)
+            if (mt == k) r = rng[k];
+          float g[4] = {0.f, 0.f, 0.f, 0.f};
+          if (r.on) {
+            gumbel4(r, (uint32_t)(vb + 32 * ((noise_b >> 2) & 1) + 8 * (noise_b & 3)), samp.step, g);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) g[e] *= inv_zscale;
+          }
+          switch (noise_b) {
+#define DM_NB(B) case B: add_noise_block<MT, B>(acc, g); break;
+            DM_NB(0) DM_NB(1) DM_NB(2) DM_NB(3) DM_NB(4) DM_NB(5) DM_NB(6) DM_NB(7)
+            DM_NB(8) DM_NB(9) DM_NB(10) DM_NB(11) DM_NB(12) DM_NB(13) DM_NB(14) DM_NB(15)
+#undef DM_NB
+            default: break;
+          }
+        }
+        if (sl == nchunks - 1) noise_b = 0;
+      }
       if (q - n * nchunks != nchunks - 1) continue;
 
       // ---- tile finished: accumulator (vt, r) of lane holds row v, column m ----
@@ -261,7 +310,9 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
           for (int rq = 0; rq < 4; ++rq) {
             float g[4] = {0.f, 0.f, 0.f, 0.f};
             const bool noisy = SAMPLE && rng[mt].on;
-            if (noisy) gumbel4(rng[mt], (uint32_t)(v0 + 64 * wave + 32 * vt + 8 * rq + 4 * hb), samp.step, g);
+            // blocks below NBL got their noise in the k loop (as g / zscale, so the same expression below holds)
+            if (noisy && mt * 8 + vt * 4 + rq >= NBL)
+              gumbel4(rng[mt], (uint32_t)(v0 + 64 * wave + 32 * vt + 8 * rq + 4 * hb), samp.step, g);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {  // ascending v for this lane: strict > keeps the smallest index
               const int r = 4 * rq + e;
