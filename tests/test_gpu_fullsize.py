@@ -179,8 +179,9 @@ def test_batched_js_sampled():
 
 
 # ------------------------------------------------------------------ sampled path tokens at full size
-def test_head8b_sampled_tokens_on_sampled_rows():
-    wl = wk.CONFIGS["head8b"]
+@pytest.mark.parametrize("K", [16, 5])     # 128 rows: noise drawn in the epilogue; 40 rows: added during the k loop
+def test_head8b_sampled_tokens_on_sampled_rows(K):
+    wl = wk.CONFIGS["head8b"].with_(K=K)
     tau = 0.8
     W, h, seeds = wk.make_weight(wl), wk.make_hidden(wl), wk.make_seeds(wl)
     draft = wk.make_draft_ids(wl, None)
@@ -196,7 +197,7 @@ def test_head8b_sampled_tokens_on_sampled_rows():
     torch.cuda.empty_cache()
     W64 = W.astype(np.float64)
     near = flips = 0
-    for t in (0, 5):                                    # two positions, all 16 paths each, full vocabulary
+    for t in (0, 5):                                    # two positions, all K paths each, full vocabulary
         Hm = np.stack([orc.masked_state(h[0, t], orc.keep_mask(int(seeds[0]), 0, t, i, wl.d, wl.p), wl.p)
                        for i in range(wl.K)])
         L = W64 @ Hm.T
@@ -207,7 +208,7 @@ def test_head8b_sampled_tokens_on_sampled_rows():
             if res["path_ids"][0, t, i] != y:
                 flips += 1
                 assert gap < 1.25e-3, (t, i, gap)
-    print(f"[head8b/sampled] rows=32 near-tie={near} flips={flips}", flush=True)
+    print(f"[head8b/sampled K={K}] rows={2 * K} near-tie={near} flips={flips}", flush=True)
     exp = orc.acceptance_from_path_ids(res["path_ids"], draft, orc.RULE_ANY)
     for k in ("vote_ids", "vote_cnt", "hit", "accept_len"):
         assert np.array_equal(res[k], exp[k]), k
