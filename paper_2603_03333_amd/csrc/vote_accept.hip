@@ -4,14 +4,14 @@
 namespace dm {
 namespace {
 
-__global__ __launch_bounds__(256) void vote_accept_kernel(const unsigned long long* __restrict__ keys,
+__global__ __launch_bounds__(1024) void vote_accept_kernel(const unsigned long long* __restrict__ keys,
                                                           const int32_t* __restrict__ draft_ids,
                                                           const int32_t* __restrict__ parent, int T, int K,
                                                           int Kv, int rule, VoteOut out,
                                                           const float* __restrict__ part_b, JsGeom jg) {
   extern __shared__ int32_t sm[];
-  vote_accept_body<false>((int)blockIdx.x, (int)threadIdx.x, 256, sm, keys, draft_ids, parent, T, K, Kv, rule, out,
-                          part_b, jg);
+  vote_accept_body<false>((int)blockIdx.x, (int)threadIdx.x, (int)blockDim.x, sm, keys, draft_ids, parent, T, K, Kv,
+                          rule, out, part_b, jg);
 }
 
 }  // namespace
@@ -32,8 +32,10 @@ hipError_t launch_vote_accept(const unsigned long long* keys, const int32_t* dra
                     vote_lds_bytes(T, K, rule) > vote_lds_bytes(4096, 4, 0)))
     return hipErrorInvalidValue;
   const JsGeom geom = jg ? *jg : JsGeom{};
-  vote_accept_kernel<<<dim3((unsigned)B), dim3(256), vote_lds_bytes(T, K, rule), stream>>>(keys, draft_ids, parent, T, K,
-                                                                                      Kv, rule, out, part_b, geom);
+  // the step takes one row per wavefront at a time (a chain of dependent cross-lane steps per row): many rows, many wavefronts
+  const unsigned threads = T > 16 ? 1024u : 256u;
+  vote_accept_kernel<<<dim3((unsigned)B), dim3(threads), vote_lds_bytes(T, K, rule), stream>>>(keys, draft_ids, parent, T,
+                                                                                          K, Kv, rule, out, part_b, geom);
   return hipGetLastError();
 }
 
