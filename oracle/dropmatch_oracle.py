@@ -51,8 +51,8 @@ listed with its reason in the design notes of the repository):
     rules (Eq. (4), (6), (7), Alg. 1) use paths 0..K-2 only;
   * Jensen-Shannon divergence (the paper names it without a formula): the standard
     JS(P||Q) = KL(P||M)/2 + KL(Q||M)/2 with M = (P+Q)/2, natural logarithm,
-    0 log 0 = 0; the two sides of Eq. (6) are compared after rounding each to
-    float32 (the precision the HIP path reports them in);
+    0 log 0 = 0; the two sides of Eq. (6) are compared in float64 (a test that compares
+    a float32 implementation with this owns the band around a tie);
   * the JS rule and Alg. 1 are defined for chains only (the paper uses tree
     decoding only together with naive token matching);
   * tree verification: parent[n] < n, node 0 is the root (always accepted); node n
@@ -183,6 +183,17 @@ def path_token(logits: np.ndarray):
     return y, float(top2[1] - top2[0])
 
 
+def tokens_within(values: np.ndarray, tol: float):
+    """Test support, not a step of the method: every index whose value is within `tol` of the
+    maximum, ascending, with its distance from the maximum.  These are the tokens a float32
+    implementation may legitimately return for a row whose top-1 is not clear of its rounding
+    errors; the parity tests accept exactly these and nothing else."""
+    values = np.asarray(values, dtype=np.float64)
+    deficit = np.max(values) - values
+    ids = np.nonzero(deficit <= float(tol))[0]
+    return ids.astype(np.int64), deficit[ids]
+
+
 def row_states(h_t, seed, step, tt, K, d, p, clean_last_path=False):
     """The K inputs of the LM head for one row, [K, d]: Eq. (1)-(2) for every path, except that
     with `clean_last_path` the last one is h_t itself (no mask, no scale)."""
@@ -227,17 +238,23 @@ def nucleus(z: np.ndarray, top_p: float):
     return q >= q[order[n - 1]], n
 
 
+def sampled_values(logits: np.ndarray, tau: float, g: np.ndarray, top_p=None) -> np.ndarray:
+    """The perturbed values logits[v] / tau + g[v] whose arg max is the Gumbel-max draw from
+    Softmax(logits / tau); with top_p, -inf outside the nucleus of that distribution."""
+    z = np.asarray(logits, dtype=np.float64) / float(tau)
+    y = z + g
+    if top_p is not None:
+        y = np.where(nucleus(z, top_p)[0], y, -np.inf)
+    return y
+
+
 def sampled_token(logits: np.ndarray, tau: float, g: np.ndarray, top_p=None):
     """Gumbel-max draw from Softmax(logits / tau): argmax_v (logits[v] / tau + g[v]), ties ->
     smallest v.  With top_p the arg max runs over the nucleus of that distribution only, which
     is a draw from the distribution renormalised on the nucleus (the noise of the other tokens
     is simply not looked at).  Also returns the top-1 minus top-2 gap of the perturbed values
     (inf when a single token is eligible)."""
-    z = np.asarray(logits, dtype=np.float64) / float(tau)
-    y = z + g
-    if top_p is not None:
-        y = np.where(nucleus(z, top_p)[0], y, -np.inf)
-    tok, gap = path_token(y)
+    tok, gap = path_token(sampled_values(logits, tau, g, top_p))
     return tok, (gap if np.isfinite(gap) else np.inf)
 
 
@@ -332,12 +349,11 @@ def js_divergence(P: np.ndarray, Q: np.ndarray) -> float:
 
 def js_rule(p_hat: np.ndarray, L: np.ndarray):
     """Eq. (6) for one position.  p_hat[V]: draft distribution; L[K, V]: path logits.
-    Returns (hit, js_draft, js_heads[K]).  The comparison is made on the float32
-    roundings of both sides."""
+    Returns (hit, js_draft, js_heads[K]).  The comparison is made in float64."""
     pbar = centroid(L)
     js_heads = np.array([js_divergence(softmax(L[i]), pbar) for i in range(L.shape[0])])
     js_draft = js_divergence(np.asarray(p_hat, dtype=np.float64), pbar)
-    hit = bool(np.float32(js_draft) <= np.float32(np.max(js_heads)))
+    hit = bool(js_draft <= np.max(js_heads))
     return hit, js_draft, js_heads
 
 
@@ -353,7 +369,7 @@ def algorithm1_hit(draft: int, p_hat: np.ndarray, L: np.ndarray, ids) -> bool:
 
 def verify_js(h, W, draft_ids, draft_probs, seeds, K: int, p, step: int = 0,
               rule: int = RULE_JS_OR_MAJORITY, share_mask_across_pos: bool = False,
-              clean_last_path: bool = False):
+              clean_last_path: bool = False, near_tol: float = 1e-2):
     """One verification step with the distribution-level rule (chains only).
 
     draft_probs [B, T, V]: the draft model's distribution for the token row t verifies
@@ -363,7 +379,8 @@ def verify_js(h, W, draft_ids, draft_probs, seeds, K: int, p, step: int = 0,
     Returns what verify() returns plus js_draft[B,T] (-1 at rows without a draft
     token), js_heads[B,T,K] (0 in the slot of a clean last path), and js_margin[B,T] =
     max_i js_heads - js_draft (the
-    distance of the Eq. (6) decision from a tie; +inf at rows without a draft token).
+    distance of the Eq. (6) decision from a tie; +inf at rows without a draft token), and
+    `near` as verify() does.
     """
     if rule not in (RULE_JS, RULE_JS_OR_MAJORITY):
         raise ValueError("verify_js takes RULE_JS or RULE_JS_OR_MAJORITY")
@@ -383,6 +400,7 @@ def verify_js(h, W, draft_ids, draft_probs, seeds, K: int, p, step: int = 0,
     js_heads = np.zeros((B, T, K))
     js_margin = np.full((B, T), np.inf)
     hit = np.zeros((B, T), dtype=np.uint8)
+    near = {}
     for b in range(B):
         for t in range(T):
             tt = 0 if share_mask_across_pos else t
@@ -390,6 +408,8 @@ def verify_js(h, W, draft_ids, draft_probs, seeds, K: int, p, step: int = 0,
             L = (W64 @ Hm.T).T                                   # Eq. (3), [K, V]
             for i in range(K):
                 path_ids[b, t, i], gap[b, t, i] = path_token(L[i])
+                if gap[b, t, i] <= near_tol:
+                    near[(b, t, i)] = tokens_within(L[i], near_tol)
             g = int(draft_ids[b, t])
             js_hit, jd, jh = js_rule(draft_probs[b, t], L[:KU])
             js_heads[b, t, :KU] = jh
@@ -405,7 +425,7 @@ def verify_js(h, W, draft_ids, draft_probs, seeds, K: int, p, step: int = 0,
     out = acceptance_from_hits(hit)
     votes = acceptance_from_path_ids(path_ids[:, :, :KU], draft_ids, RULE_MAJORITY)
     out.update(vote_ids=votes["vote_ids"], vote_cnt=votes["vote_cnt"], path_ids=path_ids, gap=gap,
-               js_draft=js_draft, js_heads=js_heads, js_margin=js_margin)
+               js_draft=js_draft, js_heads=js_heads, js_margin=js_margin, near=near, near_tol=float(near_tol))
     return out
 
 
@@ -426,7 +446,7 @@ def acceptance_from_hits(hit):
 # --------------------------------------------------------------------------- #
 def verify(h, W, draft_ids, seeds, K: int, p, step: int = 0, rule: int = RULE_ANY,
            share_mask_across_pos: bool = False, parent=None, want_logits=None,
-           clean_last_path: bool = False, temperature=None, top_p=None):
+           clean_last_path: bool = False, temperature=None, top_p=None, near_tol: float = 1e-2):
     """One DropMatch verification step for B sequences.
 
     h          [B, T, d]  final hidden states (any float dtype; used as float64)
@@ -439,10 +459,13 @@ def verify(h, W, draft_ids, seeds, K: int, p, step: int = 0, rule: int = RULE_AN
                Softmax(l / temperature) (see sampled_token; a clean last path stays arg max);
                `gap` then refers to the perturbed values
     top_p      with a temperature: sample from the nucleus of that distribution only (see nucleus)
+    near_tol   test support: for every row whose gap is at most near_tol, `near[(b, t, i)]` lists the
+               tokens whose (perturbed) value is within near_tol of the row's maximum, with their
+               distances from it (see tokens_within)
 
     Returns a dict of numpy arrays: path_ids[B,T,K], gap[B,T,K] (top-1 minus top-2
     logit of each path), vote_ids[B,T], vote_cnt[B,T], hit[B,T], accept_mask[B,T],
-    accept_len[B], best_node[B] (and logits if asked).
+    accept_len[B], best_node[B], near, near_tol (and logits if asked).
     """
     h = np.asarray(h, dtype=np.float64)
     W64 = np.asarray(W, dtype=np.float64)
@@ -454,6 +477,7 @@ def verify(h, W, draft_ids, seeds, K: int, p, step: int = 0, rule: int = RULE_AN
 
     path_ids = np.zeros((B, T, K), dtype=np.int32)
     gap = np.zeros((B, T, K), dtype=np.float64)
+    near = {}
     logits_out = None
     if want_logits is not None:
         v0, v1 = want_logits
@@ -467,10 +491,14 @@ def verify(h, W, draft_ids, seeds, K: int, p, step: int = 0, rule: int = RULE_AN
             L = W64 @ Hm.T                                       # Eq. (3), [V, K]
             for i in range(K):
                 if temperature is None or (clean_last_path and i == K - 1):
-                    path_ids[b, t, i], gap[b, t, i] = path_token(L[:, i])
+                    values = L[:, i]
+                    path_ids[b, t, i], gap[b, t, i] = path_token(values)
                 else:
                     g = gumbel_noise(sampling_uniforms(seeds[b], step, t, i, V))
+                    values = sampled_values(L[:, i], temperature, g, top_p)
                     path_ids[b, t, i], gap[b, t, i] = sampled_token(L[:, i], temperature, g, top_p)
+                if gap[b, t, i] <= near_tol:
+                    near[(b, t, i)] = tokens_within(values, near_tol)
                 if logits_out is not None:
                     logits_out[(b * T + t) * K + i] = L[v0:v1, i]
 
@@ -478,6 +506,8 @@ def verify(h, W, draft_ids, seeds, K: int, p, step: int = 0, rule: int = RULE_AN
     out = acceptance_from_path_ids(path_ids[:, :, :KU], draft_ids, rule, parent)
     out["path_ids"] = path_ids
     out["gap"] = gap
+    out["near"] = near
+    out["near_tol"] = float(near_tol)
     if logits_out is not None:
         out["logits"] = logits_out
     return out

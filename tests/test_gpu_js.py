@@ -44,7 +44,7 @@ def _check(runner, wl, W, h, seeds, draft, probs, rule, label):
     ref = orc.verify_js(h, W, draft, probs, seeds, wl.K, wl.p, rule=o_rule)
     hd, Wd = to_device(h, wl.dtype), to_device(W, wl.dtype)
     res = runner.verify_js(wl, hd, Wd, draft, probs, seeds, rule=rule)
-    nflip, nnear = compare_path_ids(res["path_ids"], ref["path_ids"], ref["gap"])
+    nflip, nnear = compare_path_ids(res["path_ids"], ref)
     votes = orc.acceptance_from_path_ids(res["path_ids"], draft, orc.RULE_MAJORITY)
     assert np.array_equal(res["vote_ids"], votes["vote_ids"]) and np.array_equal(res["vote_cnt"], votes["vote_cnt"])
     n_tie, gpu_js = compare_js(res, ref, draft, rule == dmb.DM_RULE_JS, nflip, label)
@@ -201,7 +201,7 @@ def test_js_with_clean_last_path(runner, K):
     flag = dmb.DM_FLAG_CLEAN_LAST_PATH
     ref = orc.verify_js(h, W, draft, probs, seeds, K, wl.p, rule=orc.RULE_JS_OR_MAJORITY, clean_last_path=True)
     res = runner.verify_js(wl, hd, Wd, draft, probs, seeds, rule=dmb.DM_RULE_JS_OR_MAJORITY, flags=flag)
-    nflip, _ = compare_path_ids(res["path_ids"], ref["path_ids"], ref["gap"])
+    nflip, _ = compare_path_ids(res["path_ids"], ref)
     assert np.array_equal(res["path_ids"][:, :, -1], orc.greedy_ids(h, W))
     assert np.all(res["js_heads"][:, :, -1] == 0)
     n_tie, gpu_js = compare_js(res, ref, draft, False, nflip, f"js clean K={K}")

@@ -35,8 +35,7 @@ def _problem(name, d, V, dtype, B, T, K, p, seed, bonus=False):
 
 
 def _check_against_oracle(res, ref, draft, rule, parent=None, label=""):
-    ndiff, nnear = compare_path_ids(res["path_ids"], ref["path_ids"], ref["gap"])
-    print(f"[{label}] rows={ref['gap'].size} near-tie rows(gap<1e-3)={nnear} path-token flips={ndiff}", flush=True)
+    ndiff, nnear = compare_path_ids(res["path_ids"], ref, label=label)
     expect = ref if ndiff == 0 else orc.acceptance_from_path_ids(res["path_ids"], draft, rule, parent)
     for k in ("vote_ids", "vote_cnt", "hit", "accept_mask", "accept_len", "best_node"):
         assert np.array_equal(res[k], expect[k]), f"{label}: {k} differs"
@@ -452,10 +451,8 @@ def test_sampled_path_tokens(runner, d, V, B, T, K, dtype, tau):
     for rule, step in ((orc.RULE_ANY, 0), (orc.RULE_MAJORITY, 5)):
         ref = orc.verify(h, W, draft, seeds, K, wl.p, rule=rule, step=step, temperature=tau)
         res = runner.verify(wl, hd, Wd, draft, seeds, rule=rule, step=step, flags=flag, temperature=tau)
-        mism = res["path_ids"] != ref["path_ids"]
-        assert not (mism & (ref["gap"] >= tol)).any(), "sampled token differs at a row with a clear winner"
-        print(f"[sampled {dtype} M={B*T*K} tau={tau}] near-tie rows={int((ref['gap'] < tol).sum())} flips={int(mism.sum())}", flush=True)
-        exp = ref if not mism.any() else orc.acceptance_from_path_ids(res["path_ids"], draft, rule)
+        nflip, _ = compare_path_ids(res["path_ids"], ref, tol=tol, label=f"sampled {dtype} M={B*T*K} tau={tau}")
+        exp = ref if nflip == 0 else orc.acceptance_from_path_ids(res["path_ids"], draft, rule)
         for k in ("vote_ids", "vote_cnt", "hit", "accept_mask", "accept_len", "best_node"):
             assert np.array_equal(res[k], exp[k]), k
     plain = runner.verify(wl, hd, Wd, draft, seeds)
@@ -466,8 +463,7 @@ def test_sampled_path_tokens(runner, d, V, B, T, K, dtype, tau):
     both = runner.verify(wl, hd, Wd, draft, seeds, flags=flag | dmb.DM_FLAG_CLEAN_LAST_PATH, temperature=tau)
     assert np.array_equal(both["path_ids"][:, :, -1], orc.greedy_ids(h, W))
     refc = orc.verify(h, W, draft, seeds, K, wl.p, temperature=tau, clean_last_path=True)
-    ok = refc["gap"] >= tol
-    assert np.array_equal(both["path_ids"][ok], refc["path_ids"][ok])
+    compare_path_ids(both["path_ids"], refc, tol=tol, label="sampled + clean last path")
 
 
 def test_sampling_frequencies_on_the_gpu(runner):

@@ -249,14 +249,17 @@ def test_algorithm1_accepts_superset_of_each_rule():
         assert np.array_equal(alg["vote_ids"], maj["vote_ids"]) and np.array_equal(alg["vote_cnt"], maj["vote_cnt"])
 
 
-def test_float32_comparison_of_eq6():
-    # two sides that differ only below float32 resolution count as a tie -> accepted
+def test_float64_comparison_of_eq6():
+    # Eq. (6) is decided in float64: a draft distribution equal to a head sits exactly on the
+    # boundary (<= accepts), one a hair farther from the centroid is rejected although the two
+    # sides agree to float32 resolution
     L = np.array([[0.2, 0.0], [0.0, 0.2]])
-    pbar = orc.centroid(L)
     head = orc.softmax(L[0])
-    phat = head + np.array([1e-12, -1e-12])      # a hair farther from the centroid than the head
+    hit, jd, jh = orc.js_rule(head, L)
+    assert jd == jh.max() and hit
+    phat = head + np.array([1e-12, -1e-12])
     hit, jd, jh = orc.js_rule(phat, L)
-    assert jd > jh.max() and np.float32(jd) == np.float32(jh.max()) and hit
+    assert jd > jh.max() and np.float32(jd) == np.float32(jh.max()) and not hit
 
 
 def test_draft_probs_generator_shapes_and_topk():
