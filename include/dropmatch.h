@@ -112,7 +112,11 @@ typedef struct {
   int32_t V;       /* vocabulary size */
   int32_t dtype;   /* dm_dtype */
   float p;         /* p_drop, 0 <= p < 1 (Eq. 1) */
-  uint32_t step;   /* Philox counter word 3: vary per decode step to get fresh masks from fixed seeds */
+  uint32_t step;   /* Philox counter word 3: vary per decode step to get fresh masks from fixed seeds.
+                      seeds and step are read on the host and travel as kernel arguments: a call
+                      captured into a HIP graph replays the masks (and sampling noise) it was
+                      captured with; capture one graph per step value, or update the kernel node
+                      parameters, to get fresh masks from replays */
   int32_t rule;    /* dm_rule */
   uint32_t flags;  /* DM_FLAG_* */
   const uint64_t* seeds; /* HOST [B]: mask seed per sequence; read before the call returns */
@@ -126,8 +130,10 @@ typedef struct {
 
 /* Create a context on HIP device `device` able to serve calls with B*T*K <= max_rows,
  * d <= max_d, V <= max_V.  Allocates the workspace (masked rows: max_rows rounded up to
- * 256 times max_d rounded up to 64 elements of 4 bytes, plus 16 bytes per row; for max_rows > 128
- * also 256 KB per compute unit, 64 MB on an MI355X, for the noise of sampled path tokens).  The context
+ * 256 times max_d rounded up to 64 elements of 4 bytes, plus 16 bytes per row).  One more buffer is
+ * allocated later, by the first dropmatch_verify with DM_FLAG_SAMPLE_PATHS on more than 128 rows:
+ * 256 KB per compute unit, 64 MB on an MI355X, for the noise of sampled path tokens (make that first
+ * call outside a stream capture).  The context
  * may be used from one host thread at a time; calls on one context must be enqueued on
  * one stream (or be ordered by the caller), since they share the workspace. */
 dm_status dm_create(dm_ctx** out, int device, int64_t max_rows, int32_t max_d, int32_t max_V);

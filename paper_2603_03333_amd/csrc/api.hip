@@ -20,7 +20,7 @@ struct dm_ctx {
   unsigned long long* keys = nullptr; // packed (logit, index) argmax per row
   unsigned int* done = nullptr;       // workgroups done, for the acceptance step fused into the contraction
   uint64_t* seeds_dev = nullptr;      // seeds of the current call, for the sampling epilogues
-  float* noise = nullptr;             // Gumbel noise of one tile per workgroup of the 256 x 256 kernel
+  float* noise = nullptr;             // Gumbel noise of one tile per workgroup of the 256 x 256 kernel (allocated on first use)
   // distribution-level rule (dm_reserve_js): stored logits and per-chunk partial sums
   float* lt = nullptr;
   size_t lt_floats = 0;
@@ -45,7 +45,7 @@ namespace {
 
 constexpr int kEv = 6;  // events per recorded call: before mask | lmhead | js_stats | js_terms | vote | end
 
-char g_err[512] = {0};  // failures that have no context (dm_create, NULL ctx)
+thread_local char g_err[512] = {0};  // failures that have no context (dm_create, NULL ctx), per host thread
 
 dm_status fail(dm_ctx* ctx, dm_status st, const char* fmt, ...) {
   char* buf = ctx ? ctx->err : g_err;
@@ -163,7 +163,7 @@ struct DeviceGuard {
 dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g, bool mfma, const void* h,
                           const void* W, float* logits, int v0, int v1, hipStream_t s, hipEvent_t* ev = nullptr,
                           dm::LogitStore store = dm::LogitStore{nullptr, 0, 0, 0, 0},
-                          const dm::VoteFuse* fuse = nullptr, bool* fused = nullptr) {
+                          const dm::VoteFuse* fuse = nullptr, bool* fused = nullptr, int64_t nucleus_rows = 0) {
   if (fused) *fused = false;
   store.K = p->K;  // the debug dump needs K and the clean-path flag even when nothing is stored
   store.clean_last = g.clean_last;
@@ -172,8 +172,15 @@ dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g,
   if (ev && all_stages) (void)hipEventRecord(ev[0], s);
   const bool want_seeds = (p->flags & DM_FLAG_SAMPLE_PATHS) && logits == nullptr;
   const bool sample = want_seeds && store.lt == nullptr;  // stored logits: the draw is made from them afterwards
+  // the first kernel of the call also puts back to zero what the later ones count in
+  dm::CallReset reset;
+  reset.counter = ctx->done;
+  if (nucleus_rows > 0) {
+    reset.zero64 = ctx->nuc.hist;
+    reset.n64 = nucleus_rows * 256;
+  }
   hipError_t e = dm::launch_mask_rows(h, ctx->a_ws, ctx->keys, p->seeds, g, bf16, mfma,
-                                      want_seeds ? ctx->seeds_dev : nullptr, s);
+                                      want_seeds ? ctx->seeds_dev : nullptr, reset, s);
   if (e != hipSuccess) return fail_hip(ctx, "mask_rows launch", e);
   // all stages: events on the stream around every kernel; otherwise the two events take the
   // timestamps of the contraction launch itself
@@ -284,8 +291,20 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
   dm::VoteFuse fuse{ctx->done, draft_ids, prm->parent, prm->B, prm->T, prm->K, Kv, prm->rule, out};
   const bool want_fuse = !js && !(prm->flags & DM_FLAG_SEPARATE_VOTE);
   bool fused = false;
+  // sampled tokens on the 256 x 256 kernel: its copy wavefronts leave a tile of noise (256 KB) per workgroup,
+  // at most one workgroup per compute unit; allocated by the first call that needs it
+  if ((prm->flags & DM_FLAG_SAMPLE_PATHS) && !nucleus && mfma && g.M > 128 && ctx->noise == nullptr) {
+    const hipError_t ea = hipMalloc((void**)&ctx->noise, (size_t)ctx->num_cu * 256 * 256 * 4);
+    if (ea != hipSuccess) {
+      (void)hipGetLastError();
+      ctx->noise = nullptr;
+      return fail(ctx, DM_ENOMEM, "noise scratch of %zu bytes for sampled path tokens could not be allocated: %s "
+                  "(the first such call allocates; make it outside a stream capture)",
+                  (size_t)ctx->num_cu * 256 * 256 * 4, hipGetErrorString(ea));
+    }
+  }
   if (dm_status st = run_contraction(ctx, prm, g, mfma, h, W, nullptr, 0, 0, s, ev, store, want_fuse ? &fuse : nullptr,
-                                     &fused))
+                                     &fused, nucleus ? (int64_t)ng.P * ng.K : 0))
     return st;
   hipError_t e;
   if (js) {
@@ -371,11 +390,7 @@ dm_status dm_create(dm_ctx** out, int device, int64_t max_rows, int32_t max_d, i
   if ((e = hipMalloc(&ctx->a_ws, a_bytes)) != hipSuccess ||
       (e = hipMalloc((void**)&ctx->keys, (size_t)ctx->rows_pad * 8)) != hipSuccess ||
       (e = hipMalloc((void**)&ctx->done, 256)) != hipSuccess || (e = hipMemset(ctx->done, 0, 256)) != hipSuccess ||
-      (e = hipMalloc((void**)&ctx->seeds_dev, (size_t)ctx->rows_pad * 8)) != hipSuccess ||
-      // more than 128 rows go to the 256 x 256 kernel, whose copy wavefronts leave a tile of noise (256 KB)
-      // per workgroup (at most one per compute unit) when path tokens are sampled
-      (max_rows > 128 &&
-       (e = hipMalloc((void**)&ctx->noise, (size_t)ctx->num_cu * 256 * 256 * 4)) != hipSuccess)) {
+      (e = hipMalloc((void**)&ctx->seeds_dev, (size_t)ctx->rows_pad * 8)) != hipSuccess) {
     (void)hipGetLastError();
     if (ctx->a_ws) (void)hipFree(ctx->a_ws);
     if (ctx->keys) (void)hipFree(ctx->keys);

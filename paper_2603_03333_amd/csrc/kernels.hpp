@@ -28,9 +28,17 @@ struct RowGeom {
 // per-row argmax keys reset to 0.  swizzled = layout of the MFMA kernel's B-fragments;
 // otherwise plain [M_pad, d_pad].  is_bf16 selects the element type of h and the workspace.
 // seeds_dev (optional): DEVICE [B], receives the seeds (for the sampling epilogues of the same call).
+// Per-call state of the later kernels of the same call is put back to zero here as well, so that a
+// call never depends on an earlier one having run to its end: the election counter of the fused
+// acceptance step and the digit histograms of the nucleus search.
+struct CallReset {
+  unsigned int* counter = nullptr;        // one word, or null
+  unsigned long long* zero64 = nullptr;   // n64 words, or null
+  int64_t n64 = 0;
+};
 hipError_t launch_mask_rows(const void* h, void* a_ws, unsigned long long* keys, const uint64_t* seeds_host,
                             const RowGeom& g, bool is_bf16, bool swizzled, uint64_t* seeds_dev,
-                            hipStream_t stream);
+                            const CallReset& reset, hipStream_t stream);
 
 // Eq. (1) only, bit-packed [M, ceil(d/32)].
 hipError_t launch_mask_bits(uint32_t* bits, const uint64_t* seeds_host, const RowGeom& g, hipStream_t stream);
@@ -132,7 +140,7 @@ struct VoteOut {
 // part_b / jg: partial JS sums of launch_js_terms (rules 2 and 3), else nullptr.
 // Acceptance step run as the tail of the contraction kernel: every workgroup bumps `counter` when
 // its argmax keys are merged, and the workgroup that finds it at (workgroups - 1) runs the step for
-// all B sequences and puts the counter back to 0.  counter == nullptr: not fused.
+// all B sequences.  The mask kernel of every call puts the counter to 0.  counter == nullptr: not fused.
 struct VoteFuse {
   unsigned int* counter;
   const int32_t* draft_ids;
@@ -169,7 +177,7 @@ struct NucGeom {
   int V;
 };
 struct NucBuffers {
-  unsigned long long* hist;    // [rows][256] masses per digit, zero between calls
+  unsigned long long* hist;    // [rows][256] masses per digit; zeroed by the mask kernel of the call, and by every scan
   uint32_t* prefix;            // [rows] bits of the threshold fixed so far
   unsigned long long* below;   // [rows] mass of the elements below the digits fixed so far
   unsigned long long* target;  // [rows] mass the nucleus has to reach

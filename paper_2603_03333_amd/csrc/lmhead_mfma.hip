@@ -349,7 +349,8 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
   // -------------------------------------------------------------------- fused acceptance step
   // Every thread waits until its own argmax merges are done, the workgroup meets, one thread bumps
   // the counter; the workgroup that sees all others done reads the final keys and runs the vote /
-  // rule / prefix step, then clears the counter for the next call.  The merges, the counter and the
+  // rule / prefix step.  (The counter starts at 0: the mask kernel of every call resets it, so a
+  // launch that did not finish cannot leave later calls without an elected workgroup.)  The merges, the counter and the
   // reads of the keys are all device-scope atomic operations, which are carried out at the memory
   // side, past the per-XCD L2s; that is what makes the keys of other XCDs visible here.  A device
   // scope fence is deliberately not used: it writes back and invalidates the XCD's whole L2, which the
@@ -373,7 +374,6 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
                                fuse.T, fuse.K, fuse.Kv, fuse.rule, fuse.out, nullptr, JsGeom{});
         __syncthreads();
       }
-      if (tid == 0) atomicExch(fuse.counter, 0u);
     }
   }
 }

@@ -4,7 +4,8 @@
 // across a wavefront, so the K paths of one position read the same 16 bytes of h (a broadcast
 // in the memory pipeline) and 32 consecutive rows write 512 contiguous bytes of the workspace.
 // Two Philox calls give the 8 keep bits.  The thread that handles dimension group 0 also
-// resets the row's packed argmax key.
+// resets the row's packed argmax key; the first launch of a call also puts the per-call state of
+// the later kernels (CallReset) back to zero.
 #include "kernels.hpp"
 #include "philox.hpp"
 
@@ -28,9 +29,12 @@ template <typename T, bool SWIZZLED>
 __global__ __launch_bounds__(256) void mask_rows_kernel(const T* __restrict__ h, T* __restrict__ a_ws,
                                                         unsigned long long* __restrict__ keys, SeedPack seeds,
                                                         RowGeom g, int64_t row0, int64_t nrows, int b0,
-                                                        uint64_t* __restrict__ seeds_dev, int nb) {
+                                                        uint64_t* __restrict__ seeds_dev, int nb,
+                                                        CallReset reset) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (seeds_dev != nullptr && idx < nb) seeds_dev[b0 + idx] = seeds.s[idx];  // for the sampling epilogues
+  if (reset.counter != nullptr && idx == 0) *reset.counter = 0u;
+  for (int64_t x = idx; x < reset.n64; x += (int64_t)gridDim.x * blockDim.x) reset.zero64[x] = 0ull;
   const int ngroups = g.d_pad >> 3;
   if (idx >= nrows * ngroups) return;
   const int64_t r = row0 + idx % nrows;
@@ -106,7 +110,7 @@ __global__ __launch_bounds__(256) void mask_bits_kernel(uint32_t* __restrict__ b
 
 template <typename T, bool SW>
 hipError_t run_mask_rows(const void* h, void* a_ws, unsigned long long* keys, const uint64_t* seeds_host,
-                         const RowGeom& g, uint64_t* seeds_dev, hipStream_t stream) {
+                         const RowGeom& g, uint64_t* seeds_dev, const CallReset& reset, hipStream_t stream) {
   const int64_t TK = (int64_t)g.T * g.K;
   for (int b0 = 0; b0 < g.B; b0 += kSeedsPerLaunch) {
     const int nb = (g.B - b0 < kSeedsPerLaunch) ? (g.B - b0) : kSeedsPerLaunch;
@@ -120,7 +124,8 @@ hipError_t run_mask_rows(const void* h, void* a_ws, unsigned long long* keys, co
     const int64_t nblocks = (nthreads + 255) / 256;
     if (nblocks > 0x7FFFFFFF) return hipErrorInvalidValue;
     mask_rows_kernel<T, SW><<<dim3((unsigned)nblocks), dim3(256), 0, stream>>>(
-        static_cast<const T*>(h), static_cast<T*>(a_ws), keys, sp, g, row0, nrows, b0, seeds_dev, nb);
+        static_cast<const T*>(h), static_cast<T*>(a_ws), keys, sp, g, row0, nrows, b0, seeds_dev, nb,
+        b0 == 0 ? reset : CallReset{});
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -131,12 +136,12 @@ hipError_t run_mask_rows(const void* h, void* a_ws, unsigned long long* keys, co
 
 hipError_t launch_mask_rows(const void* h, void* a_ws, unsigned long long* keys, const uint64_t* seeds_host,
                             const RowGeom& g, bool is_bf16, bool swizzled, uint64_t* seeds_dev,
-                            hipStream_t stream) {
+                            const CallReset& reset, hipStream_t stream) {
   if (is_bf16)
-    return swizzled ? run_mask_rows<uint16_t, true>(h, a_ws, keys, seeds_host, g, seeds_dev, stream)
-                    : run_mask_rows<uint16_t, false>(h, a_ws, keys, seeds_host, g, seeds_dev, stream);
+    return swizzled ? run_mask_rows<uint16_t, true>(h, a_ws, keys, seeds_host, g, seeds_dev, reset, stream)
+                    : run_mask_rows<uint16_t, false>(h, a_ws, keys, seeds_host, g, seeds_dev, reset, stream);
   if (swizzled) return hipErrorInvalidValue;
-  return run_mask_rows<float, false>(h, a_ws, keys, seeds_host, g, seeds_dev, stream);
+  return run_mask_rows<float, false>(h, a_ws, keys, seeds_host, g, seeds_dev, reset, stream);
 }
 
 hipError_t launch_mask_bits(uint32_t* bits, const uint64_t* seeds_host, const RowGeom& g, hipStream_t stream) {

@@ -15,6 +15,33 @@ def to_device(x: np.ndarray, dtype: str) -> torch.Tensor:
     return t.cuda()
 
 
+GUARD = 64      # canary elements in front of and behind every output buffer
+
+
+class Guarded:
+    """Output tensors with canary elements on both sides: the library gets a pointer into the middle
+    of a larger allocation, and check() fails if anything outside the tensor's own elements changed."""
+
+    def __init__(self, device="cuda"):
+        self.bufs = {}
+        self.device = device
+
+    def make(self, name, shape, dtype, fill):
+        n = int(np.prod(shape))
+        canary = 0xA5 if dtype == torch.uint8 else (float("-inf") if dtype.is_floating_point else -0x5EED5EED)
+        buf = torch.full((n + 2 * GUARD,), canary, dtype=dtype, device=self.device)
+        view = buf[GUARD:GUARD + n].view(shape)
+        view.fill_(fill)
+        self.bufs[name] = (buf, n, canary)
+        return view
+
+    def check(self):
+        for name, (buf, n, canary) in self.bufs.items():
+            edge = torch.cat([buf[:GUARD], buf[GUARD + n:]]).cpu().numpy()
+            want = np.full(edge.shape, canary, dtype=edge.dtype)
+            assert np.array_equal(edge, want), f"{name}: the library wrote outside the output buffer"
+
+
 class Runner:
     """Owns a context sized for one workload shape."""
 
@@ -40,17 +67,19 @@ class Runner:
         par_dev = None if parent is None else torch.from_numpy(np.ascontiguousarray(parent, dtype=np.int32)).cuda()
         prm, keep = self.params(wl, seeds, parent=par_dev, **kw)
         draft_dev = torch.from_numpy(np.ascontiguousarray(draft, dtype=np.int32)).cuda()
+        guard = Guarded()
         out = dict(
-            accept_len=torch.full((B,), -7, dtype=torch.int32, device=dev),
-            best_node=torch.full((B,), -7, dtype=torch.int32, device=dev),
-            accept_mask=torch.full((B, T), 9, dtype=torch.uint8, device=dev),
-            hit=torch.full((B, T), 9, dtype=torch.uint8, device=dev),
-            path_ids=torch.full((B, T, K), -7, dtype=torch.int32, device=dev),
-            vote_ids=torch.full((B, T), -7, dtype=torch.int32, device=dev),
-            vote_cnt=torch.full((B, T), -7, dtype=torch.int32, device=dev),
+            accept_len=guard.make("accept_len", (B,), torch.int32, -7),
+            best_node=guard.make("best_node", (B,), torch.int32, -7),
+            accept_mask=guard.make("accept_mask", (B, T), torch.uint8, 9),
+            hit=guard.make("hit", (B, T), torch.uint8, 9),
+            path_ids=guard.make("path_ids", (B, T, K), torch.int32, -7),
+            vote_ids=guard.make("vote_ids", (B, T), torch.int32, -7),
+            vote_cnt=guard.make("vote_cnt", (B, T), torch.int32, -7),
         )
         dmb.dropmatch_verify(self.ctx, prm, h_dev, W_dev, draft_dev, **out)
         torch.cuda.synchronize()
+        guard.check()
         del keep
         return {k: v.cpu().numpy() for k, v in out.items()}
 
@@ -65,19 +94,21 @@ class Runner:
         prm, keep = self.params(wl, seeds, rule=rule, **kw)
         draft_dev = torch.from_numpy(np.ascontiguousarray(draft, dtype=np.int32)).cuda()
         probs_dev = torch.from_numpy(np.ascontiguousarray(draft_probs, dtype=np.float32)).cuda()
+        guard = Guarded()
         out = dict(
-            accept_len=torch.full((B,), -7, dtype=torch.int32, device=dev),
-            best_node=torch.full((B,), -7, dtype=torch.int32, device=dev),
-            accept_mask=torch.full((B, T), 9, dtype=torch.uint8, device=dev),
-            hit=torch.full((B, T), 9, dtype=torch.uint8, device=dev),
-            path_ids=torch.full((B, T, K), -7, dtype=torch.int32, device=dev),
-            vote_ids=torch.full((B, T), -7, dtype=torch.int32, device=dev),
-            vote_cnt=torch.full((B, T), -7, dtype=torch.int32, device=dev),
-            js_draft=torch.full((B, T), float("nan"), dtype=torch.float32, device=dev),
-            js_heads=torch.full((B, T, K), float("nan"), dtype=torch.float32, device=dev),
+            accept_len=guard.make("accept_len", (B,), torch.int32, -7),
+            best_node=guard.make("best_node", (B,), torch.int32, -7),
+            accept_mask=guard.make("accept_mask", (B, T), torch.uint8, 9),
+            hit=guard.make("hit", (B, T), torch.uint8, 9),
+            path_ids=guard.make("path_ids", (B, T, K), torch.int32, -7),
+            vote_ids=guard.make("vote_ids", (B, T), torch.int32, -7),
+            vote_cnt=guard.make("vote_cnt", (B, T), torch.int32, -7),
+            js_draft=guard.make("js_draft", (B, T), torch.float32, float("nan")),
+            js_heads=guard.make("js_heads", (B, T, K), torch.float32, float("nan")),
         )
         dmb.dropmatch_verify_js(self.ctx, prm, h_dev, W_dev, draft_dev, probs_dev, **out)
         torch.cuda.synchronize()
+        guard.check()
         del keep
         return {k: v.cpu().numpy() for k, v in out.items()}
 
@@ -85,17 +116,21 @@ class Runner:
         K = kw.get("K") or wl.K
         nw = (wl.d + 31) // 32
         prm, keep = self.params(wl, seeds, **kw)
-        bits = torch.full((wl.B, wl.T, K, nw), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+        guard = Guarded()
+        bits = guard.make("bits", (wl.B, wl.T, K, nw), torch.int32, 0x5A5A5A5A)
         dmb.dm_debug_masks(self.ctx, prm, bits)
         torch.cuda.synchronize()
+        guard.check()
         return bits.cpu().numpy().view(np.uint32)
 
     def logits(self, wl, h_dev, W_dev, seeds, v0, v1, **kw):
         K = kw.get("K") or wl.K
         prm, keep = self.params(wl, seeds, **kw)
-        out = torch.full((wl.B * wl.T * K, v1 - v0), float("nan"), dtype=torch.float32, device="cuda")
+        guard = Guarded()
+        out = guard.make("logits", (wl.B * wl.T * K, v1 - v0), torch.float32, float("nan"))
         dmb.dm_debug_logits(self.ctx, prm, h_dev, W_dev, v0, v1, out)
         torch.cuda.synchronize()
+        guard.check()
         return out.cpu().numpy()
 
 

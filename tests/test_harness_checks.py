@@ -7,7 +7,8 @@ from oracle import dropmatch_oracle as orc
 from paper_2603_03333_amd import workloads as wk
 
 pytest.importorskip("torch")
-from gpu_harness import compare_path_ids  # noqa: E402
+import torch  # noqa: E402
+from gpu_harness import GUARD, Guarded, compare_path_ids  # noqa: E402
 
 
 def _near_tie_problem():
@@ -68,3 +69,20 @@ def test_sampled_values_agree_with_sampled_token():
         assert orc.tokens_within(y, 0.0)[0].tolist() == [tok]
     inside = orc.nucleus(l / 0.7, 0.6)[0]
     assert np.isneginf(y[~inside]).all() and np.isfinite(y[inside]).all()
+
+
+@pytest.mark.parametrize("dtype,fill", [(torch.int32, -7), (torch.uint8, 9), (torch.float32, float("nan"))])
+def test_guarded_outputs_catch_a_write_one_element_outside(dtype, fill):
+    g = Guarded(device="cpu")
+    v = g.make("x", (3, 5), dtype, fill)
+    assert v.shape == (3, 5) and v.is_contiguous()
+    v.fill_(1)                                   # writing every own element is fine
+    g.check()
+    buf = g.bufs["x"][0]
+    for where in (GUARD - 1, GUARD + 15):        # the element just before and just after
+        old = buf[where].clone()
+        buf[where] = 1
+        with pytest.raises(AssertionError, match="outside the output buffer"):
+            g.check()
+        buf[where] = old
+    g.check()
