@@ -230,6 +230,42 @@ dm_status dropmatch_verify_js(dm_ctx* ctx, const dm_params* prm,
                               float* js_heads,          /* DEVICE [B,T,K] or NULL */
                               void* stream);
 
+/*
+ * dropmatch_verify without a context and without any allocation, for callers that cannot allocate
+ * device memory: code that runs under a HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same step, same arguments and outputs as dropmatch_verify (token-level rules), with
+ * the HIP device number in place of the context.  Its workspace (masked rows, argmax keys, seeds,
+ * election counter) is a fixed array in device memory that is part of the library's code object:
+ * DM_STATIC_MAX_WS_BYTES + 16 bytes per row of DM_STATIC_MAX_ROWS + 256 bytes, about 8 MB, held by
+ * every GPU the library runs on until the process ends.  Nothing is allocated or freed, by this
+ * function or by anything it calls; nothing is synchronised.
+ * Limits (DM_EINVAL beyond them, nothing enqueued): B*T*K <= DM_STATIC_MAX_ROWS, and the masked rows
+ * must fit: roundup(B*T*K, 32 if B*T*K <= 128 [bf16, d % 64 == 0] else 256 [same] else 128) *
+ * roundup(d, 64) * (2 for bf16, 4 for f32) <= DM_STATIC_MAX_WS_BYTES (e.g. 1024 rows at d = 4096 in
+ * bf16).  DM_EUNSUPPORTED for the distribution-level rules and nucleus sampling (those need buffers
+ * that grow with the call; use a context).
+ * The first call on a device looks up the array's address and the device's properties (no allocation
+ * either, but make it outside a stream capture); later calls only enqueue kernels.
+ * All calls on one GPU share that GPU's array: calls that may overlap on one GPU (different streams
+ * without ordering, several host threads) race and must be ordered by the caller.  What a call needs
+ * to start from zero it clears itself, so an earlier call's contents never matter.
+ * Messages of failures: dm_last_error(NULL), per host thread.
+ */
+#define DM_STATIC_MAX_ROWS 2048
+#define DM_STATIC_MAX_WS_BYTES (8 * 1024 * 1024)
+dm_status dropmatch_verify_static(int device, const dm_params* prm,
+                                  const void* h,            /* DEVICE [B,T,d] contiguous */
+                                  const void* W,            /* DEVICE [V,d] row-major contiguous */
+                                  const int32_t* draft_ids, /* DEVICE [B,T] */
+                                  int32_t* accept_len,      /* DEVICE [B], required */
+                                  int32_t* best_node,       /* DEVICE [B] or NULL */
+                                  uint8_t* accept_mask,     /* DEVICE [B,T] or NULL */
+                                  uint8_t* hit,             /* DEVICE [B,T] or NULL */
+                                  int32_t* path_ids,        /* DEVICE [B,T,K] or NULL */
+                                  int32_t* vote_ids,        /* DEVICE [B,T] or NULL */
+                                  int32_t* vote_cnt,        /* DEVICE [B,T] or NULL */
+                                  void* stream);
+
 /* Debug: the keep-masks of Eq. 1 exactly as dropmatch_verify draws them, bit-packed.
  * bits: DEVICE uint32 [B,T,K,ceil(d/32)]; word w of a row holds dimensions 32w..32w+31,
  * bit (j & 31) = keep(j); bits past d are 0. */

@@ -22,7 +22,7 @@ LIB_PATH = os.path.join(_HERE, "libdropmatch.so")
 
 EXPORTS = ("dm_create", "dm_destroy", "dm_last_error", "dm_validate", "dropmatch_verify",
            "dm_debug_masks", "dm_debug_logits", "dm_kernel_choice", "dm_set_profiling", "dm_set_profiling_stride", "dm_get_profile",
-           "dm_get_profile_stages", "dm_reserve_js", "dropmatch_verify_js")
+           "dm_get_profile_stages", "dm_reserve_js", "dropmatch_verify_js", "dropmatch_verify_static")
 
 
 class dm_params(C.Structure):
@@ -67,6 +67,8 @@ def load_library():
     lib.dm_kernel_choice.restype = i32
     lib.dropmatch_verify.argtypes = [vp, C.POINTER(dm_params)] + [vp] * 11
     lib.dropmatch_verify.restype = C.c_int
+    lib.dropmatch_verify_static.argtypes = [C.c_int, C.POINTER(dm_params)] + [vp] * 11
+    lib.dropmatch_verify_static.restype = C.c_int
     lib.dm_debug_masks.argtypes = [vp, C.POINTER(dm_params), vp, vp]
     lib.dm_debug_masks.restype = C.c_int
     lib.dm_debug_logits.argtypes = [vp, C.POINTER(dm_params), vp, vp, i32, i32, vp, vp]
@@ -151,6 +153,15 @@ def dropmatch_verify(ctx, prm: dm_params, h, W, draft_ids, accept_len, best_node
     _check(ctx, st)
 
 
+def dropmatch_verify_static(device: int, prm: dm_params, h, W, draft_ids, accept_len, best_node=None, accept_mask=None,
+                            hit=None, path_ids=None, vote_ids=None, vote_cnt=None, stream=None) -> None:
+    """dropmatch_verify on the library's fixed workspace of GPU `device`: no context, no allocation."""
+    st = load_library().dropmatch_verify_static(device, C.byref(prm), _ptr(h), _ptr(W), _ptr(draft_ids),
+                                                _ptr(accept_len), _ptr(best_node), _ptr(accept_mask), _ptr(hit),
+                                                _ptr(path_ids), _ptr(vote_ids), _ptr(vote_cnt), _stream_handle(stream))
+    _check(None, st)
+
+
 def dm_reserve_js(ctx, max_positions: int, max_K: int) -> None:
     _check(ctx, load_library().dm_reserve_js(ctx, max_positions, max_K))
 
@@ -200,3 +211,4 @@ def dm_get_profile_stages(ctx):
     ms = (C.c_float * 5)()
     _check(ctx, load_library().dm_get_profile_stages(ctx, C.byref(n), ms))
     return n.value, [float(x) for x in ms]
+

@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "kernels.hpp"
@@ -21,6 +22,7 @@ struct dm_ctx {
   unsigned int* done = nullptr;       // workgroups done, for the acceptance step fused into the contraction
   uint64_t* seeds_dev = nullptr;      // seeds of the current call, for the sampling epilogues
   float* noise = nullptr;             // Gumbel noise of one tile per workgroup of the 256 x 256 kernel (allocated on first use)
+  bool borrowed = false;              // the workspace is the static device array: nothing is allocated or freed
   // distribution-level rule (dm_reserve_js): stored logits and per-chunk partial sums
   float* lt = nullptr;
   size_t lt_floats = 0;
@@ -58,6 +60,86 @@ dm_status fail(dm_ctx* ctx, dm_status st, const char* fmt, ...) {
 
 dm_status fail_hip(dm_ctx* ctx, const char* what, hipError_t e) {
   return fail(ctx, DM_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = true;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) != hipSuccess) { ok = false; return; }
+    if (prev != dev && hipSetDevice(dev) != hipSuccess) ok = false;
+  }
+  ~DeviceGuard() {
+    int cur = -1;
+    if (prev >= 0 && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
+  }
+};
+
+// ------------------------------------------------------------------ workspace for callers that cannot allocate
+// One array per GPU, held by every device the library's code object is loaded on until the process
+// ends.  In host code `dm_static_scratch` is only a handle for hipGetSymbolAddress: the device address
+// it returns (per device) is what kernels, copies and fills get.
+constexpr size_t kStaticRowBytes = (size_t)DM_STATIC_MAX_WS_BYTES;         // masked rows
+constexpr size_t kStaticKeysOff = kStaticRowBytes;                         // DM_STATIC_MAX_ROWS packed keys
+constexpr size_t kStaticSeedsOff = kStaticKeysOff + (size_t)DM_STATIC_MAX_ROWS * 8;  // as many seeds
+constexpr size_t kStaticDoneOff = kStaticSeedsOff + (size_t)DM_STATIC_MAX_ROWS * 8;  // election counter
+constexpr size_t kStaticBytes = kStaticDoneOff + 256;
+static_assert(kStaticRowBytes % 256 == 0 && DM_STATIC_MAX_ROWS % 256 == 0, "every part starts 256-byte aligned");
+static __device__ __align__(256) unsigned char dm_static_scratch[kStaticBytes];
+
+constexpr int kMaxStaticDevices = 64;
+struct StaticSlot {
+  bool ready = false;
+  dm_ctx ctx;  // a context whose workspace pointers point into the device's copy of the array
+};
+StaticSlot g_static[kMaxStaticDevices];
+std::mutex g_static_mutex;
+
+// Set-up of device `device`, once: address of its copy of the array, device properties, LDS limits of
+// the kernels.  No allocation.  On failure the message is left for dm_last_error(NULL).
+dm_status static_context(int device, dm_ctx** out) {
+  *out = nullptr;
+  if (device < 0 || device >= kMaxStaticDevices)
+    return fail(nullptr, DM_EINVAL, "device %d not in 0..%d", device, kMaxStaticDevices - 1);
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  StaticSlot& slot = g_static[device];
+  if (slot.ready) {
+    *out = &slot.ctx;
+    return DM_OK;
+  }
+  int ndev = 0;
+  hipError_t e = hipGetDeviceCount(&ndev);
+  if (e != hipSuccess) return fail_hip(nullptr, "hipGetDeviceCount", e);
+  if (device >= ndev) return fail(nullptr, DM_EINVAL, "device %d not in 0..%d", device, ndev - 1);
+  DeviceGuard guard(device);
+  if (!guard.ok) return fail(nullptr, DM_EHIP, "cannot select device %d", device);
+  hipDeviceProp_t prop;
+  if ((e = hipGetDeviceProperties(&prop, device)) != hipSuccess) return fail_hip(nullptr, "hipGetDeviceProperties", e);
+  if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+    return fail(nullptr, DM_EUNSUPPORTED, "device %d is %s; this library is built for gfx950 only", device, prop.gcnArchName);
+  // the device's own copy of the array (the device is current here)
+  unsigned char* base = nullptr;
+  if ((e = hipGetSymbolAddress((void**)&base, HIP_SYMBOL(dm_static_scratch))) != hipSuccess)
+    return fail_hip(nullptr, "hipGetSymbolAddress(static workspace)", e);
+  if (base == nullptr) return fail(nullptr, DM_EHIP, "hipGetSymbolAddress(static workspace) returned no address");
+  if ((e = dm::prepare_lmhead_mfma()) != hipSuccess || (e = dm::prepare_lmhead_mfma_big()) != hipSuccess ||
+      (e = dm::prepare_vote_accept()) != hipSuccess)
+    return fail_hip(nullptr, "raising the dynamic LDS limit", e);
+  dm_ctx& c = slot.ctx;
+  c.device = device;
+  c.num_cu = prop.multiProcessorCount;
+  c.max_rows = DM_STATIC_MAX_ROWS;
+  c.max_d = 0x7FFFFFFF;  // bounded by the byte size of the masked rows instead
+  c.max_V = 0x7FFFFFFF;
+  c.rows_pad = DM_STATIC_MAX_ROWS;
+  c.a_ws = base;
+  c.keys = reinterpret_cast<unsigned long long*>(base + kStaticKeysOff);
+  c.seeds_dev = reinterpret_cast<uint64_t*>(base + kStaticSeedsOff);
+  c.done = reinterpret_cast<unsigned int*>(base + kStaticDoneOff);
+  c.borrowed = true;
+  slot.ready = true;
+  *out = &c;
+  return DM_OK;
 }
 
 // Reason a parameter block is unusable, or nullptr.
@@ -145,18 +227,6 @@ dm_status make_geom(dm_ctx* ctx, const dm_params* p, bool mfma, dm::RowGeom* g) 
   return DM_OK;
 }
 
-struct DeviceGuard {
-  int prev = -1;
-  bool ok = true;
-  explicit DeviceGuard(int dev) {
-    if (hipGetDevice(&prev) != hipSuccess) { ok = false; return; }
-    if (prev != dev && hipSetDevice(dev) != hipSuccess) ok = false;
-  }
-  ~DeviceGuard() {
-    int cur = -1;
-    if (prev >= 0 && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
-  }
-};
 
 // Eq. (1)-(3) + argmax keys; shared by dropmatch_verify and dm_debug_logits.
 // `ev` (optional): 3 events recorded before the mask kernel, between the two kernels, after.
@@ -293,7 +363,7 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
   bool fused = false;
   // sampled tokens on the 256 x 256 kernel: its copy wavefronts leave a tile of noise (256 KB) per workgroup,
   // at most one workgroup per compute unit; allocated by the first call that needs it
-  if ((prm->flags & DM_FLAG_SAMPLE_PATHS) && !nucleus && mfma && g.M > 128 && ctx->noise == nullptr) {
+  if ((prm->flags & DM_FLAG_SAMPLE_PATHS) && !nucleus && mfma && g.M > 128 && ctx->noise == nullptr && !ctx->borrowed) {
     const hipError_t ea = hipMalloc((void**)&ctx->noise, (size_t)ctx->num_cu * 256 * 256 * 4);
     if (ea != hipSuccess) {
       (void)hipGetLastError();
@@ -412,6 +482,36 @@ dm_status dm_create(dm_ctx** out, int device, int64_t max_rows, int32_t max_d, i
   }
   *out = ctx;
   return DM_OK;
+}
+
+dm_status dropmatch_verify_static(int device, const dm_params* prm, const void* h, const void* W,
+                                  const int32_t* draft_ids, int32_t* accept_len, int32_t* best_node,
+                                  uint8_t* accept_mask, uint8_t* hit, int32_t* path_ids, int32_t* vote_ids,
+                                  int32_t* vote_cnt, void* stream) {
+  dm_ctx* ctx = nullptr;
+  if (dm_status st = static_context(device, &ctx)) return st;
+  // limits of the fixed workspace, checked before anything is enqueued
+  char scratch[128];
+  if (const char* why = check_params(prm, scratch, sizeof scratch)) return fail(nullptr, DM_EINVAL, "%s", why);
+  if (prm->rule >= DM_RULE_JS)
+    return fail(nullptr, DM_EUNSUPPORTED, "dropmatch_verify_static takes the token-level rules only (the others keep every logit)");
+  const int64_t M = (int64_t)prm->B * prm->T * prm->K;
+  if (M > DM_STATIC_MAX_ROWS || prm->B > DM_STATIC_MAX_ROWS)
+    return fail(nullptr, DM_EINVAL, "B*T*K = %lld exceeds DM_STATIC_MAX_ROWS = %d", (long long)M, DM_STATIC_MAX_ROWS);
+  const bool mfma = use_mfma(prm);
+  const int64_t M_pad = mfma ? (M <= 128 ? round_up(M, 32) : round_up(M, 256)) : round_up(M, 128);
+  const int64_t ws = M_pad * round_up(prm->d, 64) * (prm->dtype == DM_BF16 ? 2 : 4);
+  if (ws > (int64_t)DM_STATIC_MAX_WS_BYTES)
+    return fail(nullptr, DM_EINVAL, "the masked rows of this call take %lld bytes, more than DM_STATIC_MAX_WS_BYTES = %d",
+                (long long)ws, DM_STATIC_MAX_WS_BYTES);
+  if ((prm->flags & DM_FLAG_SAMPLE_PATHS) && prm->top_p > 0.0f && prm->top_p < 1.0f)
+    return fail(nullptr, DM_EUNSUPPORTED, "dropmatch_verify_static does not sample from a nucleus (that keeps every logit)");
+  // (sampled path tokens on more than 128 rows draw their noise in the epilogue here: the noise buffer
+  // of the faster variant is not part of the fixed workspace)
+  const dm_status st = verify_impl(ctx, prm, h, W, draft_ids, nullptr, accept_len, best_node, accept_mask, hit, path_ids,
+                                   vote_ids, vote_cnt, nullptr, nullptr, stream);
+  if (st != DM_OK) snprintf(g_err, sizeof g_err, "%s", ctx->err);
+  return st;
 }
 
 dm_status dm_destroy(dm_ctx* ctx) {
