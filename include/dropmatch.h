@@ -277,6 +277,12 @@ dm_status dm_debug_masks(dm_ctx* ctx, const dm_params* prm, uint32_t* bits, void
 dm_status dm_debug_logits(dm_ctx* ctx, const dm_params* prm, const void* h, const void* W,
                           int32_t v0, int32_t v1, float* logits, void* stream);
 
+/* Measurement aid: enqueue a bare streaming read of `bytes` bytes (a positive multiple of 16, src 16-byte
+ * aligned) of DEVICE memory, every byte once and nothing else.  Timed by the caller, it gives the read
+ * bandwidth this machine delivers to a plain kernel: the achievable ceiling to quote beside the published HBM
+ * peak for the kernels that are bound by streaming W (Eq. 3 at few masked rows). */
+dm_status dm_debug_stream_read(dm_ctx* ctx, const void* src, int64_t bytes, void* stream);
+
 /* Measurement aid.  dm_set_profiling(ctx, 1) makes every following dropmatch_verify /
  * dropmatch_verify_js record HIP events on its stream before and after each of its kernels
  * (mask rows, LM-head contraction + argmax, [JS pass 1, JS pass 2,] vote/accept); events are
@@ -301,6 +307,10 @@ dm_status dm_set_profiling(dm_ctx* ctx, int32_t enabled);
 dm_status dm_set_profiling_stride(dm_ctx* ctx, int32_t stride);
 dm_status dm_get_profile(dm_ctx* ctx, int32_t* n_calls, float* ms_mask, float* ms_lmhead, float* ms_vote);
 dm_status dm_get_profile_stages(dm_ctx* ctx, int32_t* n_calls, float* ms /* HOST [5] */);
+/* The individual durations behind those means: up to n_max samples of stage `stage` (0..4, as above), in
+ * the order of the recorded calls, into ms; *n_out = how many (calls in which the stage launched nothing
+ * are left out; with dm_set_profiling(ctx, 2) only stage 1 has samples).  Waits for the last recorded event. */
+dm_status dm_get_profile_samples(dm_ctx* ctx, int32_t stage, float* ms /* HOST [n_max] */, int32_t n_max, int32_t* n_out);
 
 /* Which contraction kernel a parameter block selects: 0 = generic fp32-FMA tiles (any
  * shape, f32 or bf16), 1 = bf16 MFMA kernel (bf16, d % 64 == 0).  Negative = dm_status. */

@@ -21,8 +21,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdropmatch.so")
 
 EXPORTS = ("dm_create", "dm_destroy", "dm_last_error", "dm_validate", "dropmatch_verify",
-           "dm_debug_masks", "dm_debug_logits", "dm_kernel_choice", "dm_set_profiling", "dm_set_profiling_stride", "dm_get_profile",
-           "dm_get_profile_stages", "dm_reserve_js", "dropmatch_verify_js", "dropmatch_verify_static")
+           "dm_debug_masks", "dm_debug_logits", "dm_debug_stream_read", "dm_kernel_choice", "dm_set_profiling", "dm_set_profiling_stride", "dm_get_profile",
+           "dm_get_profile_stages", "dm_get_profile_samples", "dm_reserve_js", "dropmatch_verify_js", "dropmatch_verify_static")
 
 
 class dm_params(C.Structure):
@@ -73,6 +73,8 @@ def load_library():
     lib.dm_debug_masks.restype = C.c_int
     lib.dm_debug_logits.argtypes = [vp, C.POINTER(dm_params), vp, vp, i32, i32, vp, vp]
     lib.dm_debug_logits.restype = C.c_int
+    lib.dm_debug_stream_read.argtypes = [vp, vp, i64, vp]
+    lib.dm_debug_stream_read.restype = C.c_int
     lib.dm_set_profiling.argtypes = [vp, i32]
     lib.dm_set_profiling.restype = C.c_int
     lib.dm_set_profiling_stride.argtypes = [vp, i32]
@@ -81,6 +83,8 @@ def load_library():
     lib.dm_get_profile.restype = C.c_int
     lib.dm_get_profile_stages.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_float)]
     lib.dm_get_profile_stages.restype = C.c_int
+    lib.dm_get_profile_samples.argtypes = [vp, i32, C.POINTER(C.c_float), i32, C.POINTER(i32)]
+    lib.dm_get_profile_samples.restype = C.c_int
     lib.dm_reserve_js.argtypes = [vp, i64, i32]
     lib.dm_reserve_js.restype = C.c_int
     lib.dropmatch_verify_js.argtypes = [vp, C.POINTER(dm_params)] + [vp] * 14
@@ -188,6 +192,11 @@ def dm_debug_logits(ctx, prm: dm_params, h, W, v0: int, v1: int, logits, stream=
     _check(ctx, st)
 
 
+def dm_debug_stream_read(ctx, src, nbytes: int, stream=None) -> None:
+    """Enqueue a bare streaming read of the first nbytes bytes of the CUDA tensor src."""
+    _check(ctx, load_library().dm_debug_stream_read(ctx, _ptr(src), int(nbytes), _stream_handle(stream)))
+
+
 def dm_set_profiling(ctx, enabled) -> None:
     """False/0: off; True/1: events around every kernel; 2: only around the contraction kernel."""
     _check(ctx, load_library().dm_set_profiling(ctx, int(enabled)))
@@ -212,3 +221,10 @@ def dm_get_profile_stages(ctx):
     _check(ctx, load_library().dm_get_profile_stages(ctx, C.byref(n), ms))
     return n.value, [float(x) for x in ms]
 
+
+def dm_get_profile_samples(ctx, stage: int, n_max: int = 512):
+    """The individual durations (ms) of one stage (0 mask rows, 1 LM head, 2/3 JS passes, 4 vote/accept)."""
+    n = C.c_int32()
+    ms = (C.c_float * n_max)()
+    _check(ctx, load_library().dm_get_profile_samples(ctx, stage, ms, n_max, C.byref(n)))
+    return [float(ms[i]) for i in range(n.value)]

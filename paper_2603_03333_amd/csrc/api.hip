@@ -658,6 +658,31 @@ dm_status dm_get_profile_stages(dm_ctx* ctx, int32_t* n_calls, float* ms /* [5] 
   return DM_OK;
 }
 
+dm_status dm_get_profile_samples(dm_ctx* ctx, int32_t stage, float* ms, int32_t n_max, int32_t* n_out) {
+  if (!ctx) return fail(nullptr, DM_EINVAL, "ctx is NULL");
+  if (stage < 0 || stage >= kEv - 1 || !ms || n_max < 0 || !n_out) return fail(ctx, DM_EINVAL, "need 0 <= stage < 5, ms, n_max >= 0, n_out");
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return fail(ctx, DM_EHIP, "cannot select device %d", ctx->device);
+  const bool light = ctx->prof_enabled == 2;  // only events 1 and 2 of every call exist
+  *n_out = 0;
+  if (light && stage != 1) return DM_OK;
+  const int n = ctx->prof_calls;
+  if (n > 0) {
+    const hipError_t e = hipEventSynchronize(ctx->ev[kEv * (n - 1) + (light ? 2 : kEv - 1)]);
+    if (e != hipSuccess) return fail_hip(ctx, "hipEventSynchronize", e);
+  }
+  for (int c = 0; c < n && *n_out < n_max; ++c) {
+    if (stage == 2 && !(ctx->prof_kind[c] & 1)) continue;
+    if (stage == 3 && !(ctx->prof_kind[c] & 4)) continue;
+    if (stage == 4 && !(ctx->prof_kind[c] & 2)) continue;
+    float t = 0.f;
+    const hipError_t e = hipEventElapsedTime(&t, ctx->ev[kEv * c + stage], ctx->ev[kEv * c + stage + 1]);
+    if (e != hipSuccess) return fail_hip(ctx, "hipEventElapsedTime", e);
+    ms[(*n_out)++] = t;
+  }
+  return DM_OK;
+}
+
 dm_status dm_get_profile(dm_ctx* ctx, int32_t* n_calls, float* ms_mask, float* ms_lmhead, float* ms_vote) {
   float ms[kEv - 1];
   if (dm_status st = dm_get_profile_stages(ctx, n_calls, ms)) return st;
@@ -676,6 +701,17 @@ dm_status dm_debug_masks(dm_ctx* ctx, const dm_params* prm, uint32_t* bits, void
   if (!guard.ok) return fail(ctx, DM_EHIP, "cannot select device %d", ctx->device);
   hipError_t e = dm::launch_mask_bits(bits, prm->seeds, g, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail_hip(ctx, "mask_bits launch", e);
+  return DM_OK;
+}
+
+dm_status dm_debug_stream_read(dm_ctx* ctx, const void* src, int64_t bytes, void* stream) {
+  if (!ctx) return fail(nullptr, DM_EINVAL, "ctx is NULL");
+  if (!src || bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15))
+    return fail(ctx, DM_EINVAL, "need a 16-byte aligned buffer of a positive multiple of 16 bytes");
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return fail(ctx, DM_EHIP, "cannot select device %d", ctx->device);
+  const hipError_t e = dm::launch_stream_read(src, (size_t)bytes, ctx->num_cu, ctx->done + 32, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail_hip(ctx, "stream_read launch", e);
   return DM_OK;
 }
 

@@ -9,21 +9,20 @@
 //   pass 1 (js_stats):  normalisers.  Z_i = max_i + ln sum_v exp(l_i[v] - max_i), with max_i already
 //                       known from the argmax key of the row; for the mean logits lbar[v] the running
 //                       (max, sum) pair, since their maximum is not known in advance.
-//   pass 2 (js_terms):  with ln p_i[v] = l_i[v] - Z_i, ln pbar[v] = lbar[v] - Zbar and
-//                       delta = ln pbar - ln p_i, the JS integrand is written without differences of
-//                       nearly equal logarithms:
-//                         a = ln((1 + e^delta) / 2) = ln(m / p_i),   m = (p_i + pbar) / 2
-//                         p_i ln(p_i/m)/2 + pbar ln(pbar/m)/2 = (pbar * delta - (p_i + pbar) * a) / 2
-//                       (for p_i -> 0 it tends to pbar ln2 / 2, for pbar -> 0 to p_i ln2 / 2).  The
-//                       shorter a = ln(p_i + pbar) - ln 2 - ln p_i was measured too: 3 % faster, ten
-//                       times the error (3e-7), so it is not used.
+//   pass 2 (js_terms):  with log p_i[v] = l_i[v] - Z_i, log pbar[v] = lbar[v] - Zbar and
+//                       delta = log pbar - log p_i, the JS integrand is written without differences of
+//                       nearly equal logarithms (js_term2).  The shorter log(p_i + pbar) - log p_i form
+//                       was measured too: ten times the error (3e-7), so it is not used.
+// Both passes are bound by the vector ALU, not by memory (a dozen plain instructions and three
+// exp/log per stored logit): everything is kept in base 2 so that the hardware's exp2/log2 units are
+// fed directly, whole chunks skip the bounds checks, and per-row work is dealt to the lanes of a group.
 // Every reduction (lanes, wavefronts, chunks) runs in a fixed order: results are reproducible.
 #include "kernels.hpp"
 
 namespace dm {
 namespace {
 
-constexpr int JT = 256;             // threads per workgroup
+constexpr int JT = 1024;            // threads per workgroup (one workgroup = kJsChunk vocabulary rows of one position)
 
 __device__ __forceinline__ float key_logit(unsigned long long key) {
   uint32_t u = (uint32_t)(key >> 32);
@@ -31,11 +30,13 @@ __device__ __forceinline__ float key_logit(unsigned long long key) {
   return __uint_as_float(u);
 }
 
-// e^x and ln x on the hardware's base-2 units (1 ulp each; the argument scaling adds a relative
-// error of about |x| * 1e-7 to e^x, far inside what Eq. (6) needs).  ln is used on [1, 2] and on
-// probabilities above the smallest normal float.
-__device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896341f); }
-__device__ __forceinline__ float fast_log(float x) { return __builtin_amdgcn_logf(x) * 0.693147180559945309f; }
+// All logarithms of the two passes are kept in base 2, the base of the hardware's exp and log units
+// (v_exp_f32, v_log_f32: 1 ulp), so that no value is rescaled on its way in or out of them; the
+// sums are turned into natural-log units once, at the end (factor ln 2).
+constexpr float kLog2e = 1.44269504088896341f;
+constexpr float kLn2 = 0.693147180559945309f;
+__device__ __forceinline__ float exp2_hw(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float log2_hw(float x) { return __builtin_amdgcn_logf(x); }
 
 __device__ __forceinline__ float wave_sum(float x) {
 #pragma unroll
@@ -43,28 +44,33 @@ __device__ __forceinline__ float wave_sum(float x) {
   return x;
 }
 
-// ln((1 + e^x) / 2) without overflow
-__device__ __forceinline__ float log_half_1pexp(float x) {
-  return fmaxf(x, 0.f) + fast_log(1.0f + fast_exp(-fabsf(x))) - 0.693147180559945309f;
-}
-
-// one JS integrand from ln p, ln q (q = centroid) and the probabilities themselves
-__device__ __forceinline__ float js_term(float lp, float p, float lq, float q) {
-  const float delta = lq - lp;
-  const float a = log_half_1pexp(delta);
-  return 0.5f * (q * delta - (p + q) * a);
+// One JS integrand in units of (ln 2) / 2, from log2 p, p, log2 q, q (q = centroid), written without
+// differences of nearly equal logarithms: with delta = log2 q - log2 p and
+//   a = log2(1 + 2^delta) = max(delta, 0) + log2(1 + 2^-|delta|)      (= 1 + log2(m / p), m = (p + q) / 2)
+//   p log2(p/m) + q log2(q/m) = q delta - (p + q) (a - 1)
+// (for p -> 0 it tends to q, for q -> 0 to p).
+__device__ __forceinline__ float js_term2(float l2p, float p, float l2q, float q) {
+  const float delta = l2q - l2p;
+  const float a = fmaxf(delta, 0.f) + log2_hw(1.0f + exp2_hw(-fabsf(delta)));
+  const float t = p + q;
+  return fmaf(q, delta, fmaf(-t, a, t));
 }
 
 // Thread mapping of both passes.  A vocabulary row holds K4 floats; G = KP / 4 consecutive lanes
 // (KP = K4 rounded up to a power of two) take 4 paths each of the same row, so one load instruction
 // of a wavefront covers 64 / G consecutive rows = a contiguous piece of memory, and a lane keeps only
-// 4 running sums.  The mean over the K paths of a row is a butterfly over the G lanes of its group;
-// lane 0 of the group then owns the row's centroid and draft terms.
+// 4 running sums.  The mean over the K paths of a row is a butterfly over the G lanes of its group.
+// What is wanted once per row (the centroid's running normaliser in pass 1, the draft term in pass 2)
+// would be computed by all G lanes of the group, since the lanes of a wavefront run in lockstep; rows
+// are therefore taken in blocks of BL = min(G, 4) iterations and lane u of a group does that work for
+// the block's u-th row.
 template <int G>
 struct RowMap {
   static constexpr int ROWS_PER_WAVE = 64 / G;
   static constexpr int ROWS_PER_ITER = (JT / 64) * ROWS_PER_WAVE;
   static constexpr int ITERS = kJsChunk / ROWS_PER_ITER;
+  static constexpr int BL = G < 4 ? G : 4;
+  static_assert(ITERS >= 1 && ITERS % BL == 0, "whole blocks of rows");
 };
 
 // Sum over the G consecutive lanes of a group (G = 1, 2, 4, 8, 16), result in every lane of the group,
@@ -91,7 +97,67 @@ __device__ __forceinline__ float column_sum(float x) {
   return x;
 }
 
-// FULL: the number of heads in use is 4 G, every lane's four paths exist (no per-path predicates).
+// What both passes know about their place: the lane's four paths, its rows, which of them count.
+template <int G, bool FULL>
+struct LaneMap {
+  int grp, i0;
+  bool active;   // the lane's group of four paths exists in the store (i0 < K4)
+  bool use[4];   // a head in use (not padding, whose slots are never written, nor the clean path); all true when FULL
+  __device__ LaneMap(int lane, const JsGeom& g) {
+    grp = lane % G;
+    i0 = 4 * grp;
+    active = i0 < g.K4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) use[j] = FULL || i0 + j < g.KU;
+  }
+};
+
+// ---------------------------------------------------------------------------------------------- pass 1
+// S_i += 2^(l2_i[v] - max2_i) for the lane's four paths and, for the rows dealt to this lane, the running
+// (max, sum) of the mean logits.  CHECK: the chunk reaches past V (only the last chunk of a position).
+template <int G, bool FULL, bool CHECK>
+__device__ __forceinline__ void stats_loop(const float* __restrict__ base, int v_first, const JsGeom& g,
+                                           const LaneMap<G, FULL>& lm, const float (&mx2)[4], float mean_scale,
+                                           float (&S)[4], float& cmax, float& csum) {
+  using RM = RowMap<G>;
+  constexpr int BL = RM::BL;
+  const float* row = base + (int64_t)v_first * g.K4;
+  const int64_t step = (int64_t)RM::ROWS_PER_ITER * g.K4;
+#pragma unroll(4 / BL)
+  for (int it0 = 0; it0 < RM::ITERS; it0 += BL) {
+    float xbar2 = 0.f;
+    bool mine = false;
+#pragma unroll
+    for (int u = 0; u < BL; ++u) {
+      const int v = v_first + (it0 + u) * RM::ROWS_PER_ITER;
+      const bool in = !CHECK || v < g.V;           // rows past the end re-read the last row with weight 0
+      const float* src = CHECK ? base + (int64_t)(in ? v : g.V - 1) * g.K4 : row;
+      row += step;
+      const float4 qv = *reinterpret_cast<const float4*>(src);
+      const float x[4] = {qv.x, qv.y, qv.z, qv.w};
+      float xs = 0.f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {   // selects, not weights: an unused slot may hold anything, NaN included
+        const float xj = lm.use[j] ? x[j] : 0.f;
+        xs += xj;
+        const float e = exp2_hw(fmaf(xj, kLog2e, -mx2[j]));
+        S[j] += (lm.use[j] && in) ? e : 0.f;
+      }
+      xs = group_sum<G>(xs);
+      if (lm.grp == u) {
+        xbar2 = xs * mean_scale;
+        mine = in;
+      }
+    }
+    if (mine) {   // online (max, sum) of the mean logits over the rows of this lane
+      const float m_new = fmaxf(cmax, xbar2);
+      csum = fmaf(csum, exp2_hw(cmax - m_new), exp2_hw(xbar2 - m_new));
+      cmax = m_new;
+    }
+  }
+}
+
+// FULL: the number of heads in use is 4 G, every lane's four paths exist (no per-path weights).
 template <int G, bool FULL>
 __global__ __launch_bounds__(JT) void js_stats_kernel(const float* __restrict__ lt,
                                                       const unsigned long long* __restrict__ keys,
@@ -102,48 +168,25 @@ __global__ __launch_bounds__(JT) void js_stats_kernel(const float* __restrict__ 
   const int pos = blockIdx.x, c = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int K = g.K, KU = g.KU;  // rows per position in the store / heads in use
-  const int grp = lane % G, rl = lane / G;
-  const int i0 = 4 * grp;             // first path of this lane
-  const bool active = i0 < g.K4;
+  const LaneMap<G, FULL> lm(lane, g);
 
-  float mx[4], S[4];
-  bool use[4];
+  float mx2[4], S[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    use[j] = FULL || i0 + j < KU;
-    mx[j] = use[j] ? scale * key_logit(keys[(int64_t)pos * K + i0 + j]) : 0.f;
+    mx2[j] = lm.use[j] ? scale * key_logit(keys[(int64_t)pos * K + lm.i0 + j]) * kLog2e : 0.f;
     S[j] = 0.f;
   }
-  // centroid: running (max, sum of exp relative to it); kept by every lane of a group, lane 0's is used.
   // "Nothing yet" is a large negative finite number so that differences never become inf - inf.
   constexpr float kNone = -3.0e38f;
   float cmax = kNone, csum = 0.f;
-  const float* base = lt + (int64_t)pos * g.V * g.K4 + (active ? i0 : 0);
-  const int v_first = c * kJsChunk + wave * RM::ROWS_PER_WAVE + rl;
-  const float inv_k = 1.0f / (float)KU;
-  const bool exact_inv = (KU & (KU - 1)) == 0;  // then x * (1/K) is the correctly rounded x / K
-#pragma unroll 4
-  for (int it = 0; it < RM::ITERS; ++it) {
-    const int v = v_first + it * RM::ROWS_PER_ITER;
-    const bool in = v < g.V;                       // only the last chunk has rows past the end:
-    const int vc = in ? v : g.V - 1;               // they re-read the last row with weight 0
-    const float4 q = *reinterpret_cast<const float4*>(base + (int64_t)vc * g.K4);
-    const float x[4] = {q.x, q.y, q.z, q.w};
-    const float wgt = (in && active) ? 1.f : 0.f;
-    float xs = 0.f;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const float xj = (use[j] && active) ? x[j] : 0.f;
-      xs += xj;
-      S[j] += (use[j] ? wgt : 0.f) * fast_exp(xj - mx[j]);
-    }
-    xs = group_sum<G>(xs);
-    const float xbar = in ? (exact_inv ? xs * inv_k : xs / (float)KU) : kNone;
-    const float m_new = fmaxf(cmax, xbar);
-    csum = csum * fast_exp(cmax - m_new) + (in ? 1.f : 0.f) * fast_exp(xbar - m_new);
-    cmax = m_new;
-  }
-  if (grp != 0) {
+  const float* base = lt + (int64_t)pos * g.V * g.K4 + (lm.active ? lm.i0 : 0);
+  const int v_first = c * kJsChunk + wave * RM::ROWS_PER_WAVE + lane / G;
+  const float mean_scale = kLog2e / (float)KU;   // mean over the heads, in base-2 units
+  if ((c + 1) * kJsChunk <= g.V)
+    stats_loop<G, FULL, false>(base, v_first, g, lm, mx2, mean_scale, S, cmax, csum);
+  else
+    stats_loop<G, FULL, true>(base, v_first, g, lm, mx2, mean_scale, S, cmax, csum);
+  if (lm.grp >= RM::BL) {   // lanes that were dealt no rows
     cmax = kNone;
     csum = 0.f;
   }
@@ -152,12 +195,12 @@ __global__ __launch_bounds__(JT) void js_stats_kernel(const float* __restrict__ 
   float wmax = cmax;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) wmax = fmaxf(wmax, __shfl_xor(wmax, off, 64));
-  csum = csum * fast_exp(cmax - wmax);
+  csum = csum * exp2_hw(cmax - wmax);
   csum = wave_sum(csum);
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const float t = column_sum<G>(S[j]);
-    if (lane < G && i0 + j < KU) red[wave][i0 + j] = t;
+    if (lane < G && lm.i0 + j < KU) red[wave][lm.i0 + j] = t;
   }
   if (lane == 0) {
     red[wave][KP] = wmax;
@@ -176,9 +219,60 @@ __global__ __launch_bounds__(JT) void js_stats_kernel(const float* __restrict__ 
     for (int w = 1; w < JT / 64; ++w) m = fmaxf(m, red[w][KP]);
     float s = 0.f;
 #pragma unroll
-    for (int w = 0; w < JT / 64; ++w) s += red[w][KP + 1] * fast_exp(red[w][KP] - m);
-    out[(int64_t)g.K4 * g.NC] = m;
-    out[(int64_t)(g.K4 + 1) * g.NC] = s;
+    for (int w = 0; w < JT / 64; ++w) s += red[w][KP + 1] * exp2_hw(red[w][KP] - m);
+    out[(int64_t)g.K4 * g.NC] = m;        // base-2 units: max over the chunk of log2(e) * mean logit
+    out[(int64_t)(g.K4 + 1) * g.NC] = s;  // sum of 2^(that - max)
+  }
+}
+
+// ---------------------------------------------------------------------------------------------- pass 2
+template <int G, bool FULL, bool CHECK>
+__device__ __forceinline__ void terms_loop(const float* __restrict__ base, const float* __restrict__ dp,
+                                           int v_first, const JsGeom& g, const LaneMap<G, FULL>& lm,
+                                           const float (&Z2)[4], float Zbar2, float mean_scale, bool draft_on,
+                                           float (&J)[4], float& Jd) {
+  using RM = RowMap<G>;
+  constexpr int BL = RM::BL;
+  const float* row = base + (int64_t)v_first * g.K4;
+  const float* prow = dp + v_first;
+  const int64_t step = (int64_t)RM::ROWS_PER_ITER * g.K4;
+#pragma unroll(4 / BL)
+  for (int it0 = 0; it0 < RM::ITERS; it0 += BL) {
+    float l2q_d = 0.f, q_d = 0.f, ph_d = 1.f;
+    bool in_d = false;
+#pragma unroll
+    for (int u = 0; u < BL; ++u) {
+      const int v = v_first + (it0 + u) * RM::ROWS_PER_ITER;
+      const bool in = !CHECK || v < g.V;           // rows past the end re-read the last row with weight 0
+      const int vc = in ? v : g.V - 1;
+      const float4 qv = *reinterpret_cast<const float4*>(CHECK ? base + (int64_t)vc * g.K4 : row);
+      const float ph = CHECK ? dp[vc] : *prow;
+      row += step;
+      prow += RM::ROWS_PER_ITER;
+      const float x[4] = {qv.x, qv.y, qv.z, qv.w};
+      float xs = 0.f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) xs += lm.use[j] ? x[j] : 0.f;   // selects: an unused slot may hold anything
+      xs = group_sum<G>(xs);
+      const float l2q = fmaf(xs, mean_scale, -Zbar2);
+      const float q = exp2_hw(l2q);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float l2p = fmaf(lm.use[j] ? x[j] : 0.f, kLog2e, -Z2[j]);
+        const float term = js_term2(l2p, exp2_hw(l2p), l2q, q);
+        J[j] += (lm.use[j] && in) ? term : 0.f;
+      }
+      if (lm.grp == u) {
+        l2q_d = l2q;
+        q_d = q;
+        ph_d = ph;
+        in_d = in;
+      }
+    }
+    // draft: log2 phat needs phat > 0; at phat = 0 the integrand is pbar (in units of ln2 / 2)
+    const bool pos_ph = ph_d > 1e-37f;
+    const float td = js_term2(log2_hw(pos_ph ? ph_d : 1.f), pos_ph ? ph_d : 0.f, l2q_d, q_d);
+    Jd += (in_d && draft_on) ? (pos_ph ? td : q_d) : 0.f;
   }
 }
 
@@ -196,13 +290,11 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
   const int pos = blockIdx.x, c = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int K = g.K, KU = g.KU;  // rows per position in the store / heads in use
-  const int grp = lane % G, rl = lane / G;
-  const int i0 = 4 * grp;
-  const bool active = i0 < g.K4;
+  const LaneMap<G, FULL> lm(lane, g);
 
-  // normalisers from the partial sums of pass 1: 8 lanes per slot (a head, or the mean logits), every
-  // lane adds every 8th chunk record (independent loads, all in flight together), then a butterfly over
-  // the 8 lanes: a fixed order, the same in every workgroup
+  // normalisers (base 2) from the partial sums of pass 1: 8 lanes per slot (a head, or the mean logits),
+  // every lane adds every 8th chunk record (independent loads, all in flight together), then a butterfly
+  // over the 8 lanes: a fixed order, the same in every workgroup
   const float* pa = part_a + (int64_t)pos * g.KS * g.NC;
   for (int slot = tid >> 3; slot <= KU; slot += JT / 8) {
     const int sub = tid & 7;
@@ -211,66 +303,45 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
       for (int cc = sub; cc < g.NC; cc += 8) s += (double)pa[(int64_t)slot * g.NC + cc];
 #pragma unroll
       for (int off = 4; off >= 1; off >>= 1) s += __shfl_xor(s, off, 8);
-      if (sub == 0) Zs[slot] = (float)((double)(scale * key_logit(keys[(int64_t)pos * K + slot])) + log(s));
-    } else {  // mean logits: chunk records are (max, sum of exp relative to that max)
+      if (sub == 0) Zs[slot] = (float)((double)(scale * key_logit(keys[(int64_t)pos * K + slot]) * kLog2e) + log2(s));
+    } else {  // mean logits: chunk records are (max, sum of 2^(x - max))
       float m = -INFINITY;
       for (int cc = sub; cc < g.NC; cc += 8) m = fmaxf(m, pa[(int64_t)g.K4 * g.NC + cc]);
 #pragma unroll
       for (int off = 4; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 8));
+      // the rescaling factors in float (relative error 1e-7 per record, as good as the records themselves)
       double s = 0.0;
       for (int cc = sub; cc < g.NC; cc += 8)
-        s += (double)pa[(int64_t)(g.K4 + 1) * g.NC + cc] * exp((double)pa[(int64_t)g.K4 * g.NC + cc] - (double)m);
+        s += (double)(pa[(int64_t)(g.K4 + 1) * g.NC + cc] * exp2_hw(pa[(int64_t)g.K4 * g.NC + cc] - m));
 #pragma unroll
       for (int off = 4; off >= 1; off >>= 1) s += __shfl_xor(s, off, 8);
-      if (sub == 0) Zs[KP] = (float)((double)m + log(s));
+      if (sub == 0) Zs[KP] = (float)((double)m + log2(s));
     }
   }
   __syncthreads();
-  float Z[4], J[4];
-  bool use[4];
+  float Z2[4], J[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    use[j] = FULL || i0 + j < KU;
-    Z[j] = use[j] ? Zs[i0 + j] : 0.f;
+    Z2[j] = lm.use[j] ? Zs[lm.i0 + j] : 0.f;
     J[j] = 0.f;
   }
-  const float Zbar = Zs[KP];
-  const bool draft_on = draft_ids[pos] >= 0 && grp == 0;
+  const float Zbar2 = Zs[KP];
+  const bool draft_on = draft_ids[pos] >= 0 && lm.grp < RM::BL;
   float Jd = 0.f;
-  const float* base = lt + (int64_t)pos * g.V * g.K4 + (active ? i0 : 0);
+  const float* base = lt + (int64_t)pos * g.V * g.K4 + (lm.active ? lm.i0 : 0);
   const float* dp = draft_probs + (int64_t)pos * g.V;
-  const int v_first = c * kJsChunk + wave * RM::ROWS_PER_WAVE + rl;
-  const float inv_k = 1.0f / (float)KU;
-  const bool exact_inv = (KU & (KU - 1)) == 0;
-#pragma unroll 4
-  for (int it = 0; it < RM::ITERS; ++it) {
-    const int v = v_first + it * RM::ROWS_PER_ITER;
-    const bool in = v < g.V;                       // rows past the end re-read the last row with weight 0
-    const int vc = in ? v : g.V - 1;
-    const float4 qv = *reinterpret_cast<const float4*>(base + (int64_t)vc * g.K4);
-    const float ph = dp[vc];
-    const float x[4] = {qv.x, qv.y, qv.z, qv.w};
-    const float wgt = (in && active) ? 1.f : 0.f;
-    float xs = 0.f;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) xs += (use[j] && active) ? x[j] : 0.f;
-    xs = group_sum<G>(xs);
-    const float lq = (exact_inv ? xs * inv_k : xs / (float)KU) - Zbar;
-    const float q = fast_exp(lq);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const float lp = ((use[j] && active) ? x[j] : 0.f) - Z[j];
-      J[j] += (use[j] ? wgt : 0.f) * js_term(lp, fast_exp(lp), lq, q);
-    }
-    // draft: ln phat needs phat > 0; at phat = 0 the integrand is pbar ln2 / 2
-    const bool pos_ph = ph > 1e-37f;
-    const float td = js_term(fast_log(pos_ph ? ph : 1.f), pos_ph ? ph : 0.f, lq, q);
-    Jd += (in && draft_on) ? (pos_ph ? td : 0.5f * 0.693147180559945309f * q) : 0.f;
-  }
+  const int v_first = c * kJsChunk + wave * RM::ROWS_PER_WAVE + lane / G;
+  const float mean_scale = kLog2e / (float)KU;
+  if ((c + 1) * kJsChunk <= g.V)
+    terms_loop<G, FULL, false>(base, dp, v_first, g, lm, Z2, Zbar2, mean_scale, draft_on, J, Jd);
+  else
+    terms_loop<G, FULL, true>(base, dp, v_first, g, lm, Z2, Zbar2, mean_scale, draft_on, J, Jd);
+
+  constexpr float kUnit = 0.5f * kLn2;   // the sums are in units of (ln 2) / 2
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const float t = column_sum<G>(J[j]);
-    if (lane < G && i0 + j < KU) red[wave][i0 + j] = t;
+    if (lane < G && lm.i0 + j < KU) red[wave][lm.i0 + j] = t;
   }
   Jd = wave_sum(Jd);
   if (lane == 0) red[wave][KP] = Jd;
@@ -280,12 +351,12 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
     float t = red[0][tid];
 #pragma unroll
     for (int w = 1; w < JT / 64; ++w) t += red[w][tid];
-    out[(int64_t)tid * g.NC] = t;
+    out[(int64_t)tid * g.NC] = t * kUnit;
   } else if (tid == 64) {
     float t = red[0][KP];
 #pragma unroll
     for (int w = 1; w < JT / 64; ++w) t += red[w][KP];
-    out[(int64_t)g.K4 * g.NC] = t;
+    out[(int64_t)g.K4 * g.NC] = t * kUnit;
   }
 }
 

@@ -106,7 +106,7 @@ hipError_t prepare_lmhead_mfma_big();
 // Distribution-level rule (Eq. (5), (6)) over the stored logits, in two passes over the vocabulary;
 // each workgroup takes kJsChunk vocabulary rows of one position and leaves partial sums that the
 // next kernel adds up in a fixed order (so results do not depend on scheduling).
-constexpr int kJsChunk = 1024;  // vocabulary rows per workgroup
+constexpr int kJsChunk = 4096;  // vocabulary rows per workgroup (1024 threads)
 constexpr int kJsMaxK = 64;     // paths per row the distribution-level rule takes
 struct JsGeom {
   int P;    // positions B*T
@@ -154,6 +154,9 @@ hipError_t launch_vote_accept(const unsigned long long* keys, const int32_t* dra
                               int B, int T, int K, int Kv, int rule, const VoteOut& out, const float* part_b,
                               const JsGeom* jg, hipStream_t stream);
 hipError_t prepare_vote_accept();
+
+// Measurement aid: plain streaming read of `bytes` bytes (a multiple of 16) at src; sink: one device word.
+hipError_t launch_stream_read(const void* src, size_t bytes, int num_cu, unsigned int* sink, hipStream_t stream);
 
 // Packed argmax key: larger logit wins, then smaller vocabulary index.  Key 0 = "nothing yet".
 __host__ __device__ inline unsigned long long pack_key(float val, uint32_t v) {

@@ -38,7 +38,8 @@ hipError_t launch_vote_accept(const unsigned long long* keys, const int32_t* dra
   if (vote_lds_bytes(T, K, rule) > vote_lds_limit()) return hipErrorInvalidValue;
   const JsGeom geom = jg ? *jg : JsGeom{};
   // the step takes one row per wavefront at a time (a chain of dependent cross-lane steps per row): many rows, many wavefronts
-  const unsigned threads = T > 16 ? 1024u : 256u;
+  // (the distribution-level rules also add up T * (K + 1) sums of chunk records, 8 lanes each)
+  const unsigned threads = (T > 16 || rule >= 2) ? 1024u : 256u;
   vote_accept_kernel<<<dim3((unsigned)B), dim3(threads), vote_lds_bytes(T, K, rule), stream>>>(keys, draft_ids, parent, T,
                                                                                           K, Kv, rule, out, part_b, geom);
   return hipGetLastError();

@@ -53,37 +53,26 @@ __device__ __forceinline__ void vote_accept_body(int b, int tid, int nthreads, i
   }
   __syncthreads();
 
-  // Eq. (6): total JS of every (row, head) and (row, draft) = its per-chunk partial sums added in
-  // ascending chunk order, one thread per sum (independent loads, so they overlap)
+  // Eq. (6): total JS of every (row, head) and (row, draft) = its per-chunk partial sums, added by 8
+  // lanes per sum: every lane adds every 8th record in ascending order (independent loads, all in
+  // flight together), then a butterfly over the 8 lanes - a fixed order, so the result is reproducible
   if (rule >= 2) {
     const int K1 = K + 1;
-    for (int x = tid; x < T * K1; x += nthreads) {
-      const int t = x / K1, i = x - t * K1;
-      if (i >= Kv && i < K) {  // slot of the clean path: not a head of the cluster
-        jsv[x] = 0.f;
-        if (out.js_heads) out.js_heads[((int64_t)b * T + t) * K + i] = 0.f;
-        continue;
-      }
-      const float* src = part_b + (((int64_t)b * T + t) * jg.KS + (i < K ? i : jg.K4)) * jg.NC;
+    const int sub = tid & 7;
+    for (int x0 = 0; x0 < T * K1; x0 += nthreads >> 3) {   // uniform trip count: every lane reaches the shuffles
+      const int x = x0 + (tid >> 3);
+      const bool live = x < T * K1;
+      const int t = live ? x / K1 : 0, i = live ? x - t * K1 : 0;
+      const bool clean_slot = i >= Kv && i < K;  // slot of the clean path: not a head of the cluster
       double s = 0.0;
-      int c = 0;
-      // the loop is bound by load latency, so many loads are issued before the first is added
-      for (; c + 32 <= jg.NC; c += 32) {
-        float v[32];
-#pragma unroll
-        for (int u = 0; u < 32; ++u) v[u] = src[c + u];
-#pragma unroll
-        for (int u = 0; u < 32; ++u) s += (double)v[u];
+      if (live && !clean_slot) {
+        const float* src = part_b + (((int64_t)b * T + t) * jg.KS + (i < K ? i : jg.K4)) * jg.NC;
+        for (int c = sub; c < jg.NC; c += 8) s += (double)src[c];
       }
-      for (; c + 8 <= jg.NC; c += 8) {
-        float v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = src[c + u];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) s += (double)v[u];
-      }
-      for (; c < jg.NC; ++c) s += (double)src[c];
-      const float js = (float)s;
+      for (int off = 4; off >= 1; off >>= 1) s += __shfl_xor(s, off, 8);
+      if (!live || sub != 0) continue;
+      const float js = clean_slot ? 0.f : (float)s;
       jsv[x] = js;
       if (i < K) {
         if (out.js_heads) out.js_heads[((int64_t)b * T + t) * K + i] = js;
