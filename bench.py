@@ -50,6 +50,8 @@ def parse_args():
                     help="time replays of a HIP graph that holds one captured step instead of eager calls")
     ap.add_argument("--static", action="store_true",
                     help="call dropmatch_verify_static (the library's fixed workspace, no context) instead of dropmatch_verify")
+    ap.add_argument("--sparse-correction", action="store_true",
+                    help="path logits as clean row minus corrections over the dropped dimensions (DM_FLAG_SPARSE_CORRECTION)")
     ap.add_argument("--ramp-seconds", type=float, default=RAMP_SECONDS, help="length of the untimed clock-ramp phase")
     ap.add_argument("--secondary", default="auto",
                     help="workload of the `secondary` object: auto = batched when the headline workload is head8b "
@@ -116,7 +118,7 @@ def describe(wl):
 
 
 def run_workload(wl, args, steps, warmup, rule_name="any", temperature=0.0, top_p=0.0, graph=False, static=False,
-                 other_kernels=True, keep_host=False):
+                 other_kernels=True, keep_host=False, sparse=False):
     """Generate the workload, make it resident, time `steps` steps.  Returns a dict of measurements
     (and, with keep_host, the host arrays the CPU baseline needs)."""
     import numpy as np
@@ -174,7 +176,8 @@ def run_workload(wl, args, steps, warmup, rule_name="any", temperature=0.0, top_
         dmb.dm_reserve_js(ctx, wl.B * wl.T, wl.K)
     prm, keep = dmb.make_params(wl.B, wl.T, wl.K, wl.d, wl.V, dmb.DM_BF16 if bf16 else dmb.DM_F32, wl.p,
                                 [int(s) for s in seeds], parent=parent_dev, rule=rule,
-                                flags=dmb.DM_FLAG_SAMPLE_PATHS if temperature > 0 else 0,
+                                flags=(dmb.DM_FLAG_SAMPLE_PATHS if temperature > 0 else 0) |
+                                      (dmb.DM_FLAG_SPARSE_CORRECTION if sparse else 0),
                                 temperature=temperature, top_p=top_p)
     kernel = dmb.dm_kernel_choice(prm)
     out = dict(accept_len=torch.zeros(wl.B, dtype=torch.int32, device="cuda"),
@@ -228,7 +231,7 @@ def run_workload(wl, args, steps, warmup, rule_name="any", temperature=0.0, top_
     # ---- the timed region.  The library brackets the contraction kernel of a sample of these very
     # calls with two HIP events that take the launch's own timestamps; a captured graph and the
     # context-free entry point hold no events, so there the kernel is timed in the pass after the region.
-    live = not graph and not static
+    live = not graph and not static and not sparse
     stride = max(1, min(8, steps // 10))          # an event pair costs ~4 us of stream time: sample, but get >= 10 samples
     if live:
         dmb.dm_set_profiling_stride(ctx, stride)
@@ -257,7 +260,9 @@ def run_workload(wl, args, steps, warmup, rule_name="any", temperature=0.0, top_
     # ---- the other kernels: a pass with events around every kernel
     stages = [0.0] * 5
     pass2 = []
-    if other_kernels or not live:
+    if sparse:
+        pass2 = list(step_ms)      # no per-kernel events on this path: the whole step stands in
+    elif other_kernels or not live:
         dmb.dm_set_profiling(ctx, True)
         for _ in range(min(steps, 512)):
             if static:
@@ -327,6 +332,8 @@ def run_workload(wl, args, steps, warmup, rule_name="any", temperature=0.0, top_
                               "not measured in this run") if traffic else None
     roof["kernel"] = ("lmhead_mfma_kernel" if M <= 128 else "lmhead_mfma_big_kernel") if kernel == 1 \
         else "lmhead_generic_kernel"
+    if sparse:
+        roof["kernel"] = "whole step: clean rows (contraction kernel, K = 1) + drop_lists_kernel + sparse_correct_kernel + vote"
     roof["kernel_ms"] = ms_lm
     roof["kernel_ms_median"] = statistics.median(lm_samples)
     roof["kernel_ms_min"] = min(lm_samples)
@@ -383,7 +390,8 @@ def main():
     torch.cuda.set_device(0)
     wl = wk.CONFIGS[args.workload]
     default_line = (args.workload == "head8b" and not args.paths and not args.batch and args.p_drop < 0 and
-                    args.rule == "any" and args.temperature == 0 and not args.graph and not args.static)
+                    args.rule == "any" and args.temperature == 0 and not args.graph and not args.static and
+                    not args.sparse_correction)
     if args.paths:
         wl = wl.with_(K=args.paths)
     if args.batch:
@@ -403,7 +411,8 @@ def main():
         sys.exit(2)
 
     m = run_workload(wl, args, args.steps, args.warmup, args.rule, args.temperature, args.top_p, args.graph,
-                     args.static, other_kernels=True, keep_host=not args.no_cpu_baseline)
+                     args.static, other_kernels=not args.sparse_correction, keep_host=not args.no_cpu_baseline,
+                     sparse=args.sparse_correction)
     result = {
         "metric": "MC-dropout LM-head verify: positions/s; HBM GB/s or MFMA % of peak",
         "value": m["value"],

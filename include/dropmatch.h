@@ -92,6 +92,15 @@ typedef enum {
  * from the stored logits. */
 #define DM_FLAG_SAMPLE_PATHS 16u
 
+/* The same path logits by linearity of Eq. 3, W (h * m) = W h - W (h * (1 - m)): one undropped row per
+ * position on the matrix cores plus, per path, a correction over the dimensions that path dropped, on the
+ * vector ALU.  Same tokens as the default path up to the order of the float32 sums.  Measured slower than
+ * the dense contraction on this chip at the paper's dropout rates; kept as an option.  bf16 with d % 64 == 0,
+ * K <= 32, token-level rules, arg-max path tokens.  The first call with this flag allocates its buffers
+ * (B*T*V*4 + B*T*K*d*4.07 bytes; later calls with larger shapes reallocate): make it outside a stream
+ * capture.  DM_EUNSUPPORTED otherwise. */
+#define DM_FLAG_SPARSE_CORRECTION 32u
+
 /* Testing aid: always run the acceptance step as its own kernel.  (Without it, calls that go to the
  * W-streaming kernel - bf16, at most 128 masked rows, token-level rule - run that step inside the
  * contraction launch, in the workgroup that finishes last.) */

@@ -16,6 +16,7 @@ DM_F32, DM_BF16 = 0, 1
 DM_RULE_ANY, DM_RULE_MAJORITY, DM_RULE_JS, DM_RULE_JS_OR_MAJORITY = 0, 1, 2, 3
 DM_FLAG_SHARE_MASK_ACROSS_POS, DM_FLAG_FORCE_GENERIC, DM_FLAG_CLEAN_LAST_PATH, DM_FLAG_SEPARATE_VOTE = 1, 2, 4, 8
 DM_FLAG_SAMPLE_PATHS = 16
+DM_FLAG_SPARSE_CORRECTION = 32
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdropmatch.so")

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdropmatch.so")
 SOURCES = ["api.hip", "mask_rows.hip", "lmhead_generic.hip", "lmhead_mfma.hip", "lmhead_mfma_big.hip", "vote_accept.hip",
-           "js_divergence.hip", "nucleus.hip", "stream_read.hip"]
+           "js_divergence.hip", "nucleus.hip", "stream_read.hip", "sparse_correction.hip"]
 HEADERS = ["kernels.hpp", "philox.hpp", "mfma_common.hpp", "vote_body.hpp", "sampling.hpp", os.path.join("..", "..", "include", "dropmatch.h")]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",

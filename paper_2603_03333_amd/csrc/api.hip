@@ -22,6 +22,12 @@ struct dm_ctx {
   unsigned int* done = nullptr;       // workgroups done, for the acceptance step fused into the contraction
   uint64_t* seeds_dev = nullptr;      // seeds of the current call, for the sampling epilogues
   float* noise = nullptr;             // Gumbel noise of one tile per workgroup of the 256 x 256 kernel (allocated on first use)
+  // sparse-correction option: clean logits [positions][V], dropped-dimension lists (allocated on first use)
+  float* sp_clean = nullptr;
+  size_t sp_clean_floats = 0;
+  uint32_t* sp_ent = nullptr;
+  uint32_t* sp_cnt = nullptr;
+  size_t sp_ent_words = 0, sp_cnt_words = 0;
   bool borrowed = false;              // the workspace is the static device array: nothing is allocated or freed
   // distribution-level rule (dm_reserve_js): stored logits and per-chunk partial sums
   float* lt = nullptr;
@@ -175,7 +181,7 @@ const char* check_params(const dm_params* p, char* scratch, size_t n) {
   if (p->rule >= DM_RULE_JS && p->parent != nullptr)
     return "the distribution-level rules are defined for chains only (parent must be NULL)";
   if (p->flags & ~(DM_FLAG_SHARE_MASK_ACROSS_POS | DM_FLAG_FORCE_GENERIC | DM_FLAG_CLEAN_LAST_PATH | DM_FLAG_SEPARATE_VOTE |
-                   DM_FLAG_SAMPLE_PATHS))
+                   DM_FLAG_SAMPLE_PATHS | DM_FLAG_SPARSE_CORRECTION))
     return "unknown bits in flags";
   if ((p->flags & DM_FLAG_CLEAN_LAST_PATH) && p->K < 2) return "DM_FLAG_CLEAN_LAST_PATH needs K >= 2";
   if (p->flags & DM_FLAG_SAMPLE_PATHS) {
@@ -295,6 +301,55 @@ void drop_events(dm_ctx* ctx) {
   ctx->ev = nullptr;
 }
 
+// Path tokens by "clean row minus corrections over the dropped dimensions" (sparse_correction.hip):
+// the clean logits of the B*T positions from the contraction kernel (one undropped row per position,
+// all logits kept), the dropped-dimension lists, then the corrections and the arg max.
+dm_status run_sparse_correction(dm_ctx* ctx, const dm_params* prm, const dm::RowGeom& g, const void* h, const void* W,
+                                hipStream_t s) {
+  const int64_t P = (int64_t)prm->B * prm->T;
+  if (P > 0x7FFFFFFF) return fail(ctx, DM_EINVAL, "B*T too large");
+  const size_t clean_floats = (size_t)P * (size_t)prm->V;
+  const size_t nslab = (size_t)prm->d / 64;
+  const size_t ent_words = (size_t)g.M * nslab * 64, cnt_words = (size_t)g.M * nslab;
+  if (clean_floats > ctx->sp_clean_floats || ent_words > ctx->sp_ent_words || cnt_words > ctx->sp_cnt_words) {
+    if (hipDeviceSynchronize() != hipSuccess) return fail(ctx, DM_EHIP, "device synchronisation failed before reallocating");
+    if (ctx->sp_clean) (void)hipFree(ctx->sp_clean);
+    if (ctx->sp_ent) (void)hipFree(ctx->sp_ent);
+    if (ctx->sp_cnt) (void)hipFree(ctx->sp_cnt);
+    ctx->sp_clean = nullptr;
+    ctx->sp_ent = ctx->sp_cnt = nullptr;
+    ctx->sp_clean_floats = ctx->sp_ent_words = ctx->sp_cnt_words = 0;
+    hipError_t e;
+    if ((e = hipMalloc((void**)&ctx->sp_clean, clean_floats * 4)) != hipSuccess ||
+        (e = hipMalloc((void**)&ctx->sp_ent, ent_words * 4)) != hipSuccess ||
+        (e = hipMalloc((void**)&ctx->sp_cnt, cnt_words * 4)) != hipSuccess) {
+      (void)hipGetLastError();
+      if (ctx->sp_clean) (void)hipFree(ctx->sp_clean);
+      if (ctx->sp_ent) (void)hipFree(ctx->sp_ent);
+      ctx->sp_clean = nullptr;
+      ctx->sp_ent = ctx->sp_cnt = nullptr;
+      return fail(ctx, DM_ENOMEM, "buffers of the sparse-correction option (%zu bytes) could not be allocated: %s",
+                  clean_floats * 4 + ent_words * 4 + cnt_words * 4, hipGetErrorString(e));
+    }
+    ctx->sp_clean_floats = clean_floats;
+    ctx->sp_ent_words = ent_words;
+    ctx->sp_cnt_words = cnt_words;
+  }
+  // one undropped row per position: the same step with K = 1 and p = 0, every logit written (scale 1)
+  dm_params cp = *prm;
+  cp.K = 1;
+  cp.p = 0.0f;
+  cp.flags = 0;
+  dm::RowGeom gc;
+  if (dm_status st = make_geom(ctx, &cp, true, &gc)) return st;
+  if (dm_status st = run_contraction(ctx, &cp, gc, true, h, W, ctx->sp_clean, 0, prm->V, s)) return st;
+  hipError_t e = dm::launch_drop_lists(h, ctx->sp_ent, ctx->sp_cnt, ctx->keys, prm->seeds, g, s);
+  if (e != hipSuccess) return fail_hip(ctx, "drop_lists launch", e);
+  e = dm::launch_sparse_correct(W, ctx->sp_clean, ctx->sp_ent, ctx->sp_cnt, ctx->keys, (int)P, prm->K, prm->d, prm->V, s);
+  if (e != hipSuccess) return fail_hip(ctx, "sparse_correct launch", e);
+  return DM_OK;
+}
+
 // The verification step; draft_probs != nullptr selects the distribution-level rules.
 dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const void* W, const int32_t* draft_ids,
                       const float* draft_probs, int32_t* accept_len, int32_t* best_node, uint8_t* accept_mask,
@@ -361,6 +416,16 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
   dm::VoteFuse fuse{ctx->done, draft_ids, prm->parent, prm->B, prm->T, prm->K, Kv, prm->rule, out};
   const bool want_fuse = !js && !(prm->flags & DM_FLAG_SEPARATE_VOTE);
   bool fused = false;
+  if (prm->flags & DM_FLAG_SPARSE_CORRECTION) {
+    if (js || (prm->flags & (DM_FLAG_SAMPLE_PATHS | DM_FLAG_FORCE_GENERIC)) || !mfma || prm->K > dm::kSparseMaxK || ctx->borrowed)
+      return fail(ctx, DM_EUNSUPPORTED, "DM_FLAG_SPARSE_CORRECTION takes bf16 with d %% 64 == 0, K <= %d, a token-level rule, "
+                  "arg-max path tokens, on a context", dm::kSparseMaxK);
+    if (dm_status st = run_sparse_correction(ctx, prm, g, h, W, s)) return st;
+    const hipError_t ev_ = dm::launch_vote_accept(ctx->keys, draft_ids, prm->parent, prm->B, prm->T, prm->K, Kv, prm->rule, out,
+                                                  nullptr, nullptr, s);
+    if (ev_ != hipSuccess) return fail_hip(ctx, "vote_accept launch", ev_);
+    return DM_OK;
+  }
   // sampled tokens on the 256 x 256 kernel: its copy wavefronts leave a tile of noise (256 KB) per workgroup,
   // at most one workgroup per compute unit; allocated by the first call that needs it
   if ((prm->flags & DM_FLAG_SAMPLE_PATHS) && !nucleus && mfma && g.M > 128 && ctx->noise == nullptr && !ctx->borrowed) {
@@ -525,6 +590,9 @@ dm_status dm_destroy(dm_ctx* ctx) {
   if (ctx->done) (void)hipFree(ctx->done);
   if (ctx->seeds_dev) (void)hipFree(ctx->seeds_dev);
   if (ctx->noise) (void)hipFree(ctx->noise);
+  if (ctx->sp_clean) (void)hipFree(ctx->sp_clean);
+  if (ctx->sp_ent) (void)hipFree(ctx->sp_ent);
+  if (ctx->sp_cnt) (void)hipFree(ctx->sp_cnt);
   if (ctx->lt) (void)hipFree(ctx->lt);
   if (ctx->part_a) (void)hipFree(ctx->part_a);
   if (ctx->part_b) (void)hipFree(ctx->part_b);

@@ -155,6 +155,15 @@ hipError_t launch_vote_accept(const unsigned long long* keys, const int32_t* dra
                               const JsGeom* jg, hipStream_t stream);
 hipError_t prepare_vote_accept();
 
+// The path logits as clean row minus per-path corrections over the dropped dimensions (sparse_correction.hip).
+// ent: [rows][d / 64][64] words (dimension inside the slab | bf16 bits of h << 16), cnt: [rows][d / 64];
+// clean: [positions][V] logits of the undropped rows.  bf16, d % 64 == 0, K <= kSparseMaxK.
+constexpr int kSparseMaxK = 32;
+hipError_t launch_drop_lists(const void* h, uint32_t* ent, uint32_t* cnt, unsigned long long* keys,
+                             const uint64_t* seeds_host, const RowGeom& g, hipStream_t stream);
+hipError_t launch_sparse_correct(const void* W, const float* clean, const uint32_t* ent, const uint32_t* cnt,
+                                 unsigned long long* keys, int P, int K, int d, int V, hipStream_t stream);
+
 // Measurement aid: plain streaming read of `bytes` bytes (a multiple of 16) at src; sink: one device word.
 hipError_t launch_stream_read(const void* src, size_t bytes, int num_cu, unsigned int* sink, hipStream_t stream);
 

@@ -61,7 +61,7 @@ def test_validate_accepts_the_benchmark_shapes():
     (dict(T=4096, K=8), "T*K"), (dict(d=0), "d"), (dict(V=0), "V"), (dict(dtype=7), "dtype"),
     (dict(p=1.0), "p"), (dict(p=-0.5), "p"), (dict(p=float("nan")), "p"), (dict(rule=4), "rule"), (dict(rule=-1), "rule"),
     (dict(rule=dmb.DM_RULE_JS, K=65), "K <= 64"), (dict(rule=dmb.DM_RULE_JS_OR_MAJORITY, parent_ptr=1), "chains"),
-    (dict(flags=32), "flags"), (dict(flags=dmb.DM_FLAG_SAMPLE_PATHS), "temperature"),
+    (dict(flags=64), "flags"), (dict(flags=dmb.DM_FLAG_SAMPLE_PATHS), "temperature"),
     (dict(flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=float("inf")), "temperature"),
     (dict(flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=1.0, rule=dmb.DM_RULE_JS), "token-level"), (dict(flags=dmb.DM_FLAG_CLEAN_LAST_PATH, K=1), "K >= 2"),
     (dict(flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=1.0, top_p=1.5), "top_p"),
