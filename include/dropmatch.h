@@ -124,8 +124,7 @@ typedef struct {
   uint32_t step;   /* Philox counter word 3: vary per decode step to get fresh masks from fixed seeds.
                       seeds and step are read on the host and travel as kernel arguments: a call
                       captured into a HIP graph replays the masks (and sampling noise) it was
-                      captured with; capture one graph per step value, or update the kernel node
-                      parameters, to get fresh masks from replays */
+                      captured with; see step_dev for replays with fresh masks */
   int32_t rule;    /* dm_rule */
   uint32_t flags;  /* DM_FLAG_* */
   const uint64_t* seeds; /* HOST [B]: mask seed per sequence; read before the call returns */
@@ -135,6 +134,12 @@ typedef struct {
   float temperature;     /* DM_FLAG_SAMPLE_PATHS only: > 0, finite.  Ignored otherwise. */
   float top_p;           /* DM_FLAG_SAMPLE_PATHS only: 0 or 1 = draw from the whole distribution;
                             0 < top_p < 1 = from its nucleus (see the flag).  Ignored otherwise. */
+  const uint32_t* step_dev; /* DEVICE or NULL.  If given, the 32-bit word it points to is read by the kernels
+                            when they RUN and added to `step` (mod 2^32): a call captured into a HIP graph
+                            then draws fresh masks (and sampling noise) on every replay for which the
+                            caller has changed that word, e.g. with a copy node or a one-thread kernel
+                            ordered before the replay.  The word must stay valid and unchanged while the
+                            call's kernels run. */
 } dm_params;
 
 /* Create a context on HIP device `device` able to serve calls with B*T*K <= max_rows,

@@ -30,7 +30,7 @@ class dm_params(C.Structure):
     _fields_ = [("B", C.c_int32), ("T", C.c_int32), ("K", C.c_int32), ("d", C.c_int32), ("V", C.c_int32),
                 ("dtype", C.c_int32), ("p", C.c_float), ("step", C.c_uint32), ("rule", C.c_int32),
                 ("flags", C.c_uint32), ("seeds", C.POINTER(C.c_uint64)), ("parent", C.c_void_p),
-                ("temperature", C.c_float), ("top_p", C.c_float)]
+                ("temperature", C.c_float), ("top_p", C.c_float), ("step_dev", C.c_void_p)]
 
 
 class DropMatchError(RuntimeError):
@@ -100,12 +100,12 @@ def _ptr(t) -> Optional[int]:
 
 def make_params(B: int, T: int, K: int, d: int, V: int, dtype: int, p: float, seeds: Sequence[int],
                 step: int = 0, rule: int = DM_RULE_ANY, flags: int = 0, parent=None, temperature: float = 0.0,
-                top_p: float = 0.0):
+                top_p: float = 0.0, step_dev=None):
     """Fill a dm_params.  Returns (params, keepalive): hold `keepalive` while params is in use."""
     arr = (C.c_uint64 * len(seeds))(*[int(s) & 0xFFFFFFFFFFFFFFFF for s in seeds])
     prm = dm_params(B, T, K, d, V, dtype, p, step, rule, flags, C.cast(arr, C.POINTER(C.c_uint64)), _ptr(parent),
-                    temperature, top_p)
-    return prm, (arr, parent)
+                    temperature, top_p, _ptr(step_dev))
+    return prm, (arr, parent, step_dev)
 
 
 def dm_validate(prm: dm_params):

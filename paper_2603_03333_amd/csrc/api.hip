@@ -228,6 +228,7 @@ dm_status make_geom(dm_ctx* ctx, const dm_params* p, bool mfma, dm::RowGeom* g) 
   g->d_pad = (int)round_up(p->d, 64);
   g->thr = (uint32_t)std::floor((double)p->p * 4294967296.0);
   g->step = p->step;
+  g->step_dev = p->step_dev;
   g->share_pos = (p->flags & DM_FLAG_SHARE_MASK_ACROSS_POS) ? 1 : 0;
   g->clean_last = (p->flags & DM_FLAG_CLEAN_LAST_PATH) ? 1 : 0;
   return DM_OK;
@@ -267,7 +268,7 @@ dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g,
     at.stop = ev[2];
   }
   const float scale = (float)(1.0 / (1.0 - (double)p->p));
-  dm::SampleCfg samp{nullptr, 0.f, p->T, p->K, p->step, g.clean_last, ctx->noise};
+  dm::SampleCfg samp{nullptr, 0.f, p->T, p->K, p->step, g.clean_last, ctx->noise, p->step_dev};
   if (sample) {
     samp.seeds = ctx->seeds_dev;
     samp.zscale = (float)(1.0 / (1.0 - (double)p->p) / (double)p->temperature);
@@ -452,7 +453,7 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
     if (ev && all_stages) (void)hipEventRecord(ev[4], s);
   } else if (nucleus) {
     const float scale = (float)(1.0 / (1.0 - (double)prm->p));
-    const dm::SampleCfg samp{ctx->seeds_dev, 0.f, prm->T, prm->K, prm->step, g.clean_last, nullptr};
+    const dm::SampleCfg samp{ctx->seeds_dev, 0.f, prm->T, prm->K, prm->step, g.clean_last, nullptr, prm->step_dev};
     e = dm::launch_nucleus(ctx->lt, ctx->keys, ctx->nuc, ng, samp, scale, (float)(1.0 / (double)prm->temperature),
                            (double)prm->top_p, s);
     if (e != hipSuccess) return fail_hip(ctx, "nucleus launch", e);

@@ -20,9 +20,16 @@ struct RowGeom {
   int d_pad;       // columns of the plain workspace layout (zero columns past d)
   uint32_t thr;    // drop threshold floor(p * 2^32)
   uint32_t step;
+  const uint32_t* step_dev;  // DEVICE word added to step when the kernels run (nullptr: nothing added)
   int share_pos;   // row word of the counter forced to 0
   int clean_last;  // path K-1 of every row keeps every dimension (the plain LM head)
 };
+
+// Counter word 3 of both Philox streams: the step of the call plus, if given, a word the kernels read from
+// device memory when they run (so that a captured graph can be replayed with fresh masks and noise).
+__device__ __forceinline__ uint32_t step_now(uint32_t step, const uint32_t* step_dev) {
+  return step_dev != nullptr ? step + *step_dev : step;
+}
 
 // Eq. (1)+(2) without the scale: masked rows a = keep ? h : 0 into the workspace, and the
 // per-row argmax keys reset to 0.  swizzled = layout of the MFMA kernel's B-fragments;
@@ -61,7 +68,8 @@ struct SampleCfg {
   int T, K;
   uint32_t step;
   int clean_last;
-  float* noise;  // DEVICE scratch, 256 KB per workgroup of the 256 x 256 kernel (its copy wavefronts draw the noise), or null
+  float* noise;
+  const uint32_t* step_dev = nullptr;  // as in RowGeom  // DEVICE scratch, 256 KB per workgroup of the 256 x 256 kernel (its copy wavefronts draw the noise), or null
 };
 
 // Where a contraction kernel is launched: the stream and, optionally, two events that receive the

@@ -117,7 +117,7 @@ __global__ __launch_bounds__(256) void lmhead_generic_kernel(const T* __restrict
     if (SAMPLE) rng = make_row_rng(samp, m0 + ty * 4 + x, M);
     const bool noisy = SAMPLE && rng.on;
     float g[4] = {0.f, 0.f, 0.f, 0.f};
-    if (noisy) gumbel4(rng, (uint32_t)(v0 + tx * 4), samp.step, g);
+    if (noisy) gumbel4(rng, (uint32_t)(v0 + tx * 4), step_now(samp.step, samp.step_dev), g);
 #pragma unroll
     for (int y = 0; y < 4; ++y) {
       const int v = v0 + tx * 4 + y;

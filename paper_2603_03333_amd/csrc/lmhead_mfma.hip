@@ -248,7 +248,7 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
             if (mt == k) r = rng[k];
           float g[4] = {0.f, 0.f, 0.f, 0.f};
           if (r.on) {
-            gumbel4(r, (uint32_t)(vb + 32 * ((noise_b >> 2) & 1) + 8 * (noise_b & 3)), samp.step, g);
+            gumbel4(r, (uint32_t)(vb + 32 * ((noise_b >> 2) & 1) + 8 * (noise_b & 3)), step_now(samp.step, samp.step_dev), g);
 #pragma unroll
             for (int e = 0; e < 4; ++e) g[e] *= inv_zscale;
           }
@@ -312,7 +312,7 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
             const bool noisy = SAMPLE && rng[mt].on;
             // blocks below NBL got their noise in the k loop (as g / zscale, so the same expression below holds)
             if (noisy && mt * 8 + vt * 4 + rq >= NBL)
-              gumbel4(rng[mt], (uint32_t)(v0 + 64 * wave + 32 * vt + 8 * rq + 4 * hb), samp.step, g);
+              gumbel4(rng[mt], (uint32_t)(v0 + 64 * wave + 32 * vt + 8 * rq + 4 * hb), step_now(samp.step, samp.step_dev), g);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {  // ascending v for this lane: strict > keeps the smallest index
               const int r = 4 * rq + e;

@@ -218,7 +218,7 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
       if ((k & 7) == 0) nrng = make_row_rng(samp, (int64_t)tm * BM + (rs >> 2) * 128 + (rs & 3) * 32 + (lane & 31), M);
       const int v4 = v_lo + tv * BN + 64 * wv_k + 32 * vt + 8 * p + 4 * (lane >> 5);
       float g[4] = {0.f, 0.f, 0.f, 0.f};
-      if (nrng.on) gumbel4(nrng, (uint32_t)v4, samp.step, g);
+      if (nrng.on) gumbel4(nrng, (uint32_t)v4, step_now(samp.step, samp.step_dev), g);
       // written once, read once, by this compute unit: streaming, so that it does not displace the W and
       // masked-row slabs the workgroups of the XCD share through L2
       __builtin_nontemporal_store(f32x4{g[0], g[1], g[2], g[3]}, noise_wg + (4 * k + p) * 64 + lane);
@@ -409,7 +409,7 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
             g[2] = g4.z;
             g[3] = g4.w;
           } else if (noisy) {
-            gumbel4(rng, (uint32_t)(vb + 32 * vt + 8 * rq), samp.step, g);
+            gumbel4(rng, (uint32_t)(vb + 32 * vt + 8 * rq), step_now(samp.step, samp.step_dev), g);
           }
 #pragma unroll
           for (int e = 0; e < 4; ++e) {  // ascending v for this lane: strict > keeps the smallest index

@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256) void mask_rows_kernel(const T* __restrict__ h,
     const uint64_t seed = seeds.s[b - b0];
     const uint32_t bits = (g.clean_last && i == g.K - 1)
                               ? 0xFFu
-                              : keep_bits8(o, g.share_pos ? 0u : (uint32_t)t, (uint32_t)i, g.step,
+                              : keep_bits8(o, g.share_pos ? 0u : (uint32_t)t, (uint32_t)i, step_now(g.step, g.step_dev),
                                            (uint32_t)seed, (uint32_t)(seed >> 32), g.thr);
     const T* src = h + ((int64_t)b * g.T + t) * g.d + 8 * (int64_t)o;
     if ((g.d & 7) == 0) {
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(256) void mask_bits_kernel(uint32_t* __restrict__ b
   } else {
 #pragma unroll
     for (uint32_t q = 0; q < 4; ++q)
-      word |= keep_bits8(4u * w + q, g.share_pos ? 0u : (uint32_t)t, (uint32_t)i, g.step, (uint32_t)seed,
+      word |= keep_bits8(4u * w + q, g.share_pos ? 0u : (uint32_t)t, (uint32_t)i, step_now(g.step, g.step_dev), (uint32_t)seed,
                          (uint32_t)(seed >> 32), g.thr)
               << (8u * q);
   }

@@ -232,7 +232,7 @@ __global__ __launch_bounds__(NT) void nucleus_draw_kernel(const float* __restric
         }
         if (!any) continue;
         float gn[4];
-        gumbel4(rng, (uint32_t)v4, samp.step, gn);
+        gumbel4(rng, (uint32_t)v4, step_now(samp.step, samp.step_dev), gn);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           if (!in[e]) continue;

@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void drop_lists_kernel(const uint16_t* __restr
   if (lane == 0) keys[r] = 0ull;
   for (int s = 0; s < nslab; ++s) {
     const int j = s * SK + lane;
-    const uint32_t bits = keep_bits8((uint32_t)j >> 3, g.share_pos ? 0u : (uint32_t)t, (uint32_t)i, g.step,
+    const uint32_t bits = keep_bits8((uint32_t)j >> 3, g.share_pos ? 0u : (uint32_t)t, (uint32_t)i, step_now(g.step, g.step_dev),
                                      (uint32_t)seed, (uint32_t)(seed >> 32), g.thr);
     const bool dropped = !clean && ((bits >> (j & 7)) & 1u) == 0u;
     const unsigned long long m = __ballot(dropped);

@@ -353,6 +353,60 @@ def test_verify_can_be_captured_in_a_hip_graph(runner, d, V, B, T, K, tau):
                         out, eager, between)
 
 
+@pytest.mark.parametrize("d,V,B,T,K,tau", [
+    (256, 3000, 2, 6, 8, 0.0),      # W-streaming kernel
+    (1024, 2000, 2, 6, 16, 0.7),    # 256 x 256 kernel, sampled tokens (noise drawn by the copy wavefronts)
+    (100, 130, 2, 3, 5, 1.5),       # generic kernel, sampled tokens (bf16 storage)
+])
+def test_graph_replays_draw_fresh_masks_from_the_device_step_word(runner, d, V, B, T, K, tau):
+    """step and the seeds travel as kernel arguments, so a captured call would replay the masks it was
+    captured with; with dm_params.step_dev the kernels add a word they read from device memory when they
+    run.  One captured graph, the word changed between replays: every replay equals the eager call (and
+    the oracle's masks) with step = base + word."""
+    wl, W, h, seeds, draft = _problem("graphstep", d, V, "bf16", B, T, K, 0.2, seed=99, bonus=True)
+    hd, Wd = to_device(h, "bf16"), to_device(W, "bf16")
+    kw = dict(flags=dmb.DM_FLAG_SAMPLE_PATHS, temperature=tau) if tau else {}
+    base = 2 ** 32 - 2                                       # the sum wraps around
+    word = torch.zeros(1, dtype=torch.int32, device="cuda")
+    prm, keep = runner.params(wl, seeds, step=base, **kw)
+    prm.step_dev = word.data_ptr()
+    draft_dev = torch.from_numpy(draft).cuda()
+    out = dict(accept_len=torch.zeros(wl.B, dtype=torch.int32, device="cuda"),
+               hit=torch.zeros((wl.B, wl.T), dtype=torch.uint8, device="cuda"),
+               path_ids=torch.zeros((wl.B, wl.T, wl.K), dtype=torch.int32, device="cuda"),
+               vote_ids=torch.zeros((wl.B, wl.T), dtype=torch.int32, device="cuda"))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dmb.dropmatch_verify(runner.ctx, prm, hd, Wd, draft_dev, stream=side, **out)     # warm-up on the capture stream
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        dmb.dropmatch_verify(runner.ctx, prm, hd, Wd, draft_dev, stream=torch.cuda.current_stream(), **out)
+    seen = []
+    for w in (0, 1, 5, 1):
+        word.fill_(w)
+        for v in out.values():
+            v.fill_(7 if v.dtype == torch.uint8 else -1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = {k: v.cpu().numpy() for k, v in out.items()}
+        eager = runner.verify(wl, hd, Wd, draft, seeds, step=(base + w) % 2 ** 32, **kw)   # eager work between replays
+        for k in got:
+            assert np.array_equal(got[k], eager[k]), f"word {w}: {k}"
+        seen.append(got["path_ids"])
+    assert (seen[0] != seen[1]).any() and (seen[1] != seen[2]).any() and np.array_equal(seen[1], seen[3])
+    # the masks themselves, through the debug call: base + word, modulo 2^32
+    word.fill_(3)
+    bits = torch.zeros((wl.B, wl.T, wl.K, (wl.d + 31) // 32), dtype=torch.int32, device="cuda")
+    dmb.dm_debug_masks(runner.ctx, prm, bits)
+    torch.cuda.synchronize()
+    want = np.stack([orc.pack_mask_bits(orc.keep_masks(int(s), (base + 3) % 2 ** 32, wl.T, wl.K, wl.d, wl.p)) for s in seeds])
+    assert np.array_equal(bits.cpu().numpy().view(np.uint32), want)
+    del graph, keep
+
+
 # ------------------------------------------------------------------ clean last path
 @pytest.mark.parametrize("d,V,B,T,K,dtype", [
     (256, 3000, 2, 6, 16, "bf16"),    # MFMA kernel, 192 rows -> 256-row tiles
