@@ -562,6 +562,9 @@ def test_profiling_modes_time_kernels_and_leave_results_alone(runner, d, V, B, T
         n, ms = dmb.dm_get_profile_stages(runner.ctx)
         assert n == 3                                   # calls 0, 3 and 6
         assert 0.0 < ms[1] < 50.0 and ms[0] == 0.0 and ms[4] == 0.0
+        samples = dmb.dm_get_profile_samples(runner.ctx, 1)        # the durations behind that mean
+        assert len(samples) == 3 and all(x > 0.0 for x in samples) and np.mean(samples) == pytest.approx(ms[1], rel=1e-5)
+        assert dmb.dm_get_profile_samples(runner.ctx, 0) == [] and dmb.dm_get_profile_samples(runner.ctx, 1, n_max=2) == samples[:2]
 
         dmb.dm_set_profiling_stride(runner.ctx, 1)
         dmb.dm_set_profiling(runner.ctx, 1)
@@ -573,6 +576,9 @@ def test_profiling_modes_time_kernels_and_leave_results_alone(runner, d, V, B, T
         assert n == 4 and ms[0] > 0.0 and ms[1] > 0.0 and ms[4] >= 0.0 and ms[2] == 0.0 and ms[3] == 0.0  # no JS passes in dropmatch_verify
         n3, m0, m1, m4 = dmb.dm_get_profile(runner.ctx)
         assert n3 == 4 and m1 == pytest.approx(ms[1])
+        assert len(dmb.dm_get_profile_samples(runner.ctx, 0)) == 4 and dmb.dm_get_profile_samples(runner.ctx, 2) == []
+        with pytest.raises(dmb.DropMatchError):
+            dmb.dm_get_profile_samples(runner.ctx, 5)
 
         dmb.dm_set_profiling(runner.ctx, 0)
         assert dmb.dm_get_profile_stages(runner.ctx)[0] == 0
@@ -581,3 +587,20 @@ def test_profiling_modes_time_kernels_and_leave_results_alone(runner, d, V, B, T
     finally:
         dmb.dm_set_profiling(runner.ctx, 0)
         dmb.dm_set_profiling_stride(runner.ctx, 1)
+
+
+def test_stream_read_aid_and_its_argument_checks(runner):
+    """dm_debug_stream_read enqueues a bare read of a buffer (the ceiling bench.py quotes beside the published
+    HBM peak): it must leave the buffer alone, and refuse sizes and addresses that are not multiples of 16."""
+    buf = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    before = buf.clone()
+    for nbytes in (16, 4 << 20, (4 << 20) - 16):
+        dmb.dm_debug_stream_read(runner.ctx, buf, nbytes)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, before)
+    for bad in (0, 8, 24, -16):
+        with pytest.raises(dmb.DropMatchError) as e:
+            dmb.dm_debug_stream_read(runner.ctx, buf, bad)
+        assert e.value.status == dmb.DM_EINVAL
+    with pytest.raises(dmb.DropMatchError):
+        dmb.dm_debug_stream_read(runner.ctx, buf[1:], 64)            # 4 bytes past a 16-byte boundary
