@@ -36,7 +36,8 @@ struct dm_ctx {
   float* part_b = nullptr;
   size_t part_floats = 0;
   // nucleus sampling (also dm_reserve_js): per-row digit histograms, search state, keys of the drawn tokens
-  dm::NucBuffers nuc{nullptr, nullptr, nullptr, nullptr, nullptr};
+  dm::NucBuffers nuc{};
+  int64_t nuc_cap = 0;
   size_t nuc_rows = 0;
   char err[512] = {0};
   // measurement aid: kEv events per recorded call
@@ -285,13 +286,13 @@ dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g,
 }
 
 void free_nucleus(dm_ctx* ctx) {
-  if (ctx->nuc.hist) (void)hipFree(ctx->nuc.hist);
-  if (ctx->nuc.prefix) (void)hipFree(ctx->nuc.prefix);
-  if (ctx->nuc.below) (void)hipFree(ctx->nuc.below);
-  if (ctx->nuc.target) (void)hipFree(ctx->nuc.target);
-  if (ctx->nuc.keys_s) (void)hipFree(ctx->nuc.keys_s);
-  ctx->nuc = dm::NucBuffers{nullptr, nullptr, nullptr, nullptr, nullptr};
+  void* const bufs[] = {ctx->nuc.hist, ctx->nuc.digit0, ctx->nuc.below, ctx->nuc.target,
+                        ctx->nuc.keys_s, ctx->nuc.cand, ctx->nuc.cand_n};
+  for (void* b : bufs)
+    if (b) (void)hipFree(b);
+  ctx->nuc = dm::NucBuffers{};
   ctx->nuc_rows = 0;
+  ctx->nuc_cap = 0;
 }
 
 void drop_events(dm_ctx* ctx) {
@@ -394,6 +395,7 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
     while (ng.KP < ng.K4) ng.KP *= 2;
     ng.KU = g.clean_last ? prm->K - 1 : prm->K;
     ng.V = prm->V;
+    ng.cap = (int)ctx->nuc_cap;
     if ((int64_t)prm->B * prm->T > 0x7FFFFFFF) return fail(ctx, DM_EINVAL, "B*T too large");
     if ((int64_t)(256 / prm->K + 2) * prm->V * ng.K4 * 4 >= ((int64_t)1 << 32))
       return fail(ctx, DM_EUNSUPPORTED, "V = %d is too large for nucleus sampling with K = %d", prm->V, prm->K);
@@ -655,8 +657,11 @@ dm_status dm_reserve_js(dm_ctx* ctx, int64_t max_positions, int32_t max_K) {
   ctx->part_floats = part_floats;
   // nucleus sampling: 256 digit bins of 8 bytes per row, kept zero between calls
   const size_t rows = (size_t)max_positions * (size_t)max_K;
+  const int64_t cap = dm::nucleus_list_capacity(ctx->max_V);
   if ((e = hipMalloc((void**)&ctx->nuc.hist, rows * 256 * 8)) != hipSuccess ||
-      (e = hipMalloc((void**)&ctx->nuc.prefix, rows * 4)) != hipSuccess ||
+      (e = hipMalloc((void**)&ctx->nuc.digit0, rows * 4)) != hipSuccess ||
+      (e = hipMalloc((void**)&ctx->nuc.cand_n, rows * 4)) != hipSuccess ||
+      (e = hipMalloc((void**)&ctx->nuc.cand, rows * (size_t)cap * 8)) != hipSuccess ||
       (e = hipMalloc((void**)&ctx->nuc.below, rows * 8)) != hipSuccess ||
       (e = hipMalloc((void**)&ctx->nuc.target, rows * 8)) != hipSuccess ||
       (e = hipMalloc((void**)&ctx->nuc.keys_s, rows * 8)) != hipSuccess ||
@@ -666,6 +671,7 @@ dm_status dm_reserve_js(dm_ctx* ctx, int64_t max_positions, int32_t max_K) {
     return fail(ctx, DM_ENOMEM, "nucleus buffers for %zu rows could not be allocated: %s", rows, hipGetErrorString(e));
   }
   ctx->nuc_rows = rows;
+  ctx->nuc_cap = cap;
   return DM_OK;
 }
 

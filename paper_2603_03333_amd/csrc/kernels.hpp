@@ -185,7 +185,8 @@ __host__ __device__ inline unsigned long long pack_key(float val, uint32_t v) {
 }
 
 // Sampled path tokens restricted to the nucleus (top-p set) of Softmax(l / tau), over the stored logits:
-// three histogram + scan levels find each row's threshold, a last pass draws inside it.
+// a histogram + scan pass finds the leading digit of each row's threshold, the draw pass draws below it and
+// lists the tokens of that digit, a last pass settles the threshold and the draw on the list.
 constexpr int kNucChunk = 1024;  // vocabulary rows per workgroup
 constexpr int kNucMaxK = 64;     // paths per row
 struct NucGeom {
@@ -195,14 +196,20 @@ struct NucGeom {
   int KP;   // K4 rounded up to a power of two (thread mapping)
   int KU;   // paths that draw (K, or K-1 when the last path is the clean one)
   int V;
+  int cap;  // entries per row of the candidate lists
 };
 struct NucBuffers {
-  unsigned long long* hist;    // [rows][256] masses per digit; zeroed by the mask kernel of the call, and by every scan
-  uint32_t* prefix;            // [rows] bits of the threshold fixed so far
-  unsigned long long* below;   // [rows] mass of the elements below the digits fixed so far
+  unsigned long long* hist;    // [rows][256] masses per leading digit; zeroed by the mask kernel of the call, and by the scan
+  uint32_t* digit0;            // [rows] leading digit of the threshold
+  unsigned long long* below;   // [rows] mass of the elements below that digit
   unsigned long long* target;  // [rows] mass the nucleus has to reach
   unsigned long long* keys_s;  // [rows] packed keys of the drawn tokens
+  uint2* cand;                 // [rows][cap] (logit bits, token) of the tokens that share the threshold's leading digit
+  uint32_t* cand_n;            // [rows] how many there are (beyond cap: the list did not fit)
 };
+// Entries per row that the lists get for a vocabulary of V tokens: an eighth of it (a flat Gaussian row puts a
+// few per cent of its tokens on the list), at least 1024.
+inline int64_t nucleus_list_capacity(int64_t V) { return V / 8 > 1024 ? V / 8 : 1024; }
 hipError_t launch_nucleus(const float* lt, const unsigned long long* keys, const NucBuffers& nb, const NucGeom& g,
                           const SampleCfg& samp, float scale, float inv_tau, double top_p, hipStream_t stream);
 hipError_t prepare_nucleus();

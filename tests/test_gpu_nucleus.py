@@ -119,8 +119,8 @@ def test_nucleus_tokens_peaked_distributions(runner):
 
 @pytest.mark.parametrize("B,T,K", [(1, 8, 16), (3, 6, 16)])     # W-streaming kernel / 256 x 256 kernel in store mode
 def test_nucleus_verify_can_be_captured_in_a_hip_graph(runner, B, T, K):
-    """The seven nucleus launches keep state between calls (bins cleared by the scans, the second key
-    array cleared at the last level): replayed from a HIP graph they must leave it as an eager call
+    """The four nucleus launches keep state between calls (bins, list counts and the second key array
+    cleared by the scan): replayed from a HIP graph they must leave it as an eager call
     does.  Every replay equals the eager call, with eager calls on other inputs in between."""
     wl = wk.Workload("nucg", d=256, V=3000, dtype="bf16", B=B, T=T, K=K, p=0.1, bonus=True, data_seed=91 + B)
     W, h, seeds = wk.make_weight(wl, sigma=0.1), wk.make_hidden(wl), wk.make_seeds(wl, base_seed=5)
@@ -141,6 +141,32 @@ def test_nucleus_verify_can_be_captured_in_a_hip_graph(runner, B, T, K):
 
     check_graph_replays(lambda st: dmb.dropmatch_verify(runner.ctx, prm, hd, Wd, draft_dev, stream=st, **out),
                         out, eager, between)
+
+
+@pytest.mark.parametrize("K,classes,top_p,tau", [
+    (16, (1.0, 0.5), 0.5, 1.0),        # 1500 tied tokens per class: the stage of a draw workgroup runs over
+    (4, (1.0, 0.5), 0.9, 1.0),         # 4 paths: the stages hold everything, the row's list itself runs over
+    (8, (1.0, 0.96875, 0.5), 0.7, 2.0),  # two classes share the leading digit of the threshold
+    (8, (0.0,), 0.6, 1.0),             # all logits equal (W = 0): the nucleus is the whole vocabulary
+])
+def test_nucleus_rows_whose_candidate_list_does_not_fit(runner, K, classes, top_p, tau):
+    """Few distinct logit values per row: thousands of tokens share the leading digit of the threshold, more
+    than a row's candidate list (max(1024, max_V / 8) entries) takes; such rows read their candidates
+    from the logit store.  W[v] = c[v mod n] * w0, so the logits of a row are c[v mod n] * (w0 . h~)."""
+    wl = wk.Workload("nucfit", d=128, V=3000, dtype="bf16", B=2, T=3, K=K, p=0.25, bonus=True, data_seed=404 + K)
+    w0 = wk.make_weight(wl.with_(V=1), sigma=0.1)[0]
+    c = np.asarray(classes, dtype=np.float32)
+    W = wk.round_to_bf16(c[np.arange(wl.V) % c.size][:, None] * w0[None, :])
+    h = wk.make_hidden(wl)
+    seeds = wk.make_seeds(wl, base_seed=8)
+    draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+    for step in (0, 5):
+        ref, res, rows, same = _run(runner, wl, W, h, seeds, draft, tau, top_p, step=step)
+        print(f"[nucleus tied classes K={K} classes={classes}] rows={rows} equal to the oracle's draw={same}", flush=True)
+        assert same >= 0.9 * rows
+    # an ordinary call right after leaves no trace of the long lists
+    W2 = wk.make_weight(wl, sigma=0.1)
+    _run(runner, wl, W2, h, seeds, wk.make_draft_ids(wl, orc.greedy_ids(h, W2)), tau, top_p)
 
 
 def test_nucleus_limits_and_options(runner):
