@@ -52,6 +52,8 @@ def parse_args():
                     help="call dropmatch_verify_static (the library's fixed workspace, no context) instead of dropmatch_verify")
     ap.add_argument("--sparse-correction", action="store_true",
                     help="path logits as clean row minus corrections over the dropped dimensions (DM_FLAG_SPARSE_CORRECTION)")
+    ap.add_argument("--separate-vote", action="store_true",
+                    help="run the acceptance step as its own kernel (DM_FLAG_SEPARATE_VOTE) instead of as the tail of another launch")
     ap.add_argument("--ramp-seconds", type=float, default=RAMP_SECONDS, help="length of the untimed clock-ramp phase")
     ap.add_argument("--secondary", default="auto",
                     help="workload of the `secondary` object: auto = batched when the headline workload is head8b "
@@ -177,7 +179,8 @@ def run_workload(wl, args, steps, warmup, rule_name="any", temperature=0.0, top_
     prm, keep = dmb.make_params(wl.B, wl.T, wl.K, wl.d, wl.V, dmb.DM_BF16 if bf16 else dmb.DM_F32, wl.p,
                                 [int(s) for s in seeds], parent=parent_dev, rule=rule,
                                 flags=(dmb.DM_FLAG_SAMPLE_PATHS if temperature > 0 else 0) |
-                                      (dmb.DM_FLAG_SPARSE_CORRECTION if sparse else 0),
+                                      (dmb.DM_FLAG_SPARSE_CORRECTION if sparse else 0) |
+                                      (dmb.DM_FLAG_SEPARATE_VOTE if getattr(args, "separate_vote", False) else 0),
                                 temperature=temperature, top_p=top_p)
     kernel = dmb.dm_kernel_choice(prm)
     out = dict(accept_len=torch.zeros(wl.B, dtype=torch.int32, device="cuda"),
