@@ -123,7 +123,7 @@ __device__ __forceinline__ void stats_loop(const float* __restrict__ base, int v
   constexpr int BL = RM::BL;
   const float* row = base + (int64_t)v_first * g.K4;
   const int64_t step = (int64_t)RM::ROWS_PER_ITER * g.K4;
-#pragma unroll(4 / BL)
+#pragma unroll 4 / BL
   for (int it0 = 0; it0 < RM::ITERS; it0 += BL) {
     float xbar2 = 0.f;
     bool mine = false;
@@ -236,7 +236,7 @@ __device__ __forceinline__ void terms_loop(const float* __restrict__ base, const
   const float* row = base + (int64_t)v_first * g.K4;
   const float* prow = dp + v_first;
   const int64_t step = (int64_t)RM::ROWS_PER_ITER * g.K4;
-#pragma unroll(4 / BL)
+#pragma unroll 4 / BL
   for (int it0 = 0; it0 < RM::ITERS; it0 += BL) {
     float l2q_d = 0.f, q_d = 0.f, ph_d = 1.f;
     bool in_d = false;

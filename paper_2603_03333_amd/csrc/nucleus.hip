@@ -72,8 +72,9 @@ __device__ __forceinline__ uint32_t lead_digit(float t) { return (uint32_t)fminf
 __device__ __forceinline__ unsigned long long mass_of(float t) {
   const float m = __builtin_amdgcn_exp2f(-t * 1.44269504088896341f) * kMassScale;
   const uint32_t hi = (uint32_t)(m * 9.5367431640625e-07f);        // m / 2^20, truncated
-  const uint32_t lo = (uint32_t)(m - (float)hi * 1048576.0f);       // exact remainder
-  return ((unsigned long long)hi << 20) + lo;
+  const uint32_t lo = (uint32_t)(m - (float)hi * 1048576.0f);       // exact remainder, below 2^20
+  // hi * 2^20 + lo as a pair of 32-bit words (two plain instructions; the 64-bit shift and add cost six issue slots)
+  return ((unsigned long long)(hi >> 12) << 32) | (unsigned long long)((hi << 20) | lo);
 }
 
 // The leading digit (bits 23..16 of the key of t) of every element of the chunk.

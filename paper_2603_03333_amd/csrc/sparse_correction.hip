@@ -30,8 +30,6 @@ constexpr int SV = 64;        // vocabulary rows per workgroup
 constexpr int SP = 4;         // positions per workgroup
 constexpr int ROW_WORDS = 33; // 64 bf16 = 32 words, + 1 word of padding
 
-__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
-
 __global__ __launch_bounds__(256) void drop_lists_kernel(const uint16_t* __restrict__ h, uint32_t* __restrict__ ent,
                                                          uint32_t* __restrict__ cnt,
                                                          unsigned long long* __restrict__ keys, SeedPack seeds,
