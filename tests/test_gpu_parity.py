@@ -493,6 +493,9 @@ def test_planted_dominant_tokens(runner):
     (1024, 2000, 2, 6, 16, "bf16", 0.7),   # 256 x 256 tiles of 16 slabs: noise drawn by the copy wavefronts; 192 of 256 rows
     (2048, 3000, 3, 7, 16, "bf16", 1.2),   # two row tiles (336 rows), ragged vocabulary, 32 slabs
     (1088, 600, 2, 5, 32, "bf16", 0.5),    # 17 slabs, K = 32, three vocabulary tiles
+    (2112, 1500, 1, 8, 16, "bf16", 0.9),   # W-streaming kernel at 128 rows (noise drawn in its epilogue), 33 slabs, ragged tiles
+    (1600, 1100, 1, 6, 16, "bf16", 1.1),   # the same at 96 rows, 25 slabs
+    (4096, 700, 1, 7, 16, "bf16", 0.8),    # 112 of 128 rows at the benchmark's d
 ])
 def test_sampled_path_tokens(runner, d, V, B, T, K, dtype, tau):
     """Path tokens drawn from Softmax(l / tau) by the Gumbel-max construction with the counter-based
