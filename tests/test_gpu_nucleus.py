@@ -169,6 +169,32 @@ def test_nucleus_rows_whose_candidate_list_does_not_fit(runner, K, classes, top_
     _run(runner, wl, W2, h, seeds, wk.make_draft_ids(wl, orc.greedy_ids(h, W2)), tau, top_p)
 
 
+def test_nucleus_candidate_list_longer_than_the_registers_hold():
+    """A list that fits its row's capacity (max_V / 8 = 5000 entries) but not the 4096 entries the last pass
+    holds in registers: it is walked in memory.  Every 9th token shares one logit (W[v] = w0), the others
+    are small Gaussian rows, so where w0 . h~ > 0 the 4445 tied tokens are the top of the row and share
+    the leading digit of the threshold; 115 of them per 1024-row chunk stay below the 128 a draw workgroup
+    stages per path."""
+    wl = wk.Workload("nuclong", d=128, V=40000, dtype="bf16", B=1, T=3, K=4, p=0.2, bonus=True, data_seed=911)
+    r = Runner(max_rows=64, max_d=128, max_V=wl.V)
+    try:
+        r.reserve_js(max_positions=wl.B * wl.T, max_K=wl.K)
+        w0 = wk.make_weight(wl.with_(V=1), sigma=0.1)[0]
+        W = wk.make_weight(wl, sigma=0.01)
+        W[::9] = w0[None, :]
+        h = wk.make_hidden(wl)
+        h[:, 1:] = wk.round_to_bf16(h[:, 1:] + 2.0 * w0)       # positions 1, 2: w0 . h~ > 0 on (nearly) every path
+        seeds = wk.make_seeds(wl, base_seed=2)
+        draft = wk.make_draft_ids(wl, orc.greedy_ids(h, W))
+        for top_p, tau in ((0.5, 1.0), (0.05, 0.7), (0.97, 1.3)):
+            ref, res, rows, same = _run(r, wl, W, h, seeds, draft, tau, top_p)
+            tied_top = sum(int(np.argmax(ref["logits"][x]) % 9 == 0) for x in range(rows))
+            print(f"[nucleus long list top_p={top_p}] rows={rows} equal={same} rows whose top is the tied class={tied_top}", flush=True)
+            assert same >= 0.9 * rows and tied_top >= 6
+    finally:
+        r.close()
+
+
 def test_nucleus_limits_and_options(runner):
     wl = wk.Workload("nucl", d=128, V=1000, dtype="bf16", B=2, T=5, K=8, p=0.3, bonus=True, data_seed=5)
     W, h = wk.make_weight(wl, sigma=0.05), wk.make_hidden(wl)
