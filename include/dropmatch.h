@@ -89,7 +89,8 @@ typedef enum {
  * K <= DM_MAX_K_JS, T*K <= DM_MAX_TK_JS), finds each row's threshold (with t the distance from the
  * row's maximum over the temperature: probability mass in 64-bit integers, floor(e^-t 2^44), so
  * reproducible run to run; tokens whose t agree to 2^-19 count as equally probable) and then draws
- * from the stored logits. */
+ * from the stored logits.  Rows whose distribution is so flat that more than an eighth of the
+ * vocabulary lies within 0.125 of the threshold in t take a slower path through the logit store. */
 #define DM_FLAG_SAMPLE_PATHS 16u
 
 /* The same path logits by linearity of Eq. 3, W (h * m) = W h - W (h * (1 - m)): one undropped row per
@@ -214,8 +215,10 @@ dm_status dropmatch_verify(dm_ctx* ctx, const dm_params* prm,
  *
  * dm_reserve_js allocates, once, what these rules need beyond dm_create: the logits of every path
  * (max_positions * max_V * roundup(max_K, 4) floats; unlike on the token-level path they are stored,
- * because Eq. 6 needs the normalisers before it can form its sums) and two small arrays of partial
- * sums.  It synchronises the device and may be called again to resize.  B*T <= max_positions and
+ * because Eq. 6 needs the normalisers before it can form its sums), two small arrays of partial
+ * sums, and for nucleus sampling 2 KB of search state plus a candidate list of max(1024, max_V / 8)
+ * (logit, token) pairs per masked row (max_positions * max_K rows; a quarter of the logit store at
+ * K = 16).  It synchronises the device and may be called again to resize.  B*T <= max_positions and
  * K <= max_K must then hold for every dropmatch_verify_js on this context.
  *
  * dropmatch_verify_js: same contract and outputs as dropmatch_verify, plus
