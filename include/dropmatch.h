@@ -90,7 +90,8 @@ typedef enum {
  * row's maximum over the temperature: probability mass in 64-bit integers, floor(e^-t 2^44), so
  * reproducible run to run; tokens whose t agree to 2^-19 count as equally probable) and then draws
  * from the stored logits.  Rows whose distribution is so flat that more than an eighth of the
- * vocabulary lies within 0.125 of the threshold in t take a slower path through the logit store. */
+ * vocabulary lies within 0.125 of the threshold in t (1/128 from temperature 2 on, up to 32 paths)
+ * take a slower path through the logit store: same result, several times the time. */
 #define DM_FLAG_SAMPLE_PATHS 16u
 
 /* The same path logits by linearity of Eq. 3, W (h * m) = W h - W (h * (1 - m)): one undropped row per

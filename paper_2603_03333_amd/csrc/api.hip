@@ -255,7 +255,7 @@ dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g,
   reset.counter = ctx->done;
   if (nucleus_rows > 0) {
     reset.zero64 = ctx->nuc.hist;
-    reset.n64 = nucleus_rows * 256;
+    reset.n64 = nucleus_rows * 512;
   }
   hipError_t e = dm::launch_mask_rows(h, ctx->a_ws, ctx->keys, p->seeds, g, bf16, mfma,
                                       want_seeds ? ctx->seeds_dev : nullptr, reset, s);
@@ -396,6 +396,7 @@ dm_status verify_impl(dm_ctx* ctx, const dm_params* prm, const void* h, const vo
     ng.KU = g.clean_last ? prm->K - 1 : prm->K;
     ng.V = prm->V;
     ng.cap = (int)ctx->nuc_cap;
+    ng.fine = dm::nucleus_fine_bins(ng.KP, prm->temperature) ? 1 : 0;
     if ((int64_t)prm->B * prm->T > 0x7FFFFFFF) return fail(ctx, DM_EINVAL, "B*T too large");
     if ((int64_t)(256 / prm->K + 2) * prm->V * ng.K4 * 4 >= ((int64_t)1 << 32))
       return fail(ctx, DM_EUNSUPPORTED, "V = %d is too large for nucleus sampling with K = %d", prm->V, prm->K);
@@ -655,17 +656,17 @@ dm_status dm_reserve_js(dm_ctx* ctx, int64_t max_positions, int32_t max_K) {
   }
   ctx->lt_floats = lt_floats;
   ctx->part_floats = part_floats;
-  // nucleus sampling: 256 digit bins of 8 bytes per row, kept zero between calls
+  // nucleus sampling: 512 digit bins (coarse, fine) of 8 bytes per row, kept zero between calls
   const size_t rows = (size_t)max_positions * (size_t)max_K;
   const int64_t cap = dm::nucleus_list_capacity(ctx->max_V);
-  if ((e = hipMalloc((void**)&ctx->nuc.hist, rows * 256 * 8)) != hipSuccess ||
+  if ((e = hipMalloc((void**)&ctx->nuc.hist, rows * 512 * 8)) != hipSuccess ||
       (e = hipMalloc((void**)&ctx->nuc.digit0, rows * 4)) != hipSuccess ||
       (e = hipMalloc((void**)&ctx->nuc.cand_n, rows * 4)) != hipSuccess ||
       (e = hipMalloc((void**)&ctx->nuc.cand, rows * (size_t)cap * 8)) != hipSuccess ||
       (e = hipMalloc((void**)&ctx->nuc.below, rows * 8)) != hipSuccess ||
       (e = hipMalloc((void**)&ctx->nuc.target, rows * 8)) != hipSuccess ||
       (e = hipMalloc((void**)&ctx->nuc.keys_s, rows * 8)) != hipSuccess ||
-      (e = hipMemset(ctx->nuc.hist, 0, rows * 256 * 8)) != hipSuccess) {
+      (e = hipMemset(ctx->nuc.hist, 0, rows * 512 * 8)) != hipSuccess) {
     (void)hipGetLastError();
     free_nucleus(ctx);
     return fail(ctx, DM_ENOMEM, "nucleus buffers for %zu rows could not be allocated: %s", rows, hipGetErrorString(e));

@@ -197,10 +197,19 @@ struct NucGeom {
   int KU;   // paths that draw (K, or K-1 when the last path is the clean one)
   int V;
   int cap;  // entries per row of the candidate lists
+  int fine; // the first histogram has fine bins next to the row's maximum (see nucleus_fine_bins)
 };
+constexpr int kNucFineMaxKP = 32;
+// Whether a call uses the fine bins.  They cost the histogram and draw passes 7 % (more instructions per
+// element, more non-empty bins to add to memory) and matter for rows so flat that an eighth of the
+// vocabulary lies within 0.125 * temperature of the threshold in logit units: taken from a temperature of 2
+// on, where synthetic Gaussian rows start to come close to that; they double the LDS of the histogram pass, so
+// only up to 32 paths.
+inline bool nucleus_fine_bins(int KP, float temperature) { return KP <= kNucFineMaxKP && temperature >= 2.0f; }
 struct NucBuffers {
-  unsigned long long* hist;    // [rows][256] masses per leading digit; zeroed by the mask kernel of the call, and by the scan
-  uint32_t* digit0;            // [rows] leading digit of the threshold
+  unsigned long long* hist;    // [rows][512] masses per leading digit, 256 coarse bins then 256 fine ones; zeroed by the
+                               // mask kernel of the call, and by the scan
+  uint32_t* digit0;            // [rows] leading digit of the threshold | (its position in the key, 16 or 12) << 16
   unsigned long long* below;   // [rows] mass of the elements below that digit
   unsigned long long* target;  // [rows] mass the nucleus has to reach
   unsigned long long* keys_s;  // [rows] packed keys of the drawn tokens

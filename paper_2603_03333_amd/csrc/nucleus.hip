@@ -14,7 +14,8 @@
 // Only the first level and the draw read the whole logit store:
 //   nucleus_hist_kernel   per (position, chunk of vocabulary rows): the mass of every leading 8-bit
 //                         digit - first in LDS (one histogram per path of the position), then the
-//                         non-empty bins are added to the row's 256 bins in memory;
+//                         non-empty bins are added to the row's bins in memory (FINE: bins of two
+//                         widths, see kFineShift below);
 //   nucleus_scan_kernel   per row: walk the bins in order of growing t until the target mass
 //                         ceil(top_p * Z) is reached: that is the BOUNDARY digit; the mass below it
 //                         is carried on, the bins cleared for the next call;
@@ -26,8 +27,9 @@
 //                         on the row's candidate list, (logit, token) pairs, through LDS;
 //   nucleus_finish_kernel per row: the two remaining levels of the search over the candidate list
 //                         alone, then the draw among the candidates inside t*.  A row whose list
-//                         did not fit (nearly uniform distributions: most of the vocabulary shares
-//                         one leading digit) takes its candidates from the logit store instead.
+//                         did not fit (nearly uniform distributions: more than an eighth of the
+//                         vocabulary shares the boundary digit) takes its candidates from the logit
+//                         store instead.
 // The first and third are bound by reading the logit store, 4 * K4 bytes per (position, vocabulary
 // row) per pass, and by the vector ALU (t, key, integer mass; the noise of half the vocabulary).
 #include "kernels.hpp"
@@ -41,6 +43,15 @@ constexpr int HT = 1024;         // threads per workgroup of the histogram passe
 constexpr int kHistChunk = 4096; // vocabulary rows per histogram workgroup: every workgroup ends with up to
                                  // 256 atomic adds to memory per path, so few large ones are cheaper
 constexpr int kBins = 256;       // 8 bits per level
+// The first histogram has bins of two widths, so that a very flat row (most of its tokens within a fraction
+// of the maximum) does not put the whole vocabulary into one bin: keys below 2^20 (t < 2) go by their FINE
+// digit key >> 12 (t in steps of 1/128, slots 0..255), the others by their COARSE digit key >> 16 (steps
+// of 1/8 up to 32; digits 16..255 in slots 256..495).  Every element adds to exactly one slot.
+constexpr int kCoarseShift = 16;
+constexpr int kFineShift = 12;
+constexpr uint32_t kFineLimit = 1u << (kFineShift + 8);                 // keys that have a fine digit
+constexpr uint32_t kCoarseFirst = kFineLimit >> kCoarseShift;           // 16: the first coarse digit with a slot of its own
+constexpr uint32_t kCoarseSlot0 = kBins - kCoarseFirst;                 // slot of coarse digit c: kCoarseSlot0 + c
 constexpr int kLevels = 3;       // levels of the search: 24 key bits
 constexpr float kMassScale = 17592186044416.0f;  // 2^44
 constexpr int kNucBatch = 8;     // vocabulary rows a thread has in flight
@@ -62,9 +73,9 @@ __device__ __forceinline__ float dist_t(float lmax, float l, float inv_tau) { re
 // is 0: whatever saturates carries no mass.)  Monotone in t, exact for the floats it is applied to.
 __device__ __forceinline__ uint32_t order_key(float t) { return (uint32_t)fminf(t * 524288.0f, 16777215.0f); }
 
-// The leading 8 bits of that key, straight from t: order_key(t) >> 16 (scaling by a power of two is exact
-// and floor(floor(x) / 2^16) = floor(x / 2^16)).
-__device__ __forceinline__ uint32_t lead_digit(float t) { return (uint32_t)fminf(t * 8.0f, 255.0f); }
+// The coarse digit straight from t: order_key(t) >> 16 (scaling by a power of two is exact and
+// floor(floor(x) / 2^16) = floor(x / 2^16)).
+__device__ __forceinline__ uint32_t coarse_digit(float t) { return (uint32_t)fminf(t * 8.0f, 255.0f); }
 
 // floor(e^-t * 2^44).  The product is a float with 24 significant bits below 2^45, so it splits
 // exactly into a multiple of 2^20 and a remainder below 2^20: two 32-bit conversions instead of the
@@ -78,14 +89,16 @@ __device__ __forceinline__ unsigned long long mass_of(float t) {
 }
 
 // The leading digit (bits 23..16 of the key of t) of every element of the chunk.
+template <bool FINE>
 __global__ __launch_bounds__(HT) void nucleus_hist_kernel(const float* __restrict__ lt,
                                                           const unsigned long long* __restrict__ keys,
                                                           unsigned long long* __restrict__ ghist, NucGeom g,
                                                           float scale, float inv_tau) {
-  extern __shared__ unsigned long long hist[];  // [KP][kBins]
+  extern __shared__ unsigned long long hist[];  // [KP][bins]: FINE: 256 fine + 240 coarse slots; else 256 coarse digits
   const int pos = blockIdx.x, c = blockIdx.y;
   const int tid = threadIdx.x;
-  for (int x = tid; x < g.KP * kBins; x += HT) hist[x] = 0ull;
+  constexpr int bins = FINE ? 2 * kBins : kBins;
+  for (int x = tid; x < g.KP * bins; x += HT) hist[x] = 0ull;
   __syncthreads();
 
   // thread = four paths (one 16-byte piece of a store row) x every (HT / KQ)-th vocabulary row
@@ -116,21 +129,28 @@ __global__ __launch_bounds__(HT) void nucleus_hist_kernel(const float* __restric
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         if (!live[j]) continue;
-        unsigned long long* hj = hist + (4 * q + j) * kBins;
+        unsigned long long* hj = hist + (4 * q + j) * bins;
 #pragma unroll
         for (int u = 0; u < kNucBatch; ++u) {
           const float xu = j == 0 ? x[u].x : j == 1 ? x[u].y : j == 2 ? x[u].z : x[u].w;
           const float t = dist_t(lmax[j], xu, inv_tau);
           const unsigned long long m = mass_of(t);
-          if (v0 + u * vstep < v_end) atomicAdd(&hj[lead_digit(t)], m);
+          uint32_t slot;
+          if constexpr (FINE) {
+            const uint32_t key = order_key(t);
+            slot = key < kFineLimit ? key >> kFineShift : kCoarseSlot0 + (key >> kCoarseShift);
+          } else {
+            slot = coarse_digit(t);
+          }
+          if (v0 + u * vstep < v_end) atomicAdd(&hj[slot], m);
         }
       }
     }
   }
   __syncthreads();
-  for (int x = tid; x < g.KU * kBins; x += HT) {
+  for (int x = tid; x < g.KU * bins; x += HT) {
     const unsigned long long m = hist[x];
-    if (m != 0ull) atomicAdd(&ghist[((int64_t)pos * g.K + x / kBins) * kBins + (x % kBins)], m);
+    if (m != 0ull) atomicAdd(&ghist[((int64_t)pos * g.K + x / bins) * (2 * kBins) + (x % bins)], m);
   }
 }
 
@@ -183,24 +203,46 @@ __global__ __launch_bounds__(NT) void nucleus_scan_kernel(unsigned long long* __
     cand_n[row] = 0u;
   }
   if (i >= g.KU) return;  // the clean path draws nothing; its bins were never touched
-  unsigned long long* bins = ghist + row * kBins;
-  unsigned long long b[4], total = 0ull;
+  // slots 0..255 (fine digits, or all 256 coarse digits without the fine bins), then slots 256..511
+  unsigned long long* bins = ghist + row * (2 * kBins);
+  unsigned long long b[4], b2[4], first_half = 0ull, second_half = 0ull;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     b[e] = bins[4 * lane + e];
-    total += b[e];
+    first_half += b[e];
     bins[4 * lane + e] = 0ull;
+    b2[e] = 0ull;
+    if (g.fine) {
+      b2[e] = bins[kBins + 4 * lane + e];
+      second_half += b2[e];
+      bins[kBins + 4 * lane + e] = 0ull;
+    }
   }
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) total += __shfl_xor(total, off, 64);
+  for (int off = 32; off >= 1; off >>= 1) {
+    first_half += __shfl_xor(first_half, off, 64);
+    second_half += __shfl_xor(second_half, off, 64);
+  }
+  const unsigned long long total = first_half + second_half;
   // target = ceil(top_p * Z), never above Z and at least 1
   unsigned long long want = (unsigned long long)ceil((double)total * top_p);
   want = want > total ? total : want;
   want = want < 1ull ? 1ull : want;
   unsigned long long lo = 0ull;
-  const int digit = search_bins(b, lo, want);
+  int digit, shift;
+  if (!g.fine) {
+    digit = search_bins(b, lo, want);
+    shift = kCoarseShift;
+  } else if (want <= first_half) {  // the threshold lies within 2 of the row's maximum: a fine digit
+    digit = search_bins(b, lo, want);
+    shift = kFineShift;
+  } else {
+    lo = first_half;
+    digit = search_bins(b2, lo, want) + (int)kCoarseFirst;
+    shift = kCoarseShift;
+  }
   if (lane == 0) {
-    digit0[row] = (uint32_t)digit;
+    digit0[row] = (uint32_t)digit | ((uint32_t)shift << 16);
     below[row] = lo;
     target[row] = want;
   }
@@ -209,6 +251,7 @@ __global__ __launch_bounds__(NT) void nucleus_scan_kernel(unsigned long long* __
 // arg max of l / tau + noise over the tokens whose leading digit lies below the boundary digit, and the
 // tokens of the boundary digit onto the candidate list; thread = (path, group of 4 consecutive vocabulary
 // rows = one block of the noise stream).
+template <bool FINE>
 __global__ __launch_bounds__(NT) void nucleus_draw_kernel(const float* __restrict__ lt,
                                                           const unsigned long long* __restrict__ keys,
                                                           const uint32_t* __restrict__ digit0,
@@ -230,7 +273,7 @@ __global__ __launch_bounds__(NT) void nucleus_draw_kernel(const float* __restric
   unsigned long long best = 0ull;
   if (live) {
     const float lmax = scale * nkey_logit(keys[row]);
-    const uint32_t d0 = digit0[row];
+    const uint32_t d0 = digit0[row] & 0xFFFFu, sh0 = digit0[row] >> 16;  // boundary digit and where it sits in the key
     const RowRng rng = make_row_rng(samp, row, (int64_t)g.P * g.K);
     const uint32_t step = step_now(samp.step, samp.step_dev);
     const float* base = lt + (int64_t)pos * g.V * g.K4 + i;
@@ -256,7 +299,8 @@ __global__ __launch_bounds__(NT) void nucleus_draw_kernel(const float* __restric
       for (int u = 0; u < NB; ++u)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const uint32_t dg = lead_digit(dist_t(lmax, l[u][e], inv_tau));
+          const float t = dist_t(lmax, l[u][e], inv_tau);
+          const uint32_t dg = FINE ? order_key(t) >> sh0 : coarse_digit(t);  // not FINE: sh0 is 16 for every row
           const bool there = whole || vb + u * 4 * nslot + e < v_end;
           in |= (there && dg < d0) ? 1u << (4 * u + e) : 0u;
           cd |= (there && dg == d0) ? 1u << (4 * u + e) : 0u;
@@ -331,7 +375,7 @@ template <typename F>
 __device__ __forceinline__ void for_candidates(bool in_regs, const uint2 (&held)[EPT], bool fits,
                                                const uint2* __restrict__ list, uint32_t n,
                                                const float* __restrict__ col, int V, int K4, float lmax, float inv_tau,
-                                               uint32_t d0, int first, int every, F f) {
+                                               uint32_t d0, uint32_t sh0, int first, int every, F f) {
   if (in_regs) {
 #pragma unroll
     for (int u = 0; u < EPT; ++u)
@@ -344,7 +388,7 @@ __device__ __forceinline__ void for_candidates(bool in_regs, const uint2 (&held)
   } else {
     for (int64_t v = threadIdx.x + (int64_t)first * FT; v < V; v += (int64_t)every * FT) {
       const float l = col[v * K4];
-      if (lead_digit(dist_t(lmax, l, inv_tau)) == d0) f(l, (uint32_t)v);
+      if ((order_key(dist_t(lmax, l, inv_tau)) >> sh0) == d0) f(l, (uint32_t)v);
     }
   }
 }
@@ -385,20 +429,24 @@ __global__ __launch_bounds__(FT) void nucleus_finish_kernel(const float* __restr
     if (!in_regs || (uint32_t)tid + (uint32_t)u * FT >= n) held[u].y = kNoToken;
   const float* col = lt + (int64_t)pos * g.V * g.K4 + i;
   const float lmax = scale * nkey_logit(keys[row]);
-  const uint32_t d0 = digit0[row];
+  const uint32_t d0 = digit0[row] & 0xFFFFu, sh0 = digit0[row] >> 16;
   const unsigned long long want = target[row];
   unsigned long long lo = below[row];
   for (int x = tid; x < (kLevels - 1) * kBins; x += FT) hist[0][x] = 0ull;
   __syncthreads();
-  uint32_t thr = d0 << 16;
+  // the remaining sh0 bits of the key, up to 8 at a time (16 = 8 + 8 below a coarse digit, 12 = 8 + 4 below a fine one)
+  uint32_t thr = d0 << sh0;
+  int shift = (int)sh0;
 #pragma unroll
   for (int level = 1; level < kLevels; ++level) {
-    const int shift = 8 * (kLevels - 1 - level);
+    const int nb = shift > 8 ? 8 : shift;
+    shift -= nb;
+    const uint32_t digit_mask = (1u << nb) - 1u;
     unsigned long long* hl = hist[level - 1];
-    for_candidates(in_regs, held, fits, list, n, col, g.V, g.K4, lmax, inv_tau, d0, 0, 1, [&](float l, uint32_t) {
+    for_candidates(in_regs, held, fits, list, n, col, g.V, g.K4, lmax, inv_tau, d0, sh0, 0, 1, [&](float l, uint32_t) {
       const float t = dist_t(lmax, l, inv_tau);
       const uint32_t key = order_key(t);
-      if ((key >> (shift + 8)) == (thr >> (shift + 8))) atomicAdd(&hl[(key >> shift) & 255u], mass_of(t));
+      if ((key >> (shift + nb)) == (thr >> (shift + nb))) atomicAdd(&hl[(key >> shift) & digit_mask], mass_of(t));
     });
     __syncthreads();
     // every wavefront walks the bins for itself: no second barrier, nothing to hand round
@@ -412,7 +460,7 @@ __global__ __launch_bounds__(FT) void nucleus_finish_kernel(const float* __restr
   const uint32_t step = step_now(samp.step, samp.step_dev);
   unsigned long long best = 0ull;
   const int share = blockIdx.y, shares = gridDim.y;  // shares: a power of two up to EPT
-  for_candidates(in_regs, held, fits, list, n, col, g.V, g.K4, lmax, inv_tau, d0, share, shares, [&](float l, uint32_t v) {
+  for_candidates(in_regs, held, fits, list, n, col, g.V, g.K4, lmax, inv_tau, d0, sh0, share, shares, [&](float l, uint32_t v) {
     if (order_key(dist_t(lmax, l, inv_tau)) > thr) return;
     float gn[4];
     gumbel4(rng, v & ~3u, step, gn);
@@ -438,12 +486,16 @@ __global__ __launch_bounds__(FT) void nucleus_finish_kernel(const float* __restr
 }  // namespace
 
 hipError_t prepare_nucleus() {
-  // the histograms of up to 64 paths need more LDS than the default limit
+  // the histograms of up to 64 paths (32 with the fine bins) need more LDS than the default limit
   hipError_t e;
-  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&nucleus_hist_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, kNucMaxK * kBins * 8)) != hipSuccess)
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&nucleus_hist_kernel<false>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kNucMaxK * kBins * 8)) != hipSuccess ||
+      (e = hipFuncSetAttribute(reinterpret_cast<const void*>(&nucleus_hist_kernel<true>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kNucFineMaxKP * 2 * kBins * 8)) != hipSuccess ||
+      (e = hipFuncSetAttribute(reinterpret_cast<const void*>(&nucleus_draw_kernel<false>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, NT * 8 + kNucMaxK * kNucStage * 8)) != hipSuccess)
     return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&nucleus_draw_kernel),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&nucleus_draw_kernel<true>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, NT * 8 + kNucMaxK * kNucStage * 8);
 }
 
@@ -459,10 +511,19 @@ hipError_t launch_nucleus(const float* lt, const unsigned long long* keys, const
   const dim3 hgrid((unsigned)g.P, (unsigned)NH), hblock(HT);
   const int64_t rows = (int64_t)g.P * g.K;
   const dim3 sgrid((unsigned)((rows + NT / 64 - 1) / (NT / 64)));
-  nucleus_hist_kernel<<<hgrid, hblock, (size_t)g.KP * kBins * 8, stream>>>(lt, keys, nb.hist, g, scale, inv_tau);
+  if (g.fine && g.KP > kNucFineMaxKP) return hipErrorInvalidValue;
+  if (g.fine)
+    nucleus_hist_kernel<true><<<hgrid, hblock, (size_t)g.KP * 2 * kBins * 8, stream>>>(lt, keys, nb.hist, g, scale, inv_tau);
+  else
+    nucleus_hist_kernel<false><<<hgrid, hblock, (size_t)g.KP * kBins * 8, stream>>>(lt, keys, nb.hist, g, scale, inv_tau);
   nucleus_scan_kernel<<<sgrid, block, 0, stream>>>(nb.hist, nb.digit0, nb.below, nb.target, nb.cand_n, nb.keys_s, g, top_p);
-  nucleus_draw_kernel<<<grid, block, (size_t)NT * 8 + (size_t)g.KP * kNucStage * 8, stream>>>(
-      lt, keys, nb.digit0, nb.keys_s, nb.cand, nb.cand_n, g, samp, scale, inv_tau);
+  const size_t draw_lds = (size_t)NT * 8 + (size_t)g.KP * kNucStage * 8;
+  if (g.fine)
+    nucleus_draw_kernel<true><<<grid, block, draw_lds, stream>>>(lt, keys, nb.digit0, nb.keys_s, nb.cand, nb.cand_n, g, samp,
+                                                                scale, inv_tau);
+  else
+    nucleus_draw_kernel<false><<<grid, block, draw_lds, stream>>>(lt, keys, nb.digit0, nb.keys_s, nb.cand, nb.cand_n, g, samp,
+                                                                 scale, inv_tau);
   unsigned shares = 1;  // workgroups per row of the last pass: as many as it takes to use the chip, at most EPT
   while (shares < (unsigned)EPT && rows * shares < 512) shares *= 2;
   nucleus_finish_kernel<<<dim3((unsigned)rows, shares), dim3(FT), 0, stream>>>(lt, keys, nb.digit0, nb.below, nb.target, nb.cand,

@@ -91,6 +91,9 @@ def _run(runner, wl, W, h, seeds, draft, tau, top_p, step=0, rule=orc.RULE_ANY, 
     (128, 1500, 1, 4, 64, "bf16", 2.0, 0.99),    # the most paths the variant takes
     (256, 3000, 1, 8, 16, "bf16", 50.0, 0.5),    # nearly uniform: distances of ~1e-5 in l / tau against the 2^-19 search key
     (256, 3000, 2, 4, 16, "bf16", 0.05, 0.9),    # very sharp: most tokens beyond the range of the key (no mass)
+    (256, 3000, 1, 8, 16, "bf16", 2.5, 0.9),     # from temperature 2 on: fine bins next to the maximum; a flat row, threshold in them
+    (256, 3000, 2, 4, 8, "bf16", 2.0, 0.15),     # the same with a small nucleus
+    (128, 1500, 1, 4, 40, "bf16", 3.0, 0.7),     # 40 paths: too many for the fine bins (coarse ones only)
 ])
 def test_nucleus_tokens_flat_distributions(runner, d, V, B, T, K, dtype, tau, top_p):
     wl = wk.Workload("nuc", d=d, V=V, dtype=dtype, B=B, T=T, K=K, p=0.2, bonus=True, data_seed=d + V + K)
@@ -110,11 +113,11 @@ def test_nucleus_tokens_peaked_distributions(runner):
     h, planted = wk.make_planted_hidden(wl, W, alpha=9.0)
     seeds = wk.make_seeds(wl, base_seed=3)
     draft = planted.copy()
-    for top_p in (0.5, 0.9):
-        ref, res, rows, same = _run(runner, wl, W, h, seeds, draft, 1.0, top_p)
-        sizes = [int(orc.nucleus(ref["logits"][r], top_p)[0].sum()) for r in range(0, rows, 7)]
-        print(f"[nucleus peaked top_p={top_p}] rows={rows} equal={same} nucleus sizes (sample)={sizes[:8]}", flush=True)
-        assert same >= 0.9 * rows and max(sizes) < wl.V // 4
+    for top_p, tau in ((0.5, 1.0), (0.9, 1.0), (0.9, 2.5), (0.999, 2.0)):   # temperature >= 2: fine bins, thresholds beyond them
+        ref, res, rows, same = _run(runner, wl, W, h, seeds, draft, tau, top_p)
+        sizes = [int(orc.nucleus(ref["logits"][r] / tau, top_p)[0].sum()) for r in range(0, rows, 7)]
+        print(f"[nucleus peaked top_p={top_p} tau={tau}] rows={rows} equal={same} nucleus sizes (sample)={sizes[:8]}", flush=True)
+        assert same >= 0.9 * rows and (tau > 1.0 or max(sizes) < wl.V // 4)
 
 
 @pytest.mark.parametrize("B,T,K", [(1, 8, 16), (3, 6, 16)])     # W-streaming kernel / 256 x 256 kernel in store mode
