@@ -39,7 +39,7 @@ namespace dm {
 namespace {
 
 constexpr int NT = 256;          // threads per workgroup (scan, draw)
-constexpr int HT = 1024;         // threads per workgroup of the histogram passes
+constexpr int HT = 1024;         // threads per workgroup of the histogram pass
 constexpr int kHistChunk = 4096; // vocabulary rows per histogram workgroup: every workgroup ends with up to
                                  // 256 atomic adds to memory per path, so few large ones are cheaper
 constexpr int kBins = 256;       // 8 bits per level
@@ -88,7 +88,7 @@ __device__ __forceinline__ unsigned long long mass_of(float t) {
   return ((unsigned long long)(hi >> 12) << 32) | (unsigned long long)((hi << 20) | lo);
 }
 
-// The leading digit (bits 23..16 of the key of t) of every element of the chunk.
+// The mass of every element of the chunk, by its leading digit (coarse, or FINE: of either width).
 template <bool FINE>
 __global__ __launch_bounds__(HT) void nucleus_hist_kernel(const float* __restrict__ lt,
                                                           const unsigned long long* __restrict__ keys,
