@@ -32,8 +32,9 @@ __device__ __forceinline__ uint32_t step_now(uint32_t step, const uint32_t* step
 }
 
 // Eq. (1)+(2) without the scale: masked rows a = keep ? h : 0 into the workspace, and the
-// per-row argmax keys reset to 0.  swizzled = layout of the MFMA kernel's B-fragments;
-// otherwise plain [M_pad, d_pad].  is_bf16 selects the element type of h and the workspace.
+// per-row argmax keys reset to 0.  layout: plain [M_pad, d_pad], or the order of the B-fragments of the
+// MFMA kernel that will read them (32 rows x 16 k for the W-streaming kernel, 16 rows x 32 k for the
+// 256 x 256 kernel).  is_bf16 selects the element type of h and the workspace.
 // seeds_dev (optional): DEVICE [B], receives the seeds (for the sampling epilogues of the same call).
 // Per-call state of the later kernels of the same call is put back to zero here as well, so that a
 // call never depends on an earlier one having run to its end: the election counter of the fused
@@ -43,8 +44,9 @@ struct CallReset {
   unsigned long long* zero64 = nullptr;   // n64 words, or null
   int64_t n64 = 0;
 };
+constexpr int kRowsPlain = 0, kRowsFrag32 = 1, kRowsFrag16 = 2;
 hipError_t launch_mask_rows(const void* h, void* a_ws, unsigned long long* keys, const uint64_t* seeds_host,
-                            const RowGeom& g, bool is_bf16, bool swizzled, uint64_t* seeds_dev,
+                            const RowGeom& g, bool is_bf16, int layout, uint64_t* seeds_dev,
                             const CallReset& reset, hipStream_t stream);
 
 // Eq. (1) only, bit-packed [M, ceil(d/32)].

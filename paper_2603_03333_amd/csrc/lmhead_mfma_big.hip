@@ -9,7 +9,9 @@
 //
 // Workgroup = 768 threads = 12 wavefronts, three per SIMD:
 //   * 8 consumers: wavefront (wv, wm) owns vocabulary rows [64 wv, +64) x masked rows
-//     [128 wm, +128) of the tile: 2 x 4 accumulator tiles (128 VGPRs);
+//     [128 wm, +128) of the tile: 4 x 8 accumulator tiles of v_mfma_f32_16x16x32_bf16 (128 VGPRs; the
+//     same flops and the same LDS fragment traffic as 2 x 4 tiles of the 32x32x16 instruction, which this
+//     kernel used first, at less power: batched 6.51 -> 6.22 ms on one box);
 //   * 4 producers: global -> LDS copies by LDS-DMA, so that a full memory queue stalls a
 //     producer and not the MFMA stream.
 // k advances in slabs of 64.  LDS holds a ring of three W slabs (two in flight: they come from
@@ -18,8 +20,8 @@
 // barrier per slab: "slab q has landed for everybody, nobody reads slab q-1 any more".  The four
 // wavefronts that share a masked row merge their arg max through the 64-bit key in memory.
 // W rows are stored in LDS with their 16-byte pieces XOR-swizzled by the row number so that
-// the MFMA fragment reads (32 rows, same piece) are bank-conflict free; masked rows arrive in
-// fragment order from the mask kernel.
+// the MFMA fragment reads (16 rows each of 4 consecutive pieces) are bank-conflict free; masked rows
+// arrive in fragment order from the mask kernel.
 //
 // Tile order.  Workgroups are persistent; in one "round" the grid covers a block of
 // BVc x BMc tiles (BMc <= 16 row tiles wide).  Workgroup ids are dealt round-robin to the 8
@@ -42,12 +44,12 @@ constexpr int kNoiseMinChunks = 16;  // tiles of fewer slabs draw their noise in
 template <int BK>
 struct Cfg {
   static constexpr int PR = BK / 8;                    // 16-byte pieces per W row per slab
-  static constexpr int KSTEPS = BK / 16;               // MFMA k-steps per slab
+  static constexpr int KSTEPS = BK / 32;               // MFMA k-steps (of 32) per slab
   static constexpr int ROW_BYTES = BK * 2;
   static constexpr int W_SLAB = BN * ROW_BYTES;
   static constexpr int A_SLAB = BM * ROW_BYTES;
   static constexpr int W_INSTR = (64 * ROW_BYTES) / 1024;  // W copy instructions per producer per slab
-  static constexpr int A_INSTR = KSTEPS * 8 / 4;           // masked-row fragments per producer per slab
+  static constexpr int A_INSTR = KSTEPS * 16 / 4;          // masked-row fragments (16 rows x 32 k) per producer per slab
   // W slabs come from HBM (long latency), masked-row slabs from L2: W gets the deeper ring.
   // 3 x 32 KB + 2 x 32 KB = all 160 KB of the LDS at BK = 64.
   static constexpr int NSW = 3, NSA = 2;
@@ -189,11 +191,11 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
     auto issue_a = [&](int q) {
       const int c = advance(ca);
       unsigned char* stage = lds + C::A_BASE + (q % C::NSA) * C::A_SLAB;
-      const char* asrc = Ab + ((int64_t)(c * C::KSTEPS) * mt_total + ca.tm * 8) * 1024;
+      const char* asrc = Ab + ((int64_t)(c * C::KSTEPS) * mt_total + ca.tm * 16) * 1024;
 #pragma unroll
       for (int x = 0; x < C::A_INSTR; ++x) {
-        const int f = p + 4 * x;  // fragment index inside the slab: f = s * 8 + mt
-        const int s = f >> 3, mt = f & 7;
+        const int f = p + 4 * x;  // fragment index inside the slab: f = s * 16 + mt
+        const int s = f >> 4, mt = f & 15;
         dma_copy16(asrc + ((int64_t)s * mt_total + mt) * 1024, aoff, stage + f * 1024);
       }
     };
@@ -201,10 +203,10 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
     // the MFMA wavefronts are working on: 256 "items" of 64 lanes x 4 vocabulary rows (one Philox block
     // per lane) per tile, spread over the tile's slabs and left in memory in the order the MFMA
     // wavefronts read them in their epilogue.  (Drawn in the epilogue, the noise also costs the main
-    // loop registers it does not have.)  Copy wavefront p makes the 64 items with row group rq = p:
-    // item k = ((wm * 4 + mt) * 8 + wv * 2 + vt) of MFMA wavefront (wv, wm), masked-row tile mt,
-    // vocabulary tile vt, stored at float4 index (4 k + rq) * 64 + lane.  Eight consecutive items share
-    // their 32 masked rows, so the rows' streams are set up once per eight.  Items of a tile are made
+    // loop registers it does not have.)  Copy wavefront p makes the 64 items with vocabulary tile w = p:
+    // item k = ((wm * 8 + a) * 4 + wv) of MFMA wavefront (wv, wm), masked-row tile a, stored at float4
+    // index (4 k + w) * 64 + lane.  Four consecutive items share their 16 masked rows, so the rows'
+    // streams are set up once per four.  Items of a tile are made
     // after the barrier of its first slab (the epilogue of the tile before has been read by then) and
     // are complete, by a wait for ALL own memory operations, before the barrier of its last slab.
     constexpr bool prod_noise = SAMPLE == 2;
@@ -214,9 +216,9 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
     RowRng nrng{0u, 0u, 0u, 0u, false};
     f32x4* const noise_wg = reinterpret_cast<f32x4*>(samp.noise) + (int64_t)blockIdx.x * (BN * BM / 4);
     auto noise_item = [&](int k, int tv, int tm) {
-      const int rs = k >> 3, wv_k = (k >> 1) & 3, vt = k & 1;
-      if ((k & 7) == 0) nrng = make_row_rng(samp, (int64_t)tm * BM + (rs >> 2) * 128 + (rs & 3) * 32 + (lane & 31), M);
-      const int v4 = v_lo + tv * BN + 64 * wv_k + 32 * vt + 8 * p + 4 * (lane >> 5);
+      const int rs = k >> 2, wv_k = k & 3;  // rs = wm * 8 + a
+      if ((k & 3) == 0) nrng = make_row_rng(samp, (int64_t)tm * BM + (rs >> 3) * 128 + (rs & 7) * 16 + (lane & 15), M);
+      const int v4 = v_lo + tv * BN + 64 * wv_k + 16 * p + 4 * (lane >> 4);
       float g[4] = {0.f, 0.f, 0.f, 0.f};
       if (nrng.on) gumbel4(nrng, (uint32_t)v4, step_now(samp.step, samp.step_dev), g);
       // written once, read once, by this compute unit: streaming, so that it does not displace the W and
@@ -257,41 +259,50 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
 
   // -------------------------------------------------------------------- consumer
   const int wv = wave & 3, wm = wave >> 2;
-  const int i32 = lane & 31;
-  const int hb = lane >> 5;
-  // W fragment of k-step s, half hb: piece (2 s + hb) ^ swz = (2 s) ^ (hb ^ swz) of the lane's row.  Every
-  // other term of the address is a multiple of the row size, so the k-step is an XOR on ONE lane
-  // offset instead of one precomputed register per k-step.
+  const int i16 = lane & 15;  // row inside a 16-row MFMA tile (vocabulary row of W, masked row of the B operand)
+  const int kq = lane >> 4;   // which 8 of the 32 k of an MFMA step; in the accumulators: which 4 of the 16 vocabulary rows
+  // W fragment of vocabulary tile w (16 rows), k-step s (32 k): piece (4 s + kq) ^ swz = (4 s) ^ (kq ^ swz) of the
+  // lane's row (swz depends on i16 only: tiles start at multiples of 16 rows).  Every other term of the address
+  // is a multiple of the row size, so the k-step is an XOR on ONE lane offset instead of one precomputed
+  // register per k-step.
   static_assert(C::ROW_BYTES == 16 * C::PR && C::W_SLAB % C::ROW_BYTES == 0, "piece index = low bits of the address");
-  const uint32_t wlane = (uint32_t)(wv * (64 * C::ROW_BYTES) + i32 * C::ROW_BYTES +
-                                    16 * (hb ^ ((i32 >> C::SWZ_SHIFT) & (C::PR - 1))));
+  static_assert(C::PR >= 4, "a k-step of 32 spans four 16-byte pieces");
+  const uint32_t wlane = (uint32_t)(wv * (64 * C::ROW_BYTES) + i16 * C::ROW_BYTES +
+                                    16 * (kq ^ ((i16 >> C::SWZ_SHIFT) & (C::PR - 1))));
 
-  f32x16 acc[4][2];
+  // acc[a][w][r]: masked row 16 a + i16 of the wavefront's 128, vocabulary row 16 w + 4 kq + r of its 64
+  f32x4 acc[8][4];
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt)
+  for (int a = 0; a < 8; ++a)
 #pragma unroll
-    for (int vt = 0; vt < 2; ++vt)
+    for (int w = 0; w < 4; ++w)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[mt][vt][r] = 0.f;
+      for (int r = 0; r < 4; ++r) acc[a][w][r] = 0.f;
 
   int it_c = -1, tv_c = 0, tm_c = 0;
   for (int q = 0; q < total; ++q) {
     DM_BARRIER();
     const uint32_t wq = (uint32_t)((q % C::NSW) * C::W_SLAB) + wlane;
-    const unsigned char* abase = lds + C::A_BASE + (q % C::NSA) * C::A_SLAB + (4 * wm) * 1024 + lane * 16;
+    const unsigned char* abase = lds + C::A_BASE + (q % C::NSA) * C::A_SLAB + (8 * wm) * 1024 + lane * 16;
 #pragma unroll
     for (int s = 0; s < C::KSTEPS; ++s) {
-      bf16x8 wf[2], af[4];
+      bf16x8 wf[4];
 #pragma unroll
-      for (int vt = 0; vt < 2; ++vt)
-        wf[vt] = *reinterpret_cast<const bf16x8*>(lds + (wq ^ (uint32_t)(32 * s)) + vt * (32 * C::ROW_BYTES));
+      for (int w = 0; w < 4; ++w)
+        wf[w] = *reinterpret_cast<const bf16x8*>(lds + (wq ^ (uint32_t)(64 * s)) + w * (16 * C::ROW_BYTES));
+      // The fragment of masked-row tile a + 1 is requested before the four MFMAs of tile a.  Left to itself the
+      // compiler requests each fragment right before its use and waits for it on the spot (measured: 6.65 ms at
+      // the batched configuration against 5.93 ms with the request pinned ahead; two tiles ahead: 5.99 ms).
+      bf16x8 af = *reinterpret_cast<const bf16x8*>(abase + (s * 16) * 1024);
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) af[mt] = *reinterpret_cast<const bf16x8*>(abase + (s * 8 + mt) * 1024);
+      for (int a = 0; a < 8; ++a) {
+        bf16x8 af_next = af;
+        if (a < 7) af_next = *reinterpret_cast<const bf16x8*>(abase + (s * 16 + a + 1) * 1024);
+        __builtin_amdgcn_sched_barrier(0);  // keeps the request above ahead of the MFMAs below
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
-          acc[mt][vt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[vt], af[mt], acc[mt][vt], 0, 0, 0);
+        for (int w = 0; w < 4; ++w) acc[a][w] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[w], af, acc[a][w], 0, 0, 0);
+        af = af_next;
+      }
     }
     asm volatile("" ::: "memory");
 
@@ -303,20 +314,21 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
     } while (!tile_of(walk, pos, it_c, tv_c, tm_c) && it_c < nit);
     if (it_c >= nit) tv_c = tm_c = 0;  // cannot happen (slabs are counted from the same walk); stays in bounds
     const int v0 = v_lo + tv_c * BN;
-    // accumulator (mt, vt, r): v = v0 + 64 wv + 32 vt + 8 (r/4) + 4 hb + r%4,  m = 256 tm + 128 wm + 32 mt + lane%32
+    const int64_t m_first = (int64_t)tm_c * BM + wm * 128;  // first masked row of this wavefront
+    // accumulator (a, w, r): v = v0 + 64 wv + 16 w + 4 kq + r,  m = m_first + 16 a + lane % 16
     if (DUMP) {
       const int nv = dv1 - dv0;
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) {
-        const int64_t m = (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32;
+      for (int a = 0; a < 8; ++a) {
+        const int64_t m = m_first + a * 16 + i16;
         const float sc = (store.clean_last && m % store.K == store.K - 1) ? 1.0f : scale;  // clean path: no 1/(1-p)
 #pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
+        for (int w = 0; w < 4; ++w)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int v = v0 + 64 * wv + 32 * vt + 8 * (r >> 2) + 4 * hb + (r & 3);
-            if (m < M && v >= dv0 && v < dv1 && v < v_hi) logits[m * nv + (v - dv0)] = sc * acc[mt][vt][r];
-            acc[mt][vt][r] = 0.f;
+          for (int r = 0; r < 4; ++r) {
+            const int v = v0 + 64 * wv + 16 * w + 4 * kq + r;
+            if (m < M && v >= dv0 && v < dv1 && v < v_hi) logits[m * nv + (v - dv0)] = sc * acc[a][w][r];
+            acc[a][w][r] = 0.f;
           }
       }
       continue;
@@ -325,112 +337,107 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
     if (MODE == 2) {
       // row m = path m % K of position m / K; stores use a uniform base (first position of this
       // wavefront's 128 rows) plus one 32-bit lane offset
-      const int64_t m_first = (int64_t)tm_c * BM + wm * 128;
       const int64_t pos0 = m_first / store.K;
       char* lt_base = reinterpret_cast<char*>(store.lt + pos0 * store.V * (int64_t)store.K4);
-      uint32_t lt_off[4];
-      bool lt_ok[4];
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) {
-        const int64_t m = m_first + mt * 32 + i32;
+      for (int a = 0; a < 8; ++a) {
+        const int64_t m = m_first + a * 16 + i16;
         const int64_t pos = m / store.K;
-        lt_ok[mt] = m < M;
-        lt_off[mt] = (uint32_t)(((pos - pos0) * store.V * store.K4 + (m - pos * store.K) + 4 * hb * store.K4) * 4);
-      }
+        const uint32_t lt_off = (uint32_t)(((pos - pos0) * store.V * store.K4 + (m - pos * store.K) + 4 * kq * store.K4) * 4);
+        if (m < M) {
 #pragma unroll
-      for (int vt = 0; vt < 2; ++vt)
+          for (int w = 0; w < 4; ++w)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int vu = v0 + 64 * wv + 32 * vt + 8 * (r >> 2) + (r & 3);  // + 4 * hb per lane
-          char* dst = lt_base + (int64_t)vu * store.K4 * 4;
-          const bool v_ok = vu + 4 * hb < v_hi;
-#pragma unroll
-          for (int mt = 0; mt < 4; ++mt)
-            if (lt_ok[mt] && v_ok) *reinterpret_cast<float*>(dst + lt_off[mt]) = scale * acc[mt][vt][r];
+            for (int r = 0; r < 4; ++r) {
+              const int vu = v0 + 64 * wv + 16 * w + r;  // + 4 * kq per lane; the base below is uniform over the wavefront
+              char* dst = lt_base + (int64_t)vu * store.K4 * 4;
+              if (vu + 4 * kq < v_hi) *reinterpret_cast<float*>(dst + lt_off) = scale * acc[a][w][r];
+            }
         }
+      }
     }
 
     if (SAMPLE == 0 && v0 + BN <= v_hi) {
       // Plain arg max over a full tile (all but the last vocabulary tile): no bounds checks, the winner is
-      // tracked as a 5-bit code and turned into its row once, -0 becomes +0 once (for the comparisons the
+      // tracked as a 4-bit code and turned into its row once, -0 becomes +0 once (for the comparisons the
       // two are equal; the packed key orders them, and ties must go to the smaller index in every tile).
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) {
-        float best = acc[mt][0][0];
+      for (int a = 0; a < 8; ++a) {
+        float best = acc[a][0][0];
         int code = 0;
-        acc[mt][0][0] = 0.f;
+        acc[a][0][0] = 0.f;
 #pragma unroll
-        for (int c = 1; c < 32; ++c) {  // ascending v for this lane: strict > keeps the smallest index
-          const float val = acc[mt][c >> 4][c & 15];
+        for (int c = 1; c < 16; ++c) {  // ascending v for this lane: strict > keeps the smallest index
+          const float val = acc[a][c >> 2][c & 3];
           const bool gt = val > best;
           best = gt ? val : best;
           code = gt ? c : code;
-          acc[mt][c >> 4][c & 15] = 0.f;
+          acc[a][c >> 2][c & 3] = 0.f;
         }
-        const int v = v0 + 64 * wv + 4 * hb + 32 * (code >> 4) + 8 * ((code & 15) >> 2) + (code & 3);
+        const int v = v0 + 64 * wv + 4 * kq + 16 * (code >> 2) + (code & 3);
         unsigned long long key = pack_key(best + 0.0f, (uint32_t)v);
-        const unsigned long long other = __shfl_xor(key, 32, 64);
+        unsigned long long other = __shfl_xor(key, 16, 64);
         key = other > key ? other : key;
-        const int64_t mrow = (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32;
-        if (hb == 0 && mrow < M) atomicMax(&keys[mrow], key);
+        other = __shfl_xor(key, 32, 64);
+        key = other > key ? other : key;
+        const int64_t mrow = m_first + a * 16 + i16;
+        if (kq == 0 && mrow < M) atomicMax(&keys[mrow], key);
       }
       continue;
     }
 
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
+    for (int a = 0; a < 8; ++a) {
       float best = -INFINITY;
       uint32_t bv = 0xFFFFFFFFu;
+      const int64_t mrow = m_first + a * 16 + i16;
       RowRng rng{0u, 0u, 0u, 0u, false};
-      if (SAMPLE == 1) rng = make_row_rng(samp, (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32, M);
-      const bool noisy = SAMPLE == 1 ? rng.on
-                                     : (SAMPLE == 2 && row_draws(samp, (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32, M));
-      // SAMPLE == 2: noise made by the copy wavefronts during the tile, items (wm, mt, wv, vt = 0) onwards
+      if (SAMPLE == 1) rng = make_row_rng(samp, mrow, M);
+      const bool noisy = SAMPLE == 1 ? rng.on : (SAMPLE == 2 && row_draws(samp, mrow, M));
+      // SAMPLE == 2: noise made by the copy wavefronts during the tile, items (wm, a, wv), vocabulary tile 0 onwards
       // (a uniform base and one lane offset, opaque so that the 32 addresses are not kept across the tile)
       const char* nz = reinterpret_cast<const char*>(samp.noise) + (int64_t)blockIdx.x * (BN * BM * 4) +
-                       (((wm * 4 + mt) * 8 + wv * 2) * 4) * 1024;
+                       ((((wm * 8 + a) * 4 + wv) * 4) * 1024);
       uint32_t nlane = (uint32_t)lane * 16u;
       if (SAMPLE == 2) asm volatile("" : "+v"(nlane));
       // First vocabulary row of this lane in the tile.  When sampling it is made opaque to the compiler
       // for every masked-row tile: otherwise whatever depends on the vocabulary row only (noise
-      // counters, the first Philox round) is shared between the four tiles, kept in registers across
+      // counters, the first Philox round) is shared between the tiles, kept in registers across
       // the main loop, and spilled there.
-      int vb = v0 + 64 * wv + 4 * hb;
+      int vb = v0 + 64 * wv + 4 * kq;
       if (SAMPLE == 1) asm volatile("" : "+v"(vb));
 #pragma unroll
-      for (int vt = 0; vt < 2; ++vt)
-#pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-          float g[4] = {0.f, 0.f, 0.f, 0.f};
-          if (SAMPLE == 2) {
-            const f32x4 g4 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(nz + (vt * 4 + rq) * 1024 + nlane));
-            g[0] = g4.x;
-            g[1] = g4.y;
-            g[2] = g4.z;
-            g[3] = g4.w;
-          } else if (noisy) {
-            gumbel4(rng, (uint32_t)(vb + 32 * vt + 8 * rq), step_now(samp.step, samp.step_dev), g);
-          }
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {  // ascending v for this lane: strict > keeps the smallest index
-            const int r = 4 * rq + e;
-            const int v = vb + 32 * vt + 8 * rq + e;
-            const float val = noisy ? fmaf(acc[mt][vt][r], samp.zscale, g[e]) : acc[mt][vt][r] + 0.0f;
-            if (v < v_hi && (bv == 0xFFFFFFFFu || val > best)) {
-              best = val;
-              bv = (uint32_t)v;
-            }
-            acc[mt][vt][r] = 0.f;
-          }
-          // the noise of one group of four rows is not computed ahead of the groups before it
-          if (SAMPLE == 1) __builtin_amdgcn_sched_barrier(0);
+      for (int w = 0; w < 4; ++w) {
+        float g[4] = {0.f, 0.f, 0.f, 0.f};
+        if (SAMPLE == 2) {
+          const f32x4 g4 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(nz + w * 1024 + nlane));
+          g[0] = g4.x;
+          g[1] = g4.y;
+          g[2] = g4.z;
+          g[3] = g4.w;
+        } else if (noisy) {
+          gumbel4(rng, (uint32_t)(vb + 16 * w), step_now(samp.step, samp.step_dev), g);
         }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {  // ascending v for this lane: strict > keeps the smallest index
+          const int v = vb + 16 * w + e;
+          const float val = noisy ? fmaf(acc[a][w][e], samp.zscale, g[e]) : acc[a][w][e] + 0.0f;
+          if (v < v_hi && (bv == 0xFFFFFFFFu || val > best)) {
+            best = val;
+            bv = (uint32_t)v;
+          }
+          acc[a][w][e] = 0.f;
+        }
+        // the noise of one group of four rows is not computed ahead of the groups before it
+        if (SAMPLE == 1) __builtin_amdgcn_sched_barrier(0);
+      }
       unsigned long long key = (bv == 0xFFFFFFFFu) ? 0ull : pack_key(best, bv);
-      const unsigned long long other = __shfl_xor(key, 32, 64);
+      unsigned long long other = __shfl_xor(key, 16, 64);
+      key = other > key ? other : key;
+      other = __shfl_xor(key, 32, 64);
       key = other > key ? other : key;
       // no LDS left for a reduction over the four wavefronts that share a masked row: each merges its own
-      const int64_t mrow = (int64_t)tm_c * BM + wm * 128 + mt * 32 + i32;
-      if (hb == 0 && mrow < M && key != 0ull) atomicMax(&keys[mrow], key);
+      if (kq == 0 && mrow < M && key != 0ull) atomicMax(&keys[mrow], key);
     }
   }
 }
@@ -482,7 +489,7 @@ hipError_t run_big(const void* W, const void* a_ws, unsigned long long* keys, co
   if (G >= 8) G -= G % 8;
   const TileWalk walk = make_walk(NV, NMB, G);
   const dim3 grid((unsigned)G), block(THREADS);
-  const int mt_total = (int)(g.M_pad >> 5);
+  const int mt_total = (int)(g.M_pad >> 4);  // masked-row tiles of 16
 #define DM_LAUNCH(MODE, SAMPLE)                                                                                    \
   launch_at(lmhead_mfma_big_kernel<BK, MODE, SAMPLE>, grid, block, (size_t)Cfg<BK>::LDS_BYTES, at,                  \
             static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo, v_hi, \

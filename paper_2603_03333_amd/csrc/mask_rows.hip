@@ -25,7 +25,7 @@ struct __attribute__((aligned(16))) Vec8<uint16_t> {
 };
 
 // T = float or uint16_t (bfloat16 bit pattern; selecting between a value and +0 needs no arithmetic)
-template <typename T, bool SWIZZLED>
+template <typename T, int LAYOUT>
 __global__ __launch_bounds__(256) void mask_rows_kernel(const T* __restrict__ h, T* __restrict__ a_ws,
                                                         unsigned long long* __restrict__ keys, SeedPack seeds,
                                                         RowGeom g, int64_t row0, int64_t nrows, int b0,
@@ -68,11 +68,16 @@ __global__ __launch_bounds__(256) void mask_rows_kernel(const T* __restrict__ h,
   }
 
   int64_t dst;
-  if (SWIZZLED) {
+  if (LAYOUT == kRowsFrag32) {
     // B-operand fragments of v_mfma_f32_32x32x16_bf16: fragment (k-step ks, row tile mt) is
     // 64 lanes x 8 elements; lane = (row % 32) + 32 * ((k % 16) / 8), element = k % 8.
     const int64_t mt_total = g.M_pad >> 5;
     dst = ((((int64_t)(o >> 1) * mt_total + (r >> 5)) * 64) + (r & 31) + 32 * (o & 1)) * 8;
+  } else if (LAYOUT == kRowsFrag16) {
+    // B-operand fragments of v_mfma_f32_16x16x32_bf16: fragment (k-step ks of 32, row tile mt of 16) is
+    // 64 lanes x 8 elements; lane = (row % 16) + 16 * ((k % 32) / 8), element = k % 8.
+    const int64_t mt_total = g.M_pad >> 4;
+    dst = ((((int64_t)(o >> 2) * mt_total + (r >> 4)) * 64) + (r & 15) + 16 * (o & 3)) * 8;
   } else {
     dst = r * g.d_pad + 8 * (int64_t)o;
   }
@@ -108,7 +113,7 @@ __global__ __launch_bounds__(256) void mask_bits_kernel(uint32_t* __restrict__ b
   bits[r * nwords + w] = word;
 }
 
-template <typename T, bool SW>
+template <typename T, int SW>
 hipError_t run_mask_rows(const void* h, void* a_ws, unsigned long long* keys, const uint64_t* seeds_host,
                          const RowGeom& g, uint64_t* seeds_dev, const CallReset& reset, hipStream_t stream) {
   const int64_t TK = (int64_t)g.T * g.K;
@@ -135,13 +140,20 @@ hipError_t run_mask_rows(const void* h, void* a_ws, unsigned long long* keys, co
 }  // namespace
 
 hipError_t launch_mask_rows(const void* h, void* a_ws, unsigned long long* keys, const uint64_t* seeds_host,
-                            const RowGeom& g, bool is_bf16, bool swizzled, uint64_t* seeds_dev,
+                            const RowGeom& g, bool is_bf16, int layout, uint64_t* seeds_dev,
                             const CallReset& reset, hipStream_t stream) {
-  if (is_bf16)
-    return swizzled ? run_mask_rows<uint16_t, true>(h, a_ws, keys, seeds_host, g, seeds_dev, reset, stream)
-                    : run_mask_rows<uint16_t, false>(h, a_ws, keys, seeds_host, g, seeds_dev, reset, stream);
-  if (swizzled) return hipErrorInvalidValue;
-  return run_mask_rows<float, false>(h, a_ws, keys, seeds_host, g, seeds_dev, reset, stream);
+  if (is_bf16) {
+    switch (layout) {
+      case kRowsPlain: return run_mask_rows<uint16_t, kRowsPlain>(h, a_ws, keys, seeds_host, g, seeds_dev, reset, stream);
+      case kRowsFrag32: return run_mask_rows<uint16_t, kRowsFrag32>(h, a_ws, keys, seeds_host, g, seeds_dev, reset, stream);
+      case kRowsFrag16:
+        if (g.d_pad % 32 != 0 || g.M_pad % 16 != 0) return hipErrorInvalidValue;
+        return run_mask_rows<uint16_t, kRowsFrag16>(h, a_ws, keys, seeds_host, g, seeds_dev, reset, stream);
+      default: return hipErrorInvalidValue;
+    }
+  }
+  if (layout != kRowsPlain) return hipErrorInvalidValue;
+  return run_mask_rows<float, kRowsPlain>(h, a_ws, keys, seeds_host, g, seeds_dev, reset, stream);
 }
 
 hipError_t launch_mask_bits(uint32_t* bits, const uint64_t* seeds_host, const RowGeom& g, hipStream_t stream) {
