@@ -284,23 +284,33 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
     DM_BARRIER();
     const uint32_t wq = (uint32_t)((q % C::NSW) * C::W_SLAB) + wlane;
     const unsigned char* abase = lds + C::A_BASE + (q % C::NSA) * C::A_SLAB + (8 * wm) * 1024 + lane * 16;
+    // Fragments are requested ahead of their use by hand: that of masked-row tile a + 1 before the four MFMAs of
+    // tile a, and inside a slab the W fragments of the next k-step one by one behind the last MFMA that reads the
+    // register they go to.  Left to itself the compiler requests each fragment right before its use and waits
+    // for it on the spot (measured: 6.65 ms at the batched configuration against 5.93 ms with the first kind of
+    // request pinned ahead and 5.90 ms with both; two tiles ahead: 5.99 ms; a slab's first requests in the order
+    // of their first use: no change, the compiler waits for all of them before the first MFMA either way).
+    bf16x8 wf[4];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) wf[w] = *reinterpret_cast<const bf16x8*>(lds + wq + w * (16 * C::ROW_BYTES));
+    bf16x8 af = *reinterpret_cast<const bf16x8*>(abase);
 #pragma unroll
     for (int s = 0; s < C::KSTEPS; ++s) {
-      bf16x8 wf[4];
-#pragma unroll
-      for (int w = 0; w < 4; ++w)
-        wf[w] = *reinterpret_cast<const bf16x8*>(lds + (wq ^ (uint32_t)(64 * s)) + w * (16 * C::ROW_BYTES));
-      // The fragment of masked-row tile a + 1 is requested before the four MFMAs of tile a.  Left to itself the
-      // compiler requests each fragment right before its use and waits for it on the spot (measured: 6.65 ms at
-      // the batched configuration against 5.93 ms with the request pinned ahead; two tiles ahead: 5.99 ms).
-      bf16x8 af = *reinterpret_cast<const bf16x8*>(abase + (s * 16) * 1024);
 #pragma unroll
       for (int a = 0; a < 8; ++a) {
+        const bool more = a < 7 || s + 1 < C::KSTEPS;  // another masked-row fragment in this slab
         bf16x8 af_next = af;
-        if (a < 7) af_next = *reinterpret_cast<const bf16x8*>(abase + (s * 16 + a + 1) * 1024);
+        if (more) af_next = *reinterpret_cast<const bf16x8*>(abase + (s * 16 + a + 1) * 1024);  // (s, 8) = (s + 1, 0)
         __builtin_amdgcn_sched_barrier(0);  // keeps the request above ahead of the MFMAs below
 #pragma unroll
-        for (int w = 0; w < 4; ++w) acc[a][w] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[w], af, acc[a][w], 0, 0, 0);
+        for (int w = 0; w < 4; ++w) {
+          acc[a][w] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[w], af, acc[a][w], 0, 0, 0);
+          if (a == 7 && s + 1 < C::KSTEPS) {
+            __builtin_amdgcn_sched_barrier(0);
+            wf[w] = *reinterpret_cast<const bf16x8*>(lds + (wq ^ (uint32_t)(64 * (s + 1))) + w * (16 * C::ROW_BYTES));
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
         af = af_next;
       }
     }
