@@ -300,7 +300,7 @@ __global__ __launch_bounds__(THREADS, 3) void lmhead_mfma_big_kernel(const __bf1
       for (int a = 0; a < 8; ++a) {
         const bool more = a < 7 || s + 1 < C::KSTEPS;  // another masked-row fragment in this slab
         bf16x8 af_next = af;
-        if (more) af_next = *reinterpret_cast<const bf16x8*>(abase + (s * 16 + a + 1) * 1024);  // (s, 8) = (s + 1, 0)
+        if (more) af_next = *reinterpret_cast<const bf16x8*>(abase + (a < 7 ? s * 16 + a + 1 : (s + 1) * 16) * 1024);
         __builtin_amdgcn_sched_barrier(0);  // keeps the request above ahead of the MFMAs below
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
