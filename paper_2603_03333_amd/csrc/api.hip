@@ -257,7 +257,7 @@ dm_status run_contraction(dm_ctx* ctx, const dm_params* p, const dm::RowGeom& g,
     reset.zero64 = ctx->nuc.hist;
     reset.n64 = nucleus_rows * 512;
   }
-  const int row_layout = !mfma ? dm::kRowsPlain : (g.M <= 128 ? dm::kRowsFrag32 : dm::kRowsFrag16);
+  const int row_layout = mfma ? dm::kRowsFrag16 : dm::kRowsPlain;
   hipError_t e = dm::launch_mask_rows(h, ctx->a_ws, ctx->keys, p->seeds, g, bf16, row_layout,
                                       want_seeds ? ctx->seeds_dev : nullptr, reset, s);
   if (e != hipSuccess) return fail_hip(ctx, "mask_rows launch", e);

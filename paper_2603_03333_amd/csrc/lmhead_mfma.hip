@@ -2,13 +2,15 @@
 //
 // The contraction is C[v, m] = sum_k W[v, k] * a[m, k] with W rows as the MFMA "A" operand
 // (index i = vocabulary row) and the masked hidden rows as the "B" operand (index j = masked
-// row).  In the 32x32 accumulator layout a lane then owns ONE masked row (j = lane % 32) and
-// 16 vocabulary rows per tile, so the running argmax over the vocabulary is a per-lane
-// compare with no cross-lane traffic; lanes meet only once per 256-row vocabulary tile.
+// row).  In the accumulator layout of v_mfma_f32_16x16x32_bf16 a lane then owns ONE masked row
+// (j = lane % 16) and 4 vocabulary rows per 16 x 16 tile, so the running argmax over the vocabulary
+// is a per-lane compare with no cross-lane traffic; lanes meet only once per 256-row vocabulary
+// tile.  (The 32x32x16 instruction, which this kernel used first, does the same flops with the
+// same fragment traffic at more power: 166.8 -> 160.9 us at 128 rows on one box.)
 //
 // Workgroup: 512 threads = 8 wavefronts, specialised by role (two per SIMD):
 //   * wavefronts 0-3, consumers: wavefront w owns vocabulary rows [64w, 64w+64) of the tile
-//     (two 32-row MFMA tiles) against all 32*MT <= 128 masked rows: 2*MT accumulator tiles.
+//     (four 16-row MFMA tiles) against all 32*MT <= 128 masked rows: 4 x 2*MT accumulator tiles.
 //     They only read LDS and issue MFMAs.
 //   * wavefronts 4-7, producers: they only issue the global -> LDS copies.  Issuing a copy
 //     blocks the wavefront while the CU's memory queue is full, which at HBM speed is most
@@ -20,8 +22,8 @@
 // VGPR staging).
 //   * W: one DMA instruction moves 8 rows x 128 B; eight consecutive lanes read one full
 //     line of a row (coalesced), and the 16-byte piece q of row r is placed at slot
-//     q ^ ((r >> 1) & 7) of the row so that the later ds_read_b128 of MFMA fragments (32
-//     different rows, same piece) spreads over all LDS banks (measured: 0 bank conflicts).
+//     q ^ ((r >> 1) & 7) of the row so that the later ds_read_b128 of MFMA fragments (16
+//     different rows per piece, 4 pieces) spreads over all LDS banks (measured: 0 bank conflicts).
 //   * masked rows: the mask kernel has already laid them out in fragment order, so the copy
 //     and the fragment reads are both linear.
 // A producer waits for its own DMA of slab q with s_waitcnt vmcnt(n); one s_barrier per slab
@@ -66,13 +68,13 @@ __host__ __device__ constexpr int lds_bytes(int MT) { return NS * slab_bytes(MT)
 //         layout [position][vocabulary row][path] (store.lt, see LogitStore).
 // SAMPLE (MODE 0 only): the per-row arg max runs over zscale * logit + Gumbel noise, i.e. the path token
 //         is drawn from Softmax(logit / temperature) instead of being the arg max.
-// acc[B / 8][(B / 4) & 1][4 * (B & 3) + e] += g[e]: noise block B of a tile (its 4 consecutive vocabulary
-// rows of masked-row tile B / 8) goes to fixed registers, so the block number has to be a constant.
+// acc[B / 4][B % 4][e] += g[e]: noise block B of a tile (the lane's 4 consecutive vocabulary rows of vocabulary
+// tile B % 4, masked-row tile B / 4) goes to fixed registers, so the block number has to be a constant.
 template <int MT, int B>
-__device__ __forceinline__ void add_noise_block(f32x16 (&acc)[MT][2], const float (&g)[4]) {
-  if constexpr (B / 8 < MT) {
+__device__ __forceinline__ void add_noise_block(f32x4 (&acc)[2 * MT][4], const float (&g)[4]) {
+  if constexpr (B / 4 < 2 * MT) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) acc[B / 8][(B / 4) & 1][4 * (B & 3) + e] += g[e];
+    for (int e = 0; e < 4; ++e) acc[B / 4][B & 3][e] += g[e];
   }
 }
 
@@ -86,7 +88,7 @@ template <int MT, int MODE, bool SAMPLE>
 __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* __restrict__ W,
                                                                  const __bf16* __restrict__ A_sw,
                                                                  unsigned long long* __restrict__ keys, int d,
-                                                                 int64_t M, int mt_total, int v_lo, int v_hi,
+                                                                 int64_t M, int mt_total /* tiles of 16 rows */, int v_lo, int v_hi,
                                                                  int rows_per_wg, float* __restrict__ logits,
                                                                  int dv0, int dv1, float scale, LogitStore store,
                                                                  VoteFuse fuse, SampleCfg samp) {
@@ -145,12 +147,12 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
           __builtin_amdgcn_global_load_lds(DM_GLOBAL_PTR(src), DM_LDS_PTR(stage + p * 8192 + rb * 1024), 16, 0, 0);
         }
       }
-      const char* asrc = Ab + ((int64_t)(c * 4) * mt_total + mblk * MT) * 1024;
+      const char* asrc = Ab + ((int64_t)(c * 2) * mt_total + mblk * (2 * MT)) * 1024;
 #pragma unroll
       for (int x = 0; x < MT; ++x) {
-        const int f = p + 4 * x;  // fragment index inside the slab: f = s * MT + mt
-        const int s = f / MT;
-        const int mt = f - s * MT;
+        const int f = p + 4 * x;  // fragment index inside the slab: f = s * 2 MT + mt (k-step of 32, tile of 16 rows)
+        const int s = f / (2 * MT);
+        const int mt = f - s * (2 * MT);
         dma_copy16(asrc + ((int64_t)s * mt_total + mt) * 1024, aoff, stage + W_SLAB_BYTES + f * 1024);
       }
     };
@@ -170,65 +172,82 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
     }
   } else {
     // -------------------------------------------------------------------- consumer
-    const int i32 = lane & 31;  // row inside a 32-row MFMA tile
-    const int hb = lane >> 5;   // which 8 of the 16 k of an MFMA step
-    const int swz = (i32 >> 1) & 7;
+    const int i16 = lane & 15;  // row inside a 16-row MFMA tile (vocabulary row of W, masked row of the B operand)
+    const int kq = lane >> 4;   // which 8 of the 32 k of an MFMA step; in the accumulators: which 4 of a tile's 16 vocabulary rows
+    const int swz = (i16 >> 1) & 7;
+    constexpr int NA = 2 * MT;  // masked-row tiles of 16
 
-    f32x16 acc[MT][2];
+    // acc[a][w][r]: masked row 16 a + i16 of the row block, vocabulary row 16 w + 4 kq + r of the wavefront's 64
+    f32x4 acc[NA][4];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int a = 0; a < NA; ++a)
 #pragma unroll
-      for (int vt = 0; vt < 2; ++vt)
+      for (int w = 0; w < 4; ++w)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[mt][vt][r] = 0.f;
+        for (int r = 0; r < 4; ++r) acc[a][w][r] = 0.f;
 
     // MODE 2: where this lane's masked rows live in the logit store (row m = path m % K of position
     // m / K), as a 32-bit byte offset from the first position of the workgroup's row block, so that a
-    // store needs one address register (uniform base + lane offset).  The lane's 4 * hb vocabulary-row
+    // store needs one address register (uniform base + lane offset).  The lane's 4 * kq vocabulary-row
     // offset is folded in.
-    uint32_t lt_off[MT];
-    bool lt_ok[MT];
+    uint32_t lt_off[NA];
+    bool lt_ok[NA];
     char* lt_base = nullptr;
     if (MODE == 2) {
       const int64_t pos0 = ((int64_t)mblk * MT * 32) / store.K;
       lt_base = reinterpret_cast<char*>(store.lt + pos0 * store.V * (int64_t)store.K4);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int64_t m = (int64_t)(mblk * MT + mt) * 32 + i32;
+      for (int a = 0; a < NA; ++a) {
+        const int64_t m = (int64_t)mblk * (MT * 32) + a * 16 + i16;
         const int64_t pos = m / store.K;
-        lt_ok[mt] = m < M;
-        lt_off[mt] = (uint32_t)(((pos - pos0) * store.V * store.K4 + (m - pos * store.K) + 4 * hb * store.K4) * 4);
+        lt_ok[a] = m < M;
+        lt_off[a] = (uint32_t)(((pos - pos0) * store.V * store.K4 + (m - pos * store.K) + 4 * kq * store.K4) * 4);
       }
     }
 
-    RowRng rng[MT];
     constexpr int NBL = noise_blocks_in_loop(MT);  // SAMPLE: noise blocks 0 .. NBL-1 of a tile are added in the k loop
     static_assert(NBL <= 16, "the switch below has 16 cases");
+    static_assert(NBL == 0 || NBL == 4 * NA, "either all blocks of a tile in the k loop or none");
+    RowRng rng[NBL > 0 ? NA : 1];                  // the row streams, kept over the k loop only when it draws the noise
     int noise_b = 0;                               // next of them
     const float inv_zscale = SAMPLE ? 1.0f / samp.zscale : 0.f;
-    if (SAMPLE) {
+    if (SAMPLE && NBL > 0) {
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) rng[mt] = make_row_rng(samp, (int64_t)(mblk * MT + mt) * 32 + i32, M);
+      for (int a = 0; a < NA; ++a) rng[a] = make_row_rng(samp, (int64_t)mblk * (MT * 32) + a * 16 + i16, M);
     }
 
     for (int q = 0; q < total; ++q) {
       DM_BARRIER();
       const unsigned char* stage = lds + (q % NS) * SLAB;
-      const unsigned char* wbase = stage + wave * 8192 + i32 * 128;
+      const unsigned char* wbase = stage + wave * 8192 + i16 * 128;
       const unsigned char* abase = stage + W_SLAB_BYTES + lane * 16;
+      // Fragments are requested ahead of their use by hand: that of masked-row tile a + 1 before the four MFMAs
+      // of tile a, and the W fragments of the slab's second k-step one by one behind the last MFMA that reads the
+      // register they go to (left to itself the compiler requests each fragment right before its use and waits
+      // for it on the spot).
+      bf16x8 wf[4];
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        bf16x8 wf[2], af[MT];
+      for (int w = 0; w < 4; ++w) wf[w] = *reinterpret_cast<const bf16x8*>(wbase + w * 2048 + 16 * (kq ^ swz));
+      bf16x8 af = *reinterpret_cast<const bf16x8*>(abase);
 #pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
-          wf[vt] = *reinterpret_cast<const bf16x8*>(wbase + vt * 4096 + 16 * ((2 * s + hb) ^ swz));
+      for (int s = 0; s < 2; ++s) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) af[mt] = *reinterpret_cast<const bf16x8*>(abase + (s * MT + mt) * 1024);
+        for (int a = 0; a < NA; ++a) {
+          const bool more = a + 1 < NA || s == 0;  // another masked-row fragment in this slab
+          bf16x8 af_next = af;
+          if (more) af_next = *reinterpret_cast<const bf16x8*>(abase + (a + 1 < NA ? s * NA + a + 1 : (s + 1) * NA) * 1024);
+          __builtin_amdgcn_sched_barrier(0);  // keeps the request above ahead of the MFMAs below
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-          for (int vt = 0; vt < 2; ++vt)
-            acc[mt][vt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[vt], af[mt], acc[mt][vt], 0, 0, 0);
+          for (int w = 0; w < 4; ++w) {
+            acc[a][w] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[w], af, acc[a][w], 0, 0, 0);
+            if (a == NA - 1 && s == 0) {
+              __builtin_amdgcn_sched_barrier(0);
+              wf[w] = *reinterpret_cast<const bf16x8*>(wbase + w * 2048 + 16 * ((4 + kq) ^ swz));
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+          af = af_next;
+        }
       }
       asm volatile("" ::: "memory");
 
@@ -239,16 +258,16 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
         // Philox call), evenly over the slabs of the tile, while the wavefront would wait for data anyway
         const int sl = q - n * nchunks;
         const int due = ((sl + 1) * NBL) / nchunks;  // blocks added by the end of this slab; all NBL at the last
-        const int vb = row_begin + n * BN + 64 * wave + 4 * hb;
+        const int vb = row_begin + n * BN + 64 * wave + 4 * kq;
         for (; noise_b < due; ++noise_b) {
-          const int mt = noise_b >> 3;
+          const int a = noise_b >> 2;
           RowRng r = rng[0];
 #pragma unroll
-          for (int k = 1; k < MT; ++k)
-            if (mt == k) r = rng[k];
+          for (int k = 1; k < NA; ++k)
+            if (a == k) r = rng[k];
           float g[4] = {0.f, 0.f, 0.f, 0.f};
           if (r.on) {
-            gumbel4(r, (uint32_t)(vb + 32 * ((noise_b >> 2) & 1) + 8 * (noise_b & 3)), step_now(samp.step, samp.step_dev), g);
+            gumbel4(r, (uint32_t)(vb + 16 * (noise_b & 3)), step_now(samp.step, samp.step_dev), g);
 #pragma unroll
             for (int e = 0; e < 4; ++e) g[e] *= inv_zscale;
           }
@@ -264,22 +283,22 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
       }
       if (q - n * nchunks != nchunks - 1) continue;
 
-      // ---- tile finished: accumulator (vt, r) of lane holds row v, column m ----
-      //   v = v0 + 64*wave + 32*vt + 8*(r/4) + 4*hb + (r%4),  m = 32*(MT*mblk + mt) + lane%32
+      // ---- tile finished: accumulator (a, w, r) of lane holds row v, column m ----
+      //   v = v0 + 64*wave + 16*w + 4*kq + r,  m = 32*MT*mblk + 16*a + lane%16
       const int v0 = row_begin + n * BN;
       if (DUMP) {
         const int nv = dv1 - dv0;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          const int64_t m = (int64_t)(mblk * MT + mt) * 32 + i32;
+        for (int a = 0; a < NA; ++a) {
+          const int64_t m = (int64_t)mblk * (MT * 32) + a * 16 + i16;
           const float sc = (store.clean_last && m % store.K == store.K - 1) ? 1.0f : scale;  // clean path: no 1/(1-p)
 #pragma unroll
-          for (int vt = 0; vt < 2; ++vt)
+          for (int w = 0; w < 4; ++w)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int v = v0 + 64 * wave + 32 * vt + 8 * (r >> 2) + 4 * hb + (r & 3);
-              if (m < M && v >= dv0 && v < dv1 && v < row_end) logits[m * nv + (v - dv0)] = sc * acc[mt][vt][r];
-              acc[mt][vt][r] = 0.f;
+            for (int r = 0; r < 4; ++r) {
+              const int v = v0 + 64 * wave + 16 * w + 4 * kq + r;
+              if (m < M && v >= dv0 && v < dv1 && v < row_end) logits[m * nv + (v - dv0)] = sc * acc[a][w][r];
+              acc[a][w][r] = 0.f;
             }
         }
         continue;
@@ -287,48 +306,55 @@ __global__ __launch_bounds__(THREADS, 2) void lmhead_mfma_kernel(const __bf16* _
 
       if (MODE == 2) {
 #pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
+        for (int w = 0; w < 4; ++w)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int vu = v0 + 64 * wave + 32 * vt + 8 * (r >> 2) + (r & 3);  // + 4 * hb per lane
+          for (int r = 0; r < 4; ++r) {
+            const int vu = v0 + 64 * wave + 16 * w + r;  // + 4 * kq per lane
             char* dst = lt_base + (int64_t)vu * store.K4 * 4;
-            const bool v_ok = vu + 4 * hb < row_end;
+            const bool v_ok = vu + 4 * kq < row_end;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-              if (lt_ok[mt] && v_ok) *reinterpret_cast<float*>(dst + lt_off[mt]) = scale * acc[mt][vt][r];
+            for (int a = 0; a < NA; ++a)
+              if (lt_ok[a] && v_ok) *reinterpret_cast<float*>(dst + lt_off[a]) = scale * acc[a][w][r];
           }
       }
 
       unsigned long long* red = reinterpret_cast<unsigned long long*>(lds + NS * SLAB);  // [4][MT*32]
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
+      for (int a = 0; a < NA; ++a) {
         float best = -INFINITY;
         uint32_t bv = 0xFFFFFFFFu;
-#pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
-#pragma unroll
-          for (int rq = 0; rq < 4; ++rq) {
-            float g[4] = {0.f, 0.f, 0.f, 0.f};
-            const bool noisy = SAMPLE && rng[mt].on;
-            // blocks below NBL got their noise in the k loop (as g / zscale, so the same expression below holds)
-            if (noisy && mt * 8 + vt * 4 + rq >= NBL)
-              gumbel4(rng[mt], (uint32_t)(v0 + 64 * wave + 32 * vt + 8 * rq + 4 * hb), step_now(samp.step, samp.step_dev), g);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {  // ascending v for this lane: strict > keeps the smallest index
-              const int r = 4 * rq + e;
-              const int v = v0 + 64 * wave + 32 * vt + 8 * rq + 4 * hb + e;
-              const float val = noisy ? fmaf(acc[mt][vt][r], samp.zscale, g[e]) : acc[mt][vt][r] + 0.0f;
-              if (v < row_end && (bv == 0xFFFFFFFFu || val > best)) {
-                best = val;
-                bv = (uint32_t)v;
-              }
-              acc[mt][vt][r] = 0.f;
-            }
+        bool noisy = false;
+        RowRng ra{0u, 0u, 0u, 0u, false};
+        if constexpr (SAMPLE) {
+          if constexpr (NBL > 0) {
+            noisy = rng[a].on;  // all blocks got their noise in the k loop (as g / zscale, so the expression below holds)
+          } else {
+            ra = make_row_rng(samp, (int64_t)mblk * (MT * 32) + a * 16 + i16, M);
+            noisy = ra.on;
           }
+        }
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float g[4] = {0.f, 0.f, 0.f, 0.f};
+          if (SAMPLE && NBL == 0 && noisy)
+            gumbel4(ra, (uint32_t)(v0 + 64 * wave + 16 * w + 4 * kq), step_now(samp.step, samp.step_dev), g);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {  // ascending v for this lane: strict > keeps the smallest index
+            const int v = v0 + 64 * wave + 16 * w + 4 * kq + e;
+            const float val = noisy ? fmaf(acc[a][w][e], samp.zscale, g[e]) : acc[a][w][e] + 0.0f;
+            if (v < row_end && (bv == 0xFFFFFFFFu || val > best)) {
+              best = val;
+              bv = (uint32_t)v;
+            }
+            acc[a][w][e] = 0.f;
+          }
+        }
         unsigned long long key = (bv == 0xFFFFFFFFu) ? 0ull : pack_key(best, bv);
-        const unsigned long long other = __shfl_xor(key, 32, 64);
+        unsigned long long other = __shfl_xor(key, 16, 64);
         key = other > key ? other : key;
-        if (hb == 0) red[wave * (MT * 32) + mt * 32 + i32] = key;
+        other = __shfl_xor(key, 32, 64);
+        key = other > key ? other : key;
+        if (kq == 0) red[wave * (MT * 32) + a * 16 + i16] = key;
       }
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): LDS writes above are done
@@ -398,7 +424,7 @@ hipError_t run(const void* W, const void* a_ws, unsigned long long* keys, const 
   const dim3 grid((unsigned)gx, (unsigned)mblocks), block(THREADS);
 #define DM_LAUNCH(MODE, SAMPLE)                                                                                 \
   launch_at(lmhead_mfma_kernel<MT, MODE, SAMPLE>, grid, block, (size_t)lds_bytes(MT), at,                        \
-            static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, mt_total, v_lo,    \
+            static_cast<const __bf16*>(W), static_cast<const __bf16*>(a_ws), keys, g.d, g.M, 2 * mt_total, v_lo, \
             v_hi, rows_per_wg, logits, v0, v1, scale, store, fuse, samp)
   if (dump)
     DM_LAUNCH(1, false);
