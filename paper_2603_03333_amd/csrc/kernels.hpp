@@ -33,8 +33,7 @@ __device__ __forceinline__ uint32_t step_now(uint32_t step, const uint32_t* step
 
 // Eq. (1)+(2) without the scale: masked rows a = keep ? h : 0 into the workspace, and the
 // per-row argmax keys reset to 0.  layout: plain [M_pad, d_pad], or the order of the B-fragments of the
-// MFMA kernel that will read them (32 rows x 16 k for the W-streaming kernel, 16 rows x 32 k for the
-// 256 x 256 kernel).  is_bf16 selects the element type of h and the workspace.
+// MFMA kernels that will read them (16 rows x 32 k).  is_bf16 selects the element type of h and the workspace.
 // seeds_dev (optional): DEVICE [B], receives the seeds (for the sampling epilogues of the same call).
 // Per-call state of the later kernels of the same call is put back to zero here as well, so that a
 // call never depends on an earlier one having run to its end: the election counter of the fused
@@ -44,7 +43,7 @@ struct CallReset {
   unsigned long long* zero64 = nullptr;   // n64 words, or null
   int64_t n64 = 0;
 };
-constexpr int kRowsPlain = 0, kRowsFrag32 = 1, kRowsFrag16 = 2;
+constexpr int kRowsPlain = 0, kRowsFrag16 = 1;
 hipError_t launch_mask_rows(const void* h, void* a_ws, unsigned long long* keys, const uint64_t* seeds_host,
                             const RowGeom& g, bool is_bf16, int layout, uint64_t* seeds_dev,
                             const CallReset& reset, hipStream_t stream);
@@ -97,7 +96,7 @@ hipError_t launch_lmhead_generic(const void* W, const void* a_ws, unsigned long 
                                  int V, bool is_bf16, float* logits, int v0, int v1, float scale,
                                  const LogitStore& store, const SampleCfg& samp, const LaunchSite& at);
 
-// Eq. (3) + per-row argmax on bf16 MFMA; a_ws swizzled layout; d % 64 == 0.
+// Eq. (3) + per-row argmax on bf16 MFMA; a_ws in fragment order (kRowsFrag16); d % 64 == 0.
 struct VoteFuse;
 // fuse (optional): also run the acceptance step in the same launch (token-level rules, no dump, no store).
 // *fused is set when that was done.

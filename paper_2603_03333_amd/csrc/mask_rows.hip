@@ -68,12 +68,7 @@ __global__ __launch_bounds__(256) void mask_rows_kernel(const T* __restrict__ h,
   }
 
   int64_t dst;
-  if (LAYOUT == kRowsFrag32) {
-    // B-operand fragments of v_mfma_f32_32x32x16_bf16: fragment (k-step ks, row tile mt) is
-    // 64 lanes x 8 elements; lane = (row % 32) + 32 * ((k % 16) / 8), element = k % 8.
-    const int64_t mt_total = g.M_pad >> 5;
-    dst = ((((int64_t)(o >> 1) * mt_total + (r >> 5)) * 64) + (r & 31) + 32 * (o & 1)) * 8;
-  } else if (LAYOUT == kRowsFrag16) {
+  if (LAYOUT == kRowsFrag16) {
     // B-operand fragments of v_mfma_f32_16x16x32_bf16: fragment (k-step ks of 32, row tile mt of 16) is
     // 64 lanes x 8 elements; lane = (row % 16) + 16 * ((k % 32) / 8), element = k % 8.
     const int64_t mt_total = g.M_pad >> 4;
@@ -145,7 +140,6 @@ hipError_t launch_mask_rows(const void* h, void* a_ws, unsigned long long* keys,
   if (is_bf16) {
     switch (layout) {
       case kRowsPlain: return run_mask_rows<uint16_t, kRowsPlain>(h, a_ws, keys, seeds_host, g, seeds_dev, reset, stream);
-      case kRowsFrag32: return run_mask_rows<uint16_t, kRowsFrag32>(h, a_ws, keys, seeds_host, g, seeds_dev, reset, stream);
       case kRowsFrag16:
         if (g.d_pad % 32 != 0 || g.M_pad % 16 != 0) return hipErrorInvalidValue;
         return run_mask_rows<uint16_t, kRowsFrag16>(h, a_ws, keys, seeds_host, g, seeds_dev, reset, stream);
