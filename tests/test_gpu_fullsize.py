@@ -55,8 +55,8 @@ def _one_position_per_row_tile(wl, stride=1):
     return out
 
 
-def _run_config(name, sample):
-    wl = wk.CONFIGS[name]
+def _run_config(name, sample, wl=None):
+    wl = wl or wk.CONFIGS[name]
     print(f"[{name}] generating inputs", flush=True)
     W, h, seeds = wk.make_weight(wl), wk.make_hidden(wl), wk.make_seeds(wl)
     W64 = W.astype(np.float64)
@@ -125,6 +125,15 @@ def test_tree_one_position_per_row_tile():
 
 def test_batched_one_position_per_row_tile():
     _run_config("batched", sample=True)
+
+
+@pytest.mark.parametrize("B", [2, 4])
+def test_head8b_shape_between_the_two_kernels(B):
+    """256 and 512 masked rows at the head8b shape: the points of the rows sweep where W still streams from memory
+    but the 256 x 256 kernel runs (one or two row tiles, two or four rounds of vocabulary tiles per workgroup).
+    Every position against the oracle."""
+    wl = wk.CONFIGS["head8b"].with_(B=B, data_seed=1010 + B)
+    _run_config(f"head8b-shape B={B}", sample=False, wl=wl)
 
 
 # ------------------------------------------------------------------ distribution-level rule (Eq. 5, 6, Alg. 1)
