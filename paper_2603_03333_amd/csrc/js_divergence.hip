@@ -38,6 +38,15 @@ constexpr float kLn2 = 0.693147180559945309f;
 __device__ __forceinline__ float exp2_hw(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float log2_hw(float x) { return __builtin_amdgcn_logf(x); }
 
+// log2 of a sum kept in double, without the double-precision library routine (a few hundred instructions that every
+// workgroup of pass 2 would run before its first load): the exponent is exact, and the hardware logarithm of the
+// mantissa in [0.5, 1) is good to 6e-8 absolute, far below the rounding of the normaliser it goes into.
+__device__ __forceinline__ double log2_of_sum(double s) {
+  int e;
+  const float f = frexpf((float)s, &e);
+  return (double)e + (double)log2_hw(f);
+}
+
 __device__ __forceinline__ float wave_sum(float x) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
@@ -303,7 +312,7 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
       for (int cc = sub; cc < g.NC; cc += 8) s += (double)pa[(int64_t)slot * g.NC + cc];
 #pragma unroll
       for (int off = 4; off >= 1; off >>= 1) s += __shfl_xor(s, off, 8);
-      if (sub == 0) Zs[slot] = (float)((double)(scale * key_logit(keys[(int64_t)pos * K + slot]) * kLog2e) + log2(s));
+      if (sub == 0) Zs[slot] = (float)((double)(scale * key_logit(keys[(int64_t)pos * K + slot]) * kLog2e) + log2_of_sum(s));
     } else {  // mean logits: chunk records are (max, sum of 2^(x - max))
       float m = -INFINITY;
       for (int cc = sub; cc < g.NC; cc += 8) m = fmaxf(m, pa[(int64_t)g.K4 * g.NC + cc]);
@@ -315,7 +324,7 @@ __global__ __launch_bounds__(JT) void js_terms_kernel(const float* __restrict__ 
         s += (double)(pa[(int64_t)(g.K4 + 1) * g.NC + cc] * exp2_hw(pa[(int64_t)g.K4 * g.NC + cc] - m));
 #pragma unroll
       for (int off = 4; off >= 1; off >>= 1) s += __shfl_xor(s, off, 8);
-      if (sub == 0) Zs[KP] = (float)((double)m + log2(s));
+      if (sub == 0) Zs[KP] = (float)((double)m + log2_of_sum(s));
     }
   }
   __syncthreads();
